@@ -1,0 +1,104 @@
+"""Decoder-only transformer forward pass, full recompute, no KV cache, fp64.
+
+Oracle code: test infrastructure, independent of the HIP library.
+
+The paper treats the models as conditional distributions given by
+softmax(logits / temperature) (Sec. 2) and says nothing about the network.
+The architecture is the workload's: pre-norm decoder with RMSNorm, rotary
+position embedding, causal multi-head / grouped-query attention, SwiGLU
+feed-forward, untied embedding and LM head, no biases.  Conventions fixed here
+(parity unpinned by the paper): RMSNorm eps 1e-5 inside the square root; RoPE
+base 10000 rotating the interleaved pairs (2j, 2j+1) of each head by
+pos * base^(-2j/head_dim); attention scale 1/sqrt(head_dim).
+
+Weights are [out_features, in_features] matrices: y = x @ W.T.
+`storage` names the dtype in which the GPU path stores GEMM operands, K/V and
+rotated queries ("f32" = no rounding here, "bf16" = round-to-nearest-even to
+bfloat16 at exactly those storage points).  All arithmetic is fp64.
+"""
+import numpy as np
+
+
+def round_bf16(x):
+    """Round fp64 values to the nearest bfloat16 (8 significant bits), ties to even."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)
+    return np.ldexp(np.round(m * 256.0) / 256.0, e)
+
+
+def _store(x, storage):
+    if storage == "bf16":
+        return round_bf16(x)
+    return x
+
+
+def rmsnorm(x, gain, eps):
+    x = np.asarray(x, dtype=np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gain, dtype=np.float64)
+
+
+def rope(x, positions, base):
+    """x [n, heads, head_dim]; rotates pairs (2j, 2j+1) by positions * base^(-2j/head_dim)."""
+    n, h, hd = x.shape
+    j = np.arange(hd // 2, dtype=np.float64)
+    inv_freq = base ** (-2.0 * j / hd)
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * inv_freq[None, :]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    xe, xo = x[..., 0::2], x[..., 1::2]
+    out = np.empty_like(x)
+    out[..., 0::2] = xe * c - xo * s
+    out[..., 1::2] = xe * s + xo * c
+    return out
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def forward(cfg, W, tokens, storage="f32", return_hidden=False):
+    """Logits [n, V] (fp64) for every position of one token sequence.
+
+    cfg: dict(n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab,
+              rope_base=10000.0, norm_eps=1e-5)
+    W:   mapping name -> array: 'embed', 'final_norm', 'lm_head' and per layer l
+         'l{l}.attn_norm', 'l{l}.wq', 'l{l}.wk', 'l{l}.wv', 'l{l}.wo',
+         'l{l}.ffn_norm', 'l{l}.w_gate', 'l{l}.w_up', 'l{l}.w_down'.
+    """
+    tokens = np.asarray(tokens, dtype=np.int64)
+    n = tokens.shape[0]
+    H, KVH, hd = cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    base = cfg.get("rope_base", 10000.0)
+    eps = cfg.get("norm_eps", 1e-5)
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    pos = np.arange(n)
+    x = f64(W["embed"])[tokens]                                     # residual stream
+    causal = np.tril(np.ones((n, n), dtype=bool))
+    for l in range(cfg["n_layers"]):
+        g = lambda name: f64(W[f"l{l}.{name}"])
+        h = _store(rmsnorm(x, g("attn_norm"), eps), storage)
+        q = (h @ g("wq").T).reshape(n, H, hd)
+        k = (h @ g("wk").T).reshape(n, KVH, hd)
+        v = (h @ g("wv").T).reshape(n, KVH, hd)
+        q = _store(rope(q, pos, base), storage)
+        k = _store(rope(k, pos, base), storage)
+        v = _store(v, storage)
+        att = np.empty((n, H, hd))
+        for head in range(H):
+            kvh = head // (H // KVH)
+            s = (q[:, head, :] @ k[:, kvh, :].T) / np.sqrt(hd)
+            s = np.where(causal, s, -np.inf)
+            s = s - s.max(axis=-1, keepdims=True)
+            p = np.exp(s)
+            p = p / p.sum(axis=-1, keepdims=True)
+            att[:, head, :] = p @ v[:, kvh, :]
+        att = _store(att.reshape(n, H * hd), storage)
+        x = x + att @ g("wo").T
+        h = _store(rmsnorm(x, g("ffn_norm"), eps), storage)
+        a = _store(silu(h @ g("w_gate").T) * (h @ g("w_up").T), storage)
+        x = x + a @ g("w_down").T
+    h = _store(rmsnorm(x, f64(W["final_norm"]), eps), storage)
+    logits = h @ f64(W["lm_head"]).T
+    if return_hidden:
+        return logits, x
+    return logits
