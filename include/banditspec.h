@@ -1,0 +1,217 @@
+/*
+ * banditspec.h - C ABI of the MI355X (gfx950) hot path of BanditSpec (arXiv 2505.15141).
+ *
+ * One speculative-decoding round = the subroutine of Alg. 2 instantiated with vanilla speculative
+ * decoding (App. A): gamma draft draws, one target pass over gamma+1 query positions, accept/reject
+ * with residual / bonus sampling.  The arm-selection rules UCBSpec (Alg. 4) and EXP3Spec (Alg. 5)
+ * run on the host between rounds (Alg. 3).
+ *
+ * Conventions
+ *  - Every function returns an int status: BS_OK (0) or a negative bs_status.  bs_last_error_string()
+ *    gives the detail for the calling thread.  Nothing throws, nothing aborts.
+ *  - Pointers named dev_* are DEVICE pointers, host_* / plain structs are HOST memory.  All device
+ *    memory (weights, KV caches, tokens, logits, workspaces) is owned by the caller and must stay
+ *    alive until the stream work of the call has finished.  The library allocates no device memory.
+ *    It owns only the small host handles it creates (create/destroy pairs).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only enqueue work;
+ *    they never synchronise unless stated.
+ *  - Matrices are row-major [out_features, in_features] (y = x W^T), in the model dtype.
+ *    Norm gains are float32.  Logits are always float32 on the model path.
+ *  - Shapes and arguments are validated on the host before anything is launched.
+ */
+#ifndef BANDITSPEC_H
+#define BANDITSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BS_OK = 0,
+    BS_EINVAL = -1,     /* null pointer, value out of range */
+    BS_ESHAPE = -2,     /* sizes that do not fit together or exceed a kernel limit */
+    BS_EDTYPE = -3,     /* unknown or unsupported dtype */
+    BS_EWORKSPACE = -4, /* workspace too small or misaligned */
+    BS_ESTATE = -5,     /* call order / handle state */
+    BS_EHIP = -6        /* a HIP runtime call failed */
+} bs_status;
+
+typedef enum { BS_F32 = 0, BS_BF16 = 1 } bs_dtype;
+
+const char* bs_last_error_string(void);
+int bs_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Philox4x32-10 word used by every random decision (host function, for parity checks).
+ * Counter = (b, t, slot, purpose), key = seed.  purpose: 0 draft draw, 1 acceptance test,
+ * 2 residual/bonus draw, 3 EXP3Spec arm draw.  Acceptance uniforms are ((w>>8)+1)*2^-24 in (0,1],
+ * draw uniforms (w>>8)*2^-24 in [0,1).
+ * ---------------------------------------------------------------------------------------------- */
+uint32_t bs_philox_word(uint64_t seed, uint32_t b, uint32_t t, uint32_t slot, uint32_t purpose);
+
+/* ------------------------------------------------------------------------------------------------
+ * Accept/reject + residual/bonus sampling (App. A, vanilla speculative decoding, the loop over draft
+ * positions and the bonus draw).  For each sequence b:
+ *   tau = number of leading draft positions i with  u_i <= min{1, p_i(x~_i) / q_i(x~_i)}  (tested as
+ *         u_i * q_i(x~_i) <= p_i(x~_i)),  p_i = softmax(target_logits[b,i]/T), q_i likewise;
+ *   next_token ~ Norm([p_{tau+1} - q_{tau+1}]_+) if tau < gamma, else ~ p_{gamma+1};
+ *   draws are inverse-CDF in increasing token id with one uniform in [0,1).
+ *
+ *  dev_target_logits [B, gamma+1, V], dev_draft_logits [B, gamma, V]  contiguous, `dtype` elements
+ *  dev_draft_tokens  [B, gamma] int32, each in [0, V)
+ *  dev_uniforms      [B, gamma+1] float32 (columns 0..gamma-1 acceptance, column gamma final draw),
+ *                    or NULL: then Philox(seed; b, round, i, purpose) is generated in the kernel
+ *  dev_accept_len    [B] int32 out (tau);  dev_next_token [B] int32 out
+ *  dev_margins       [B, gamma] float32 out or NULL: min(1,p/q) - u for every position (all tested)
+ *  dev_workspace     bs_spec_sample_workspace_bytes(B, gamma) bytes, 16-byte aligned, contents ignored
+ * gamma >= 0, B >= 0 (B == 0 is a no-op), 1 <= V <= 2^20, temperature > 0.
+ * ---------------------------------------------------------------------------------------------- */
+size_t bs_spec_sample_workspace_bytes(int B, int gamma);
+int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
+                   const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype,
+                   float temperature, const float* dev_uniforms, uint64_t seed, uint32_t round,
+                   int32_t* dev_accept_len, int32_t* dev_next_token, float* dev_margins,
+                   void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Arm selection (host only).  UCBSpec: Alg. 4 / its full version - arms 0..K-1 in order for the
+ * first K rounds, then argmax of mean + (L/2) sqrt((1+n)/n^2 (1 + 2 ln(K t^2 sqrt(1+n)/delta))),
+ * ties to the lowest index.  EXP3Spec: full version of Alg. 5 - eta_t = sqrt(ln K/(tK)),
+ * p_t ~ exp(-eta_t * cumulative estimated loss), arm drawn by inverse CDF with the Philox uniform
+ * (seed; 0, t-1, 0, 3); after the round Zhat = (L+1-y)/(L p_t[arm]).
+ * y is the accepted length including the bonus token (Sec. 3), 1 <= y <= L+1 (a batch mean is fine).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct bs_bandit bs_bandit;
+typedef enum { BS_UCBSPEC = 0, BS_EXP3SPEC = 1 } bs_bandit_kind;
+int bs_bandit_create(int kind, int K, int L, double delta, uint64_t seed, bs_bandit** out);
+int bs_bandit_destroy(bs_bandit* b);
+int bs_bandit_select(bs_bandit* b, int* arm_out);
+int bs_bandit_update(bs_bandit* b, int arm, double y); /* arm must be the last selected arm */
+/* UCBSpec: the K indices mean+radius (+inf during round-robin); EXP3Spec: p_t for the next round. */
+int bs_bandit_probs(bs_bandit* b, double* host_out_K);
+/* pulls n_i, and per arm sum of y (UCBSpec) or cumulative estimated loss (EXP3Spec); rounds so far */
+int bs_bandit_stats(bs_bandit* b, double* host_n_K, double* host_sum_K, int64_t* rounds_out);
+
+/* ------------------------------------------------------------------------------------------------
+ * Models (Sec. 2: a model is the conditional distribution softmax(logits/T); the network itself is
+ * the workload's: pre-norm decoder, RMSNorm, RoPE on interleaved pairs, causal MHA/GQA, SwiGLU).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab;
+    int32_t dtype;          /* bs_dtype of matrices, embeddings, KV cache and stored activations */
+    float rope_base;        /* e.g. 10000 */
+    float norm_eps;         /* e.g. 1e-5 */
+} bs_model_cfg;
+
+typedef struct {
+    const float* attn_norm; /* [d_model] */
+    const void* wq;         /* [n_heads*head_dim, d_model] */
+    const void* wk;         /* [n_kv_heads*head_dim, d_model] */
+    const void* wv;         /* [n_kv_heads*head_dim, d_model] */
+    const void* wo;         /* [d_model, n_heads*head_dim] */
+    const float* ffn_norm;  /* [d_model] */
+    const void* w_gate;     /* [d_ff, d_model] */
+    const void* w_up;       /* [d_ff, d_model] */
+    const void* w_down;     /* [d_model, d_ff] */
+} bs_layer_weights;
+
+typedef struct {
+    const void* embed;              /* [vocab, d_model] */
+    const float* final_norm;        /* [d_model] */
+    const void* lm_head;            /* [vocab, d_model] */
+    const bs_layer_weights* layers; /* host array of n_layers entries (copied by bs_model_create) */
+} bs_model_weights;
+
+typedef struct bs_model bs_model;
+int bs_model_create(const bs_model_cfg* cfg, const bs_model_weights* dev_weights, bs_model** out);
+int bs_model_destroy(bs_model* m);
+
+/* KV cache bound to caller memory.  Layout [layer][K|V][B][kv_head][max_len][head_dim], model dtype. */
+typedef struct bs_kv bs_kv;
+size_t bs_kv_bytes(const bs_model_cfg* cfg, int B, int max_len);
+int bs_kv_bind(const bs_model* m, int B, int max_len, void* dev_buf, size_t bytes, bs_kv** out);
+int bs_kv_destroy(bs_kv* kv);
+
+/* Workspace needed by bs_verify_forward / bs_prefill for at most max_rows = B*q_len query rows. */
+size_t bs_forward_workspace_bytes(const bs_model_cfg* cfg, int B, int max_q_len, int max_len);
+
+/* ------------------------------------------------------------------------------------------------
+ * Target verification forward (App. A, "calculate P(x~_i | pt, x~_{1:i-1}) for all i in parallel"):
+ * runs the model over q_len query tokens per sequence against its KV cache.
+ *   query j of sequence b sits at position pos = kv_len[b] + j, attends to cache positions
+ *   0..pos (causal), and its K/V are written to the cache at pos (the cache length itself is the
+ *   caller's dev_kv_len; nothing else records it).
+ *  dev_q_tokens [B, q_len] int32;  dev_kv_len [B] int32 (tokens already in the cache)
+ *  logit_rows   how many trailing query rows per sequence get logits (q_len for verification,
+ *               1 for a draft step, 0 for cache fill only)
+ *  dev_logits   [B, logit_rows, vocab] float32 out (may be NULL if logit_rows == 0)
+ * Sequences with kv_len[b] + q_len > max_len are skipped entirely and bit 0 of the device status
+ * word (first int32 of the workspace) is set; other sequences are unaffected.
+ * The same call serves the draft model's steps (q_len = 1 or 2, logit_rows = 1).
+ * ---------------------------------------------------------------------------------------------- */
+int bs_verify_forward(const bs_model* m, const bs_kv* kv, const int32_t* dev_q_tokens,
+                      const int32_t* dev_kv_len, int q_len, int logit_rows, float* dev_logits,
+                      void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/* Prompt processing: fills the cache for positions 0..n-1 of every sequence (same n for all), in
+ * chunks through the same kernels.  dev_tokens [B, token_stride] int32, n <= token_stride.
+ * dev_last_logits [B, vocab] float32 (logits after the last prompt token) or NULL. */
+int bs_prefill(const bs_model* m, const bs_kv* kv, const int32_t* dev_tokens, int token_stride, int n,
+               float* dev_last_logits, void* dev_workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * One speculative round for a batch (Alg. 2 with vanilla speculative decoding, App. A; the device part
+ * of one iteration of Alg. 3).  An arm is a (draft model, gamma) pair; L = max gamma.
+ * Device state owned by the caller and advanced by the round:
+ *   dev_tokens [B, max_len] int32   the growing prompts (Alg. 3, pt_t)
+ *   dev_total_len [B] int32         tokens per sequence; invariant: the target cache holds total_len-1
+ *   dev_goal_len [B] int32          generation stops here (tokens beyond it are dropped; the reported
+ *                                   accepted length is not truncated)
+ * Random numbers: Philox(seed; b, t, slot, purpose) with t the device round counter (bs_round_reset).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    const bs_model* target;
+    const bs_kv* target_kv;
+    int32_t n_drafts;
+    const bs_model* const* drafts;     /* host array [n_drafts] */
+    const bs_kv* const* draft_kvs;     /* host array [n_drafts], each bound with the same B, max_len */
+    int32_t n_arms;
+    const int32_t* arm_draft;          /* host array [n_arms]: index into drafts */
+    const int32_t* arm_gamma;          /* host array [n_arms]: speculation length, >= 1 */
+    int32_t B, max_len;
+    int32_t* dev_tokens;
+    int32_t* dev_total_len;
+    const int32_t* dev_goal_len;
+    float temperature;
+    uint64_t seed;
+    void* dev_workspace;               /* bs_round_workspace_bytes(...) bytes, 256-byte aligned */
+    size_t workspace_bytes;
+    int32_t use_graph;                 /* 1: capture each arm's round once into a HIP graph and replay it */
+} bs_round_cfg;
+
+typedef struct bs_round bs_round;
+size_t bs_round_workspace_bytes(const bs_model_cfg* target, const bs_model_cfg* const* drafts, int n_drafts,
+                                int B, int L, int max_len);
+int bs_round_create(const bs_round_cfg* cfg, bs_round** out);
+int bs_round_destroy(bs_round* r);
+/* Sets the device round counter t (enqueues a tiny kernel) and marks every draft cache as holding
+ * total_len-2 valid positions or more (true right after prefill of the same prompts). */
+int bs_round_reset(bs_round* r, uint32_t t0, void* stream);
+/* Enqueues draft proposal -> verification -> accept/reject -> commit for arm `arm`.
+ *  dev_emitted   [B, L+1] int32 out: accepted draft tokens then the residual/bonus token
+ *  dev_n_emitted [B] int32 out: y = tau + 1 (the reward of Sec. 3; 0 for sequences already at goal)
+ * The caller copies dev_n_emitted to the host and synchronises before bs_bandit_update. */
+int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emitted, void* stream);
+/* Views into the round workspace for parity checks (valid after the round's stream work is done):
+ * target logits [B, gamma+1, V] f32, draft logits [B, gamma, V] f32, draft tokens [B, gamma] int32,
+ * margins [B, gamma] f32 of the most recent round. */
+int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const float** dev_draft_logits,
+                         const int32_t** dev_draft_tokens, const float** dev_margins);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BANDITSPEC_H */

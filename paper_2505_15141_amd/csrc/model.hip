@@ -1,0 +1,496 @@
+// Host side of the model path: handles, workspace carving, the forward pass schedule (verification
+// pass of App. A and the draft steps), prompt prefill, and the round driver (Alg. 2 with vanilla
+// speculative decoding; one iteration of the loop of Alg. 3 on the device).
+#include <new>
+#include <vector>
+#include "common.h"
+#include "kernels.h"
+#include "sample.h"
+
+using namespace bs;
+
+struct bs_model {
+    bs_model_cfg cfg;
+    const void* embed;
+    const float* final_norm;
+    const void* lm_head;
+    std::vector<bs_layer_weights> layers;
+};
+
+struct bs_kv {
+    bs_model_cfg cfg;
+    int B, max_len;
+    char* buf;
+    size_t bytes;
+};
+
+static size_t esize(int dtype) { return dtype == BS_BF16 ? 2 : 4; }
+
+static int check_cfg(const bs_model_cfg* c, const char* who) {
+    BS_REQUIRE(c, BS_EINVAL, "%s: cfg is NULL", who);
+    BS_REQUIRE(c->dtype == BS_F32 || c->dtype == BS_BF16, BS_EDTYPE, "%s: dtype %d", who, c->dtype);
+    BS_REQUIRE(c->n_layers >= 1 && c->d_model >= 8 && c->n_heads >= 1 && c->n_kv_heads >= 1 && c->d_ff >= 8 && c->vocab >= 1,
+               BS_ESHAPE, "%s: non-positive model dimension", who);
+    BS_REQUIRE(c->n_heads % c->n_kv_heads == 0, BS_ESHAPE, "%s: n_heads %d not a multiple of n_kv_heads %d", who, c->n_heads, c->n_kv_heads);
+    BS_REQUIRE(c->head_dim % 8 == 0 && c->head_dim >= 8 && c->head_dim <= 128, BS_ESHAPE,
+               "%s: head_dim %d must be a multiple of 8 in [8,128]", who, c->head_dim);
+    BS_REQUIRE(c->d_model % 8 == 0 && c->d_ff % 8 == 0, BS_ESHAPE, "%s: d_model and d_ff must be multiples of 8", who);
+    BS_REQUIRE(c->vocab <= (1 << 20), BS_ESHAPE, "%s: vocab %d > 2^20", who, c->vocab);
+    BS_REQUIRE(c->rope_base > 1.f && c->norm_eps > 0.f, BS_EINVAL, "%s: rope_base/norm_eps out of range", who);
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_model_create(const bs_model_cfg* cfg, const bs_model_weights* w, bs_model** out) {
+    int rc = check_cfg(cfg, "bs_model_create");
+    if (rc != BS_OK) return rc;
+    BS_REQUIRE(w && out, BS_EINVAL, "bs_model_create: NULL argument");
+    BS_REQUIRE(w->embed && w->final_norm && w->lm_head && w->layers, BS_EINVAL, "bs_model_create: NULL weight pointer");
+    bs_model* m = new (std::nothrow) bs_model();
+    BS_REQUIRE(m, BS_EINVAL, "bs_model_create: out of host memory");
+    m->cfg = *cfg; m->embed = w->embed; m->final_norm = w->final_norm; m->lm_head = w->lm_head;
+    m->layers.assign(w->layers, w->layers + cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const bs_layer_weights& L = m->layers[l];
+        const void* ptrs[9] = {L.attn_norm, L.wq, L.wk, L.wv, L.wo, L.ffn_norm, L.w_gate, L.w_up, L.w_down};
+        for (int i = 0; i < 9; ++i) {
+            if (!ptrs[i] || (reinterpret_cast<uintptr_t>(ptrs[i]) & 15)) {
+                delete m;
+                BS_FAIL(BS_EINVAL, "bs_model_create: layer %d weight %d is NULL or not 16-byte aligned", l, i);
+            }
+        }
+    }
+    *out = m;
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_model_destroy(bs_model* m) { delete m; return BS_OK; }
+
+extern "C" __attribute__((visibility("default"))) size_t bs_kv_bytes(const bs_model_cfg* c, int B, int max_len) {
+    if (!c || B < 1 || max_len < 1) return 0;
+    return (size_t)c->n_layers * 2 * B * c->n_kv_heads * (size_t)max_len * c->head_dim * esize(c->dtype);
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_kv_bind(const bs_model* m, int B, int max_len, void* dev_buf, size_t bytes, bs_kv** out) {
+    BS_REQUIRE(m && dev_buf && out, BS_EINVAL, "bs_kv_bind: NULL argument");
+    BS_REQUIRE(B >= 1 && max_len >= 1, BS_ESHAPE, "bs_kv_bind: B=%d max_len=%d", B, max_len);
+    BS_REQUIRE(bytes >= bs_kv_bytes(&m->cfg, B, max_len), BS_EWORKSPACE, "bs_kv_bind: buffer %zu < %zu bytes", bytes, bs_kv_bytes(&m->cfg, B, max_len));
+    BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_buf) & 255) == 0, BS_EWORKSPACE, "bs_kv_bind: buffer not 256-byte aligned");
+    bs_kv* kv = new (std::nothrow) bs_kv();
+    BS_REQUIRE(kv, BS_EINVAL, "bs_kv_bind: out of host memory");
+    kv->cfg = m->cfg; kv->B = B; kv->max_len = max_len; kv->buf = reinterpret_cast<char*>(dev_buf); kv->bytes = bytes;
+    *out = kv;
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_kv_destroy(bs_kv* kv) { delete kv; return BS_OK; }
+
+// ---- forward workspace ----------------------------------------------------------------------------
+static int attn_splits(int B, int H, int max_len) {
+    int by_len = (max_len + 255) / 256;              // at least ~4 tiles of 64 keys per split at full length
+    int by_fill = (1024 + B * H - 1) / (B * H);      // enough workgroups to cover 256 CUs a few times
+    int s = by_len < by_fill ? by_len : by_fill;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return s;
+}
+
+struct FwdWs {
+    int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* qkv; void* q; void* att; void* act;
+    float* part; size_t total;
+};
+
+static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* base) {
+    FwdWs w;
+    const size_t M = (size_t)B * q_len, es = esize(c.dtype);
+    const size_t nq = (size_t)c.n_heads * c.head_dim, nkv = (size_t)c.n_kv_heads * c.head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return base ? base + o : (char*)nullptr; };
+    w.status = (int32_t*)take(256);
+    w.pos = (int32_t*)take(M * 4);
+    w.tok = (int32_t*)take(M * 4);
+    w.rope = (float2*)take(M * (c.head_dim / 2) * 8);
+    w.x = (float*)take(M * c.d_model * 4);
+    w.h = take(M * c.d_model * es);
+    w.qkv = (float*)take(M * (nq + 2 * nkv) * 4);
+    w.q = take(M * nq * es);
+    w.att = take(M * nq * es);
+    w.act = take(M * c.d_ff * es);
+    w.part = (float*)take(M * c.n_heads * attn_splits(B, c.n_heads, max_len) * (size_t)(c.head_dim + 2) * 4);
+    w.total = off;
+    return w;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t bs_forward_workspace_bytes(const bs_model_cfg* c, int B, int max_q_len, int max_len) {
+    if (!c || B < 1 || max_q_len < 1 || max_len < 1) return 0;
+    return carve(*c, B, max_q_len, max_len, nullptr).total;
+}
+
+// One pass of the model over q_len tokens per sequence (see bs_verify_forward).  kv position of query j is
+// kv_len[b] + kv_base + j; logits of the trailing logit_rows rows go to logits + b*logits_bstride + r*V.
+static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, int q_stride, const int32_t* kv_len,
+                   int kv_base, int q_len, int logit_rows, float* logits, size_t logits_bstride, void* ws, size_t ws_bytes,
+                   hipStream_t s) {
+    const bs_model_cfg& c = m->cfg;
+    const int B = kv->B, M = B * q_len, dt = c.dtype;
+    const size_t need = carve(c, B, q_len, kv->max_len, nullptr).total;
+    BS_REQUIRE(ws_bytes >= need, BS_EWORKSPACE, "forward: workspace %zu < %zu bytes", ws_bytes, need);
+    BS_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255) == 0, BS_EWORKSPACE, "forward: workspace not 256-byte aligned");
+    FwdWs w = carve(c, B, q_len, kv->max_len, reinterpret_cast<char*>(ws));
+    const int H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim;
+    const int nq = H * hd, nkv = KVH * hd;
+    const size_t es = esize(dt);
+    const size_t kv_layer = (size_t)2 * B * KVH * (size_t)kv->max_len * hd * es;
+    const int splits = attn_splits(B, H, kv->max_len);
+    int rc;
+#define BS_TRY(expr) do { rc = (expr); if (rc != BS_OK) return rc; } while (0)
+    BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
+                       w.rope, w.status, s));
+    BS_TRY(launch_embed(dt, w.tok, m->embed, M, c.d_model, w.x, s));
+    for (int l = 0; l < c.n_layers; ++l) {
+        const bs_layer_weights& L = m->layers[l];
+        char* kc = kv->buf + (size_t)l * kv_layer;
+        char* vc = kc + kv_layer / 2;
+        BS_TRY(launch_rmsnorm(dt, w.x, L.attn_norm, c.d_model, c.norm_eps, B, q_len, q_len, w.h, s));
+        GemmArgs g;
+        g.x = w.h; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
+        g.out = w.qkv; g.M = M; g.N = nq + 2 * nkv; g.K = c.d_model; g.ldo = nq + 2 * nkv;
+        BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
+        BS_TRY(launch_rope_kv(dt, w.qkv, w.pos, w.rope, M, q_len, H, KVH, hd, kv->max_len, w.q, kc, vc, s));
+        BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, kv->max_len, splits, w.part, w.att, s));
+        g.x = w.att; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.d_model; g.seg_rows[1] = 0;
+        g.out = w.x; g.M = M; g.N = c.d_model; g.K = nq; g.ldo = c.d_model;
+        BS_TRY(launch_gemm(dt, GEMM_ADD, g, s));
+        BS_TRY(launch_rmsnorm(dt, w.x, L.ffn_norm, c.d_model, c.norm_eps, B, q_len, q_len, w.h, s));
+        g.x = w.h; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = c.d_ff; g.seg_rows[1] = 0;
+        g.out = w.act; g.M = M; g.N = c.d_ff; g.K = c.d_model; g.ldo = c.d_ff;
+        BS_TRY(launch_gemm(dt, GEMM_SWIGLU, g, s));
+        g.x = w.act; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.d_model; g.seg_rows[1] = 0;
+        g.out = w.x; g.M = M; g.N = c.d_model; g.K = c.d_ff; g.ldo = c.d_model;
+        BS_TRY(launch_gemm(dt, GEMM_ADD, g, s));
+    }
+    if (logit_rows > 0) {
+        BS_TRY(launch_rmsnorm(dt, w.x, m->final_norm, c.d_model, c.norm_eps, B, q_len, logit_rows, w.h, s));
+        // one GEMM per sequence when the caller's rows of one sequence are not contiguous with the next
+        const bool contiguous = logits_bstride == (size_t)logit_rows * c.vocab;
+        GemmArgs g;
+        g.w[0] = m->lm_head; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.vocab; g.seg_rows[1] = 0;
+        g.N = c.vocab; g.K = c.d_model; g.ldo = c.vocab;
+        if (contiguous || logit_rows > 1) {
+            if (contiguous) {
+                g.x = w.h; g.out = logits; g.M = B * logit_rows;
+                BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
+            } else {
+                for (int b = 0; b < B; ++b) {
+                    g.x = reinterpret_cast<char*>(w.h) + (size_t)b * logit_rows * c.d_model * es;
+                    g.out = logits + (size_t)b * logits_bstride; g.M = logit_rows;
+                    BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
+                }
+            }
+        } else {
+            // one row per sequence, rows strided in the output: a single GEMM with ldo = batch stride
+            g.x = w.h; g.out = logits; g.M = B; g.ldo = (int)logits_bstride;
+            BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
+        }
+    }
+#undef BS_TRY
+    return BS_OK;
+}
+
+static int check_fwd_args(const bs_model* m, const bs_kv* kv, const char* who) {
+    BS_REQUIRE(m && kv, BS_EINVAL, "%s: NULL handle", who);
+    const bs_model_cfg &a = m->cfg, &b = kv->cfg;
+    BS_REQUIRE(a.n_layers == b.n_layers && a.n_kv_heads == b.n_kv_heads && a.head_dim == b.head_dim && a.dtype == b.dtype,
+               BS_ESTATE, "%s: KV cache was bound for a different model shape", who);
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_verify_forward(const bs_model* m, const bs_kv* kv, const int32_t* dev_q_tokens, const int32_t* dev_kv_len,
+                                 int q_len, int logit_rows, float* dev_logits, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_fwd_args(m, kv, "bs_verify_forward");
+    if (rc != BS_OK) return rc;
+    BS_REQUIRE(dev_q_tokens && dev_kv_len && ws, BS_EINVAL, "bs_verify_forward: NULL pointer");
+    BS_REQUIRE(q_len >= 1 && q_len <= kv->max_len, BS_ESHAPE, "bs_verify_forward: q_len=%d outside [1, max_len=%d]", q_len, kv->max_len);
+    BS_REQUIRE(logit_rows >= 0 && logit_rows <= q_len, BS_ESHAPE, "bs_verify_forward: logit_rows=%d outside [0, q_len=%d]", logit_rows, q_len);
+    BS_REQUIRE(logit_rows == 0 || dev_logits, BS_EINVAL, "bs_verify_forward: dev_logits is NULL");
+    BS_REQUIRE((long long)kv->B * q_len <= (1 << 20), BS_ESHAPE, "bs_verify_forward: too many query rows");
+    return forward(m, kv, dev_q_tokens, q_len, dev_kv_len, 0, q_len, logit_rows, dev_logits, (size_t)logit_rows * m->cfg.vocab,
+                   ws, ws_bytes, reinterpret_cast<hipStream_t>(stream));
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_prefill(const bs_model* m, const bs_kv* kv, const int32_t* dev_tokens, int token_stride, int n,
+                          float* dev_last_logits, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_fwd_args(m, kv, "bs_prefill");
+    if (rc != BS_OK) return rc;
+    BS_REQUIRE(dev_tokens && ws, BS_EINVAL, "bs_prefill: NULL pointer");
+    BS_REQUIRE(n >= 1 && n <= token_stride && n <= kv->max_len, BS_ESHAPE, "bs_prefill: n=%d, stride=%d, max_len=%d", n, token_stride, kv->max_len);
+    // largest chunk the workspace allows (at most 128 query rows per sequence)
+    int chunk = n < 128 ? n : 128;
+    while (chunk > 1 && bs_forward_workspace_bytes(&m->cfg, kv->B, chunk, kv->max_len) > ws_bytes) chunk /= 2;
+    BS_REQUIRE(bs_forward_workspace_bytes(&m->cfg, kv->B, chunk, kv->max_len) <= ws_bytes, BS_EWORKSPACE,
+               "bs_prefill: workspace %zu bytes too small even for one row per sequence", ws_bytes);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    for (int start = 0; start < n; start += chunk) {
+        const int len = (n - start < chunk) ? n - start : chunk;
+        const bool last = start + len >= n;
+        rc = forward(m, kv, dev_tokens + start, token_stride, nullptr, start, len, (last && dev_last_logits) ? 1 : 0,
+                     dev_last_logits, (size_t)m->cfg.vocab, ws, ws_bytes, s);
+        if (rc != BS_OK) return rc;
+    }
+    return BS_OK;
+}
+
+// =====================================================================================================
+// Round driver
+// =====================================================================================================
+struct RoundWs {
+    uint32_t* round; int32_t* status;
+    int32_t *q_draft2, *q_draft1, *q_target, *draft_tokens, *kvlen_draft, *kvlen_target, *flags, *cand, *active;
+    float *draft_logits, *target_logits, *margins;
+    char* fwd; size_t fwd_bytes; size_t total;
+};
+
+static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* drafts, int n_drafts, int B, int L, int max_len, char* base) {
+    RoundWs w;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return base ? base + o : (char*)nullptr; };
+    char* hdr = take(256);
+    w.round = (uint32_t*)hdr; w.status = (int32_t*)(hdr ? hdr + 64 : nullptr);
+    w.q_draft2 = (int32_t*)take((size_t)B * 2 * 4);
+    w.q_draft1 = (int32_t*)take((size_t)B * 4);
+    w.q_target = (int32_t*)take((size_t)B * (L + 1) * 4);
+    w.draft_tokens = (int32_t*)take((size_t)B * L * 4);
+    w.kvlen_draft = (int32_t*)take((size_t)B * 4);
+    w.kvlen_target = (int32_t*)take((size_t)B * 4);
+    w.flags = (int32_t*)take((size_t)B * (L + 1) * 4);
+    w.cand = (int32_t*)take((size_t)B * (L + 1) * 4);
+    w.active = (int32_t*)take((size_t)B * 4);
+    w.margins = (float*)take((size_t)B * L * 4);
+    w.draft_logits = (float*)take((size_t)B * L * t.vocab * 4);
+    w.target_logits = (float*)take((size_t)B * (L + 1) * t.vocab * 4);
+    size_t f = carve(t, B, L + 1, max_len, nullptr).total;
+    for (int i = 0; i < n_drafts; ++i) {
+        size_t fd = carve(*drafts[i], B, 2, max_len, nullptr).total;
+        if (fd > f) f = fd;
+    }
+    w.fwd = take(f); w.fwd_bytes = f;
+    w.total = off;
+    return w;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t bs_round_workspace_bytes(const bs_model_cfg* target, const bs_model_cfg* const* drafts, int n_drafts,
+                                                   int B, int L, int max_len) {
+    if (!target || !drafts || n_drafts < 1 || B < 1 || L < 1 || max_len < 1) return 0;
+    return carve_round(*target, drafts, n_drafts, B, L, max_len, nullptr).total;
+}
+
+struct ArmGraph {
+    hipGraphExec_t exec = nullptr;
+    int32_t* emitted = nullptr; int32_t* n_emitted = nullptr; hipStream_t stream = nullptr;
+};
+
+struct bs_round {
+    bs_round_cfg cfg;
+    std::vector<const bs_model*> drafts;
+    std::vector<const bs_kv*> draft_kvs;
+    std::vector<int> arm_draft, arm_gamma;
+    int L;
+    RoundWs ws;
+    std::vector<ArmGraph> graphs;
+    int last_gamma;
+};
+
+namespace bs {
+
+__global__ void set_round_kernel(uint32_t* round, int32_t* status, int32_t* fwd_status, uint32_t t0) {
+    if (threadIdx.x == 0) { *round = t0; *status = 0; *fwd_status = 0; }
+}
+
+// Start of a round: gather the draft's first two inputs and the target's first query token.
+__global__ void round_begin_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ total_len,
+                                   const int32_t* __restrict__ goal_len, int B, int max_len, int tq_stride,
+                                   int32_t* __restrict__ q_draft2, int32_t* __restrict__ q_target,
+                                   int32_t* __restrict__ kvlen_draft, int32_t* __restrict__ kvlen_target,
+                                   int32_t* __restrict__ active, int32_t* __restrict__ status) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int total = total_len[b];
+    const bool ok = total >= 2 && total <= max_len;
+    if (!ok) atomicOr(status, 4);
+    const int t1 = ok ? tokens[(size_t)b * max_len + total - 1] : 0;
+    const int t0 = ok ? tokens[(size_t)b * max_len + total - 2] : 0;
+    q_draft2[2 * b] = t0; q_draft2[2 * b + 1] = t1;
+    q_target[(size_t)b * tq_stride] = t1;
+    kvlen_draft[b] = ok ? total - 2 : max_len;        // max_len: makes the forward skip the sequence
+    kvlen_target[b] = ok ? total - 1 : max_len;
+    active[b] = ok && (goal_len == nullptr || total < goal_len[b]);
+}
+
+// End of a round (Alg. 3: pt_t = concat(pt_{t-1}, x_t); reward y = len(x_t)).
+__global__ void round_commit_kernel(const int32_t* __restrict__ flags, const int32_t* __restrict__ cand,
+                                    const int32_t* __restrict__ draft_tokens, const int32_t* __restrict__ active,
+                                    const int32_t* __restrict__ goal_len, int B, int gamma, int L, int max_len,
+                                    int32_t* __restrict__ tokens, int32_t* __restrict__ total_len,
+                                    int32_t* __restrict__ emitted, int32_t* __restrict__ n_emitted,
+                                    uint32_t* __restrict__ round) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b == 0) *round += 1u;      // every kernel of this round has already read the counter (stream order)
+    if (b >= B) return;
+    if (!active[b]) { n_emitted[b] = 0; return; }
+    int tau = 0;
+    while (tau < gamma && (flags[(size_t)b * (gamma + 1) + tau] & 1)) ++tau;
+    const int total = total_len[b];
+    const int goal = goal_len ? min(goal_len[b], max_len) : max_len;
+    int len = total;
+    for (int i = 0; i <= tau; ++i) {
+        const int tk = (i < tau) ? draft_tokens[(size_t)b * gamma + i] : cand[(size_t)b * (gamma + 1) + tau];
+        emitted[(size_t)b * (L + 1) + i] = tk;
+        if (len < goal) { tokens[(size_t)b * max_len + len] = tk; ++len; }
+    }
+    for (int i = tau + 1; i <= L; ++i) emitted[(size_t)b * (L + 1) + i] = -1;
+    total_len[b] = len;
+    n_emitted[b] = tau + 1;
+}
+
+}  // namespace bs
+
+extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_round_cfg* cfg, bs_round** out) {
+    BS_REQUIRE(cfg && out, BS_EINVAL, "bs_round_create: NULL argument");
+    BS_REQUIRE(cfg->target && cfg->target_kv && cfg->drafts && cfg->draft_kvs && cfg->arm_draft && cfg->arm_gamma, BS_EINVAL,
+               "bs_round_create: NULL handle array");
+    BS_REQUIRE(cfg->dev_tokens && cfg->dev_total_len && cfg->dev_workspace, BS_EINVAL, "bs_round_create: NULL device pointer");
+    BS_REQUIRE(cfg->n_drafts >= 1 && cfg->n_arms >= 1 && cfg->B >= 1 && cfg->max_len >= 2, BS_ESHAPE, "bs_round_create: bad counts");
+    BS_REQUIRE(cfg->temperature > 0.f, BS_EINVAL, "bs_round_create: temperature must be > 0");
+    int rc = check_fwd_args(cfg->target, cfg->target_kv, "bs_round_create(target)");
+    if (rc != BS_OK) return rc;
+    BS_REQUIRE(cfg->target_kv->B == cfg->B && cfg->target_kv->max_len == cfg->max_len, BS_ESHAPE,
+               "bs_round_create: target cache bound for B=%d max_len=%d", cfg->target_kv->B, cfg->target_kv->max_len);
+    std::vector<const bs_model_cfg*> dcfg;
+    for (int i = 0; i < cfg->n_drafts; ++i) {
+        rc = check_fwd_args(cfg->drafts[i], cfg->draft_kvs[i], "bs_round_create(draft)");
+        if (rc != BS_OK) return rc;
+        BS_REQUIRE(cfg->draft_kvs[i]->B == cfg->B && cfg->draft_kvs[i]->max_len == cfg->max_len, BS_ESHAPE,
+                   "bs_round_create: draft %d cache bound for another B/max_len", i);
+        BS_REQUIRE(cfg->drafts[i]->cfg.vocab == cfg->target->cfg.vocab, BS_ESHAPE, "bs_round_create: draft %d vocabulary differs", i);
+        dcfg.push_back(&cfg->drafts[i]->cfg);
+    }
+    int L = 0;
+    for (int a = 0; a < cfg->n_arms; ++a) {
+        BS_REQUIRE(cfg->arm_draft[a] >= 0 && cfg->arm_draft[a] < cfg->n_drafts, BS_EINVAL, "bs_round_create: arm %d names draft %d", a, cfg->arm_draft[a]);
+        BS_REQUIRE(cfg->arm_gamma[a] >= 1 && cfg->arm_gamma[a] <= 64, BS_EINVAL, "bs_round_create: arm %d gamma %d outside [1,64]", a, cfg->arm_gamma[a]);
+        if (cfg->arm_gamma[a] > L) L = cfg->arm_gamma[a];
+    }
+    const size_t need = carve_round(cfg->target->cfg, dcfg.data(), cfg->n_drafts, cfg->B, L, cfg->max_len, nullptr).total;
+    BS_REQUIRE(cfg->workspace_bytes >= need, BS_EWORKSPACE, "bs_round_create: workspace %zu < %zu bytes", cfg->workspace_bytes, need);
+    BS_REQUIRE((reinterpret_cast<uintptr_t>(cfg->dev_workspace) & 255) == 0, BS_EWORKSPACE, "bs_round_create: workspace not 256-byte aligned");
+    bs_round* r = new (std::nothrow) bs_round();
+    BS_REQUIRE(r, BS_EINVAL, "bs_round_create: out of host memory");
+    r->cfg = *cfg;
+    r->drafts.assign(cfg->drafts, cfg->drafts + cfg->n_drafts);
+    r->draft_kvs.assign(cfg->draft_kvs, cfg->draft_kvs + cfg->n_drafts);
+    r->arm_draft.assign(cfg->arm_draft, cfg->arm_draft + cfg->n_arms);
+    r->arm_gamma.assign(cfg->arm_gamma, cfg->arm_gamma + cfg->n_arms);
+    r->L = L;
+    r->ws = carve_round(cfg->target->cfg, dcfg.data(), cfg->n_drafts, cfg->B, L, cfg->max_len, reinterpret_cast<char*>(cfg->dev_workspace));
+    r->graphs.resize(cfg->n_arms);
+    r->last_gamma = 0;
+    *out = r;
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_round_destroy(bs_round* r) {
+    if (r) {
+        for (auto& g : r->graphs)
+            if (g.exec) hipGraphExecDestroy(g.exec);
+        delete r;
+    }
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_round_reset(bs_round* r, uint32_t t0, void* stream) {
+    BS_REQUIRE(r, BS_EINVAL, "bs_round_reset: NULL handle");
+    hipLaunchKernelGGL(bs::set_round_kernel, dim3(1), dim3(64), 0, reinterpret_cast<hipStream_t>(stream), r->ws.round, r->ws.status, reinterpret_cast<int32_t*>(r->ws.fwd), t0);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emitted, hipStream_t s) {
+    const bs_round_cfg& c = r->cfg;
+    const int gamma = r->arm_gamma[arm], B = c.B, V = c.target->cfg.vocab;
+    const bs_model* draft = r->drafts[r->arm_draft[arm]];
+    const bs_kv* dkv = r->draft_kvs[r->arm_draft[arm]];
+    RoundWs& w = r->ws;
+    int rc;
+    hipLaunchKernelGGL(bs::round_begin_kernel, dim3((B + 127) / 128), dim3(128), 0, s, c.dev_tokens, c.dev_total_len,
+                       c.dev_goal_len, B, c.max_len, gamma + 1, w.q_draft2, w.q_target, w.kvlen_draft, w.kvlen_target,
+                       w.active, w.status);
+    BS_LAUNCH_CHECK();
+    // ---- draft proposal: gamma sequential steps (App. A, generation of x~_1..x~_gamma) ----
+    for (int i = 0; i < gamma; ++i) {
+        float* row = w.draft_logits + (size_t)i * V;                  // [B, gamma, V], row i of every sequence
+        if (i == 0)
+            rc = forward(draft, dkv, w.q_draft2, 2, w.kvlen_draft, 0, 2, 1, row, (size_t)gamma * V, w.fwd, w.fwd_bytes, s);
+        else
+            rc = forward(draft, dkv, w.q_draft1, 1, w.kvlen_draft, i + 1, 1, 1, row, (size_t)gamma * V, w.fwd, w.fwd_bytes, s);
+        if (rc != BS_OK) return rc;
+        DrawParams d;
+        d.logits = row; d.row_stride = gamma * V; d.V = V; d.inv_temp = 1.0f / c.temperature; d.seed = c.seed;
+        d.round_ptr = w.round; d.round = 0; d.slot = (uint32_t)i;
+        d.out0 = w.draft_tokens; d.stride0 = gamma; d.off0 = i;
+        d.out1 = w.q_target; d.stride1 = gamma + 1; d.off1 = i + 1;
+        d.out2 = w.q_draft1; d.stride2 = 1; d.off2 = 0;
+        rc = launch_draw(d, B, s);
+        if (rc != BS_OK) return rc;
+    }
+    // ---- verification: one target pass over gamma+1 positions ----
+    rc = forward(c.target, c.target_kv, w.q_target, gamma + 1, w.kvlen_target, 0, gamma + 1, gamma + 1, w.target_logits,
+                 (size_t)(gamma + 1) * V, w.fwd, w.fwd_bytes, s);
+    if (rc != BS_OK) return rc;
+    // ---- accept / reject, residual and bonus candidates ----
+    rc = launch_spec_rows(w.target_logits, w.draft_logits, w.draft_tokens, B, gamma, V, BS_F32, c.temperature, nullptr,
+                          c.seed, w.round, 0, w.flags, w.cand, w.margins, s);
+    if (rc != BS_OK) return rc;
+    // ---- commit ----
+    hipLaunchKernelGGL(bs::round_commit_kernel, dim3((B + 127) / 128), dim3(128), 0, s, w.flags, w.cand, w.draft_tokens,
+                       w.active, c.dev_goal_len, B, gamma, r->L, c.max_len, c.dev_tokens, c.dev_total_len, emitted,
+                       n_emitted, w.round);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emitted, void* stream) {
+    BS_REQUIRE(r, BS_EINVAL, "bs_spec_round: NULL handle");
+    BS_REQUIRE(arm >= 0 && arm < (int)r->arm_gamma.size(), BS_EINVAL, "bs_spec_round: arm %d not in [0,%zu)", arm, r->arm_gamma.size());
+    BS_REQUIRE(dev_emitted && dev_n_emitted, BS_EINVAL, "bs_spec_round: NULL output pointer");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    r->last_gamma = r->arm_gamma[arm];
+    if (!r->cfg.use_graph) return enqueue_round(r, arm, dev_emitted, dev_n_emitted, s);
+    BS_REQUIRE(s != nullptr, BS_EINVAL, "bs_spec_round: graph mode needs a non-null stream");
+    ArmGraph& g = r->graphs[arm];
+    if (g.exec && (g.emitted != dev_emitted || g.n_emitted != dev_n_emitted)) {
+        hipGraphExecDestroy(g.exec);
+        g.exec = nullptr;
+    }
+    if (!g.exec) {
+        hipGraph_t graph = nullptr;
+        BS_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+        const int rc = enqueue_round(r, arm, dev_emitted, dev_n_emitted, s);
+        const hipError_t e = hipStreamEndCapture(s, &graph);
+        if (rc != BS_OK) { if (graph) hipGraphDestroy(graph); return rc; }
+        if (e != hipSuccess) BS_FAIL(BS_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        const hipError_t e2 = hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0);
+        hipGraphDestroy(graph);
+        if (e2 != hipSuccess) { g.exec = nullptr; BS_FAIL(BS_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e2)); }
+        g.emitted = dev_emitted; g.n_emitted = dev_n_emitted;
+    }
+    BS_HIP(hipGraphLaunch(g.exec, s));
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_round_debug_views(bs_round* r, const float** tl, const float** dl, const int32_t** dt, const float** mg) {
+    BS_REQUIRE(r, BS_EINVAL, "bs_round_debug_views: NULL handle");
+    if (tl) *tl = r->ws.target_logits;
+    if (dl) *dl = r->ws.draft_logits;
+    if (dt) *dt = r->ws.draft_tokens;
+    if (mg) *mg = r->ws.margins;
+    return BS_OK;
+}

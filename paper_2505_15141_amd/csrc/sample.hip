@@ -1,0 +1,563 @@
+// Vocabulary-wide softmax + accept/reject + residual/bonus sampling (App. A, vanilla speculative
+// decoding: the loop over draft positions and the bonus draw), and the categorical draw used by
+// the draft steps.
+//
+// One workgroup of 512 lanes owns one (sequence, position) row pair (target row p, draft row q).
+// It reads both rows from HBM exactly once with 16-byte loads, keeps them in registers when the
+// vocabulary fits (V <= 32768), and produces
+//   * the acceptance decision  u * q(x~) <= p(x~)      (positions i < gamma)
+//   * the token an inverse-CDF draw would give if this position turned out to be the deciding one:
+//     from [p - q]_+ for i < gamma, from p for the bonus position i = gamma.
+// A second, tiny kernel walks the gamma flags of each sequence and picks the deciding position.
+// All positions are processed in parallel: nothing waits on the sequential accept chain.
+//
+// Reductions: per-lane online softmax (max, sum) -> wavefront shuffles -> LDS across 8 wavefronts.
+// Inverse CDF in increasing token id: lane t owns 8-token groups t, t+512, ...; "slab" k is the
+// 4096 consecutive tokens of groups [512k, 512k+512).  Slab totals locate the slab, a block-wide
+// scan of the 512 group sums locates the group, a serial scan of 8 weights locates the token.
+#include <math.h>
+#include "common.h"
+#include "sample.h"
+
+namespace bs {
+
+constexpr int ST = 512;           // lanes per workgroup
+constexpr int SW = ST / 64;       // wavefronts per workgroup
+constexpr int GE = 8;             // tokens per group
+constexpr int MAX_SLABS = 256;    // V <= 2^20
+constexpr int SLAB_BATCH = 4;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// A group = tokens [8g, 8g+8) of a row, held as loaded (16 B of bf16, or 32 B of float); tokens >= V
+// read as -inf.  expand() turns it into floats scaled by 1/temperature.
+template <typename T> struct Raw;
+template <> struct Raw<uint16_t> { uint4 v; };
+template <> struct Raw<float> { float4 a, b; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ Raw<uint16_t> neg_inf_raw(const uint16_t*) {
+    Raw<uint16_t> r; r.v = make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u); return r;
+}
+__device__ __forceinline__ Raw<float> neg_inf_raw(const float*) {
+    Raw<float> r; r.a = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY); r.b = r.a; return r;
+}
+
+__device__ __forceinline__ Raw<uint16_t> load_raw_vec(const uint16_t* __restrict__ row, int g) {
+    Raw<uint16_t> r;
+    r.v = *reinterpret_cast<const uint4*>(row + g * GE);
+    return r;
+}
+__device__ __forceinline__ Raw<float> load_raw_vec(const float* __restrict__ row, int g) {
+    Raw<float> r;
+    r.a = *reinterpret_cast<const float4*>(row + g * GE);
+    r.b = *reinterpret_cast<const float4*>(row + g * GE + 4);
+    return r;
+}
+__device__ __forceinline__ Raw<uint16_t> load_raw(const uint16_t* __restrict__ row, int g, int V, bool vec_ok) {
+    const int base = g * GE;
+    Raw<uint16_t> r;
+    if (vec_ok && base + GE <= V) {
+        r.v = *reinterpret_cast<const uint4*>(row + base);
+    } else {
+        uint32_t h[GE];
+#pragma unroll
+        for (int e = 0; e < GE; ++e) h[e] = (base + e < V) ? (uint32_t)row[base + e] : 0xFF80u;
+        r.v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+    return r;
+}
+__device__ __forceinline__ Raw<float> load_raw(const float* __restrict__ row, int g, int V, bool vec_ok) {
+    const int base = g * GE;
+    Raw<float> r;
+    if (vec_ok && base + GE <= V) {
+        r.a = *reinterpret_cast<const float4*>(row + base);
+        r.b = *reinterpret_cast<const float4*>(row + base + 4);
+    } else {
+        float h[GE];
+#pragma unroll
+        for (int e = 0; e < GE; ++e) h[e] = (base + e < V) ? row[base + e] : -INFINITY;
+        r.a = make_float4(h[0], h[1], h[2], h[3]);
+        r.b = make_float4(h[4], h[5], h[6], h[7]);
+    }
+    return r;
+}
+// Stops the compiler from carrying values derived from a group across passes.
+__device__ __forceinline__ void keep_opaque(Raw<uint16_t>& r) {
+    asm volatile("" : "+v"(r.v.x), "+v"(r.v.y), "+v"(r.v.z), "+v"(r.v.w));
+}
+__device__ __forceinline__ void keep_opaque(Raw<float>& r) {
+    asm volatile("" : "+v"(r.a.x), "+v"(r.a.y), "+v"(r.a.z), "+v"(r.a.w), "+v"(r.b.x), "+v"(r.b.y), "+v"(r.b.z), "+v"(r.b.w));
+}
+__device__ __forceinline__ void expand(const Raw<uint16_t>& r, float s, float out[GE]) {
+    out[0] = bf16_lo(r.v.x) * s; out[1] = bf16_hi(r.v.x) * s; out[2] = bf16_lo(r.v.y) * s; out[3] = bf16_hi(r.v.y) * s;
+    out[4] = bf16_lo(r.v.z) * s; out[5] = bf16_hi(r.v.z) * s; out[6] = bf16_lo(r.v.w) * s; out[7] = bf16_hi(r.v.w) * s;
+}
+__device__ __forceinline__ void expand(const Raw<float>& r, float s, float out[GE]) {
+    out[0] = r.a.x * s; out[1] = r.a.y * s; out[2] = r.a.z * s; out[3] = r.a.w * s;
+    out[4] = r.b.x * s; out[5] = r.b.y * s; out[6] = r.b.z * s; out[7] = r.b.w * s;
+}
+
+template <typename T>
+__device__ __forceinline__ float load_one(const T* row, int idx);
+template <>
+__device__ __forceinline__ float load_one<float>(const float* row, int idx) { return row[idx]; }
+template <>
+__device__ __forceinline__ float load_one<uint16_t>(const uint16_t* row, int idx) {
+    return __uint_as_float((uint32_t)row[idx] << 16);
+}
+
+struct RowShared {
+    float red[4][SW];
+    float slab_tot[MAX_SLABS];
+    float wave_tot[SW];
+    int wave_first[SW];
+    int wave_last[SW];
+    float bcast[8];
+    int ibcast[4];
+};
+
+struct RowResult {
+    int token;        // candidate token of this row (valid in every lane)
+    float p_x, q_x;   // normalised probabilities of the drafted token (lane 0 only, if x >= 0)
+    int fallback;     // residual had no mass: drew from p instead
+};
+
+// Processes one row pair.  has_q = false: the draw is from softmax(p) (bonus token, draft draws).
+// x = drafted token for the acceptance test, or -1.
+template <typename T, int NG, bool CACHED>
+__device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ q, bool has_q, int V, float inv_temp,
+                                 int x, float u_final, RowShared& sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int ngroups = (V + GE - 1) / GE;
+    const int nslabs = (ngroups + ST - 1) / ST;
+    const bool vec_p = ((reinterpret_cast<uintptr_t>(p) & 15) == 0);
+    const bool vec_q = has_q && ((reinterpret_cast<uintptr_t>(q) & 15) == 0);
+
+    Raw<T> pv[CACHED ? NG : 1], qv[CACHED ? NG : 1];
+
+    // ---- pass 1: the only HBM read; per-lane online (max, sum of exp) for both rows ----
+    float mp = -INFINITY, sp = 0.f, mq = -INFINITY, sq = 0.f;
+    auto online = [&](float& m, float& s, const Raw<T>& raw) {
+        float v[GE];
+        expand(raw, inv_temp, v);
+        float gm = v[0];
+#pragma unroll
+        for (int e = 1; e < GE; ++e) gm = fmaxf(gm, v[e]);
+        if (gm == -INFINITY) return;
+        const float mn = fmaxf(m, gm);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < GE; ++e) acc += __expf(v[e] - mn);
+        s = s * __expf(m - mn) + acc;
+        m = mn;
+    };
+    if constexpr (CACHED) {
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+            const int g = tid + k * ST;
+            // the host launches this variant only for 16-byte aligned rows with V % 8 == 0
+            pv[k] = (g < ngroups) ? load_raw_vec(p, g) : neg_inf_raw(p);
+            qv[k] = (has_q && g < ngroups) ? load_raw_vec(q, g) : neg_inf_raw(p);
+        }
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+            online(mp, sp, pv[k]);
+            if (has_q) online(mq, sq, qv[k]);
+            __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the live set small
+        }
+    } else {
+        for (int g = tid; g < ngroups; g += ST) {
+            online(mp, sp, load_raw(p, g, V, vec_p));
+            if (has_q) online(mq, sq, load_raw(q, g, V, vec_q));
+        }
+    }
+    if constexpr (CACHED) {
+        // the later passes recompute from the packed registers instead of keeping expanded values alive
+#pragma unroll
+        for (int k = 0; k < NG; ++k) { keep_opaque(pv[k]); keep_opaque(qv[k]); }
+    }
+    // block combine of (max, sum): maxima first, then rescaled sums
+    {
+        const float wmp = wave_max(mp), wmq = wave_max(mq);
+        if (lane == 0) { sh.red[0][wid] = wmp; sh.red[1][wid] = wmq; }
+        __syncthreads();
+        float bmp = sh.red[0][0], bmq = sh.red[1][0];
+#pragma unroll
+        for (int w = 1; w < SW; ++w) { bmp = fmaxf(bmp, sh.red[0][w]); bmq = fmaxf(bmq, sh.red[1][w]); }
+        const float rp = (mp == -INFINITY) ? 0.f : sp * __expf(mp - bmp);
+        const float rq = (mq == -INFINITY) ? 0.f : sq * __expf(mq - bmq);
+        const float wsp = wave_sum(rp), wsq = wave_sum(rq);
+        if (lane == 0) { sh.red[2][wid] = wsp; sh.red[3][wid] = wsq; }
+        __syncthreads();
+        float zp = 0.f, zq = 0.f;
+#pragma unroll
+        for (int w = 0; w < SW; ++w) { zp += sh.red[2][w]; zq += sh.red[3][w]; }
+        mp = bmp; mq = bmq; sp = zp; sq = zq;
+    }
+    const float inv_zp = 1.0f / sp;
+    const float inv_zq = has_q ? 1.0f / sq : 0.f;
+
+    RowResult res;
+    res.p_x = 0.f; res.q_x = 0.f; res.fallback = 0; res.token = 0;
+    if (tid == 0 && x >= 0) {
+        res.p_x = __expf(load_one<T>(p, x) * inv_temp - mp) * inv_zp;
+        res.q_x = has_q ? __expf(load_one<T>(q, x) * inv_temp - mq) * inv_zq : 0.f;
+    }
+
+    // ---- weights of the draw: [p - q]_+ (normalised probabilities) or exp(p - max) ----
+    bool residual = has_q;
+    auto weights = [&](const Raw<T>& ra, const Raw<T>& rb, float w[GE]) {
+        float a[GE];
+        expand(ra, inv_temp, a);
+        if (residual) {
+            float b[GE];
+            expand(rb, inv_temp, b);
+#pragma unroll
+            for (int e = 0; e < GE; ++e)
+                w[e] = fmaxf(__expf(a[e] - mp) * inv_zp - __expf(b[e] - mq) * inv_zq, 0.f);
+        } else {
+#pragma unroll
+            for (int e = 0; e < GE; ++e) w[e] = __expf(a[e] - mp);
+        }
+    };
+    auto group_weights = [&](int k, int g, float w[GE]) {
+        if (g >= ngroups) {
+#pragma unroll
+            for (int e = 0; e < GE; ++e) w[e] = 0.f;
+            return;
+        }
+        if constexpr (CACHED) {
+            weights(pv[k], qv[k], w);
+        } else {
+            const Raw<T> ra = load_raw(p, g, V, vec_p);
+            const Raw<T> rb = residual ? load_raw(q, g, V, vec_q) : ra;
+            weights(ra, rb, w);
+        }
+    };
+    auto group_sum = [&](int k, int g) {
+        float w[GE];
+        group_weights(k, g, w);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < GE; ++e) s += w[e];
+        return s;
+    };
+
+    float total = 0.f;
+#pragma nounroll
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        // ---- pass 2: slab totals ----
+        if constexpr (CACHED) {
+            float ss[NG];
+#pragma unroll
+            for (int k = 0; k < NG; ++k) {
+                ss[k] = group_sum(k, tid + k * ST);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int k = 0; k < NG; ++k) ss[k] = wave_sum(ss[k]);
+            __syncthreads();
+            if (lane == 0) {
+#pragma unroll
+                for (int k = 0; k < NG; ++k) sh.slab_tot[k * SW + wid] = ss[k];   // staging: [slab][wave]
+            }
+            __syncthreads();
+            float tot[NG];
+#pragma unroll
+            for (int k = 0; k < NG; ++k) {
+                float t = 0.f;
+#pragma unroll
+                for (int w = 0; w < SW; ++w) t += sh.slab_tot[k * SW + w];
+                tot[k] = t;
+            }
+            __syncthreads();
+            if (tid == 0) {
+#pragma unroll
+                for (int k = 0; k < NG; ++k) sh.slab_tot[k] = tot[k];
+            }
+            __syncthreads();
+        } else {
+            for (int k0 = 0; k0 < nslabs; k0 += SLAB_BATCH) {
+                float ss[SLAB_BATCH];
+#pragma unroll
+                for (int j = 0; j < SLAB_BATCH; ++j)
+                    ss[j] = (k0 + j < nslabs) ? wave_sum(group_sum(k0 + j, tid + (k0 + j) * ST)) : 0.f;
+                __syncthreads();
+                if (lane == 0) {
+#pragma unroll
+                    for (int j = 0; j < SLAB_BATCH; ++j) sh.red[j][wid] = ss[j];
+                }
+                __syncthreads();
+                if (tid < SLAB_BATCH && k0 + tid < nslabs) {
+                    float t = 0.f;
+#pragma unroll
+                    for (int w = 0; w < SW; ++w) t += sh.red[tid][w];
+                    sh.slab_tot[k0 + tid] = t;
+                }
+            }
+            __syncthreads();
+        }
+        total = 0.f;
+        for (int k = 0; k < nslabs; ++k) total += sh.slab_tot[k];
+        if (!residual || total > 0.f) break;
+        // residual without mass (p == q up to rounding): draw from p instead
+        residual = false;
+        res.fallback = 1;
+        __syncthreads();
+    }
+
+    // ---- locate the slab ----
+    const float thr = u_final * total;
+    int kstar = -1;
+    float base = 0.f;
+    {
+        float run = 0.f;
+        int last_pos = 0;
+        float last_base = 0.f;
+        for (int k = 0; k < nslabs; ++k) {
+            const float t = sh.slab_tot[k];
+            if (t > 0.f) { last_pos = k; last_base = run; }
+            if (run + t > thr) { kstar = k; base = run; break; }
+            run += t;
+        }
+        if (kstar < 0) { kstar = last_pos; base = last_base; }   // thr >= total only through rounding
+    }
+
+    // ---- pass 3: scan of the 1024 group sums of slab kstar ----
+    float w[GE];
+    {
+        const int g = tid + kstar * ST;
+        if constexpr (CACHED) {
+            // select the register slab without dynamic indexing, then recompute its weights (cheaper
+            // in registers than keeping every slab's weights alive since pass 2)
+#pragma unroll
+            for (int k = 0; k < NG; ++k) { keep_opaque(pv[k]); keep_opaque(qv[k]); }
+            Raw<T> sp_ = pv[0], sq_ = qv[0];
+#pragma unroll
+            for (int k = 1; k < NG; ++k) {
+                if (k == kstar) { sp_ = pv[k]; sq_ = qv[k]; }
+            }
+            keep_opaque(sp_);
+            keep_opaque(sq_);
+            if (g < ngroups) {
+                weights(sp_, sq_, w);
+            } else {
+#pragma unroll
+                for (int e = 0; e < GE; ++e) w[e] = 0.f;
+            }
+        } else {
+            group_weights(kstar, g, w);
+        }
+    }
+    float gs = 0.f;
+#pragma unroll
+    for (int e = 0; e < GE; ++e) gs += w[e];
+    float incl = gs;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    __syncthreads();
+    if (lane == 63) sh.wave_tot[wid] = incl;
+    __syncthreads();
+    float before = base;
+    for (int wv = 0; wv < wid; ++wv) before += sh.wave_tot[wv];
+    incl += before;
+    const bool hit = incl > thr;
+    const uint64_t mhit = __ballot(hit);
+    const uint64_t mpos = __ballot(gs > 0.f);
+    if (lane == 0) {
+        sh.wave_first[wid] = mhit ? (__ffsll((long long)mhit) - 1) : 64;
+        sh.wave_last[wid] = mpos ? (63 - __clzll((long long)mpos)) : -1;
+    }
+    __syncthreads();
+    int tstar = -1, tlast = -1;
+    for (int wv = 0; wv < SW; ++wv) {
+        if (tstar < 0 && sh.wave_first[wv] < 64) tstar = wv * 64 + sh.wave_first[wv];
+        if (sh.wave_last[wv] >= 0) tlast = wv * 64 + sh.wave_last[wv];
+    }
+    const bool forced = tstar < 0;            // rounding pushed thr past this slab's scan total
+    if (forced) tstar = tlast;
+    if (tid == tstar) {
+        float run = incl - gs;
+        int pick = -1, lastpos = 0;
+#pragma unroll
+        for (int e = 0; e < GE; ++e) {
+            run += w[e];
+            if (w[e] > 0.f) lastpos = e;
+            if (pick < 0 && !forced && run > thr) pick = e;
+        }
+        if (pick < 0) pick = lastpos;
+        sh.ibcast[0] = (tid + kstar * ST) * GE + pick;
+    }
+    if (tstar < 0 && tid == 0) sh.ibcast[0] = 0;   // only with non-finite input
+    __syncthreads();
+    res.token = min(sh.ibcast[0], V - 1);
+    return res;
+}
+
+struct SampleParams {
+    const void* p_logits;
+    const void* q_logits;
+    const int32_t* draft_tokens;
+    const float* uniforms;
+    uint64_t seed;
+    const uint32_t* round_ptr;
+    uint32_t round;
+    int gamma, V;
+    float inv_temp;
+    int32_t* flags;      // [B, gamma+1]
+    int32_t* cand;       // [B, gamma+1]
+    float* margins;      // [B, gamma] or null
+};
+
+template <typename T, int NG, bool CACHED>
+__global__ __launch_bounds__(ST) void spec_rowpair_kernel(SampleParams a) {
+    __shared__ RowShared sh;
+    const int row = blockIdx.x;
+    const int b = row / (a.gamma + 1), i = row % (a.gamma + 1);
+    const bool has_q = i < a.gamma;
+    const T* p = reinterpret_cast<const T*>(a.p_logits) + (size_t)row * a.V;
+    const T* q = has_q ? reinterpret_cast<const T*>(a.q_logits) + ((size_t)b * a.gamma + i) * a.V : nullptr;
+    const uint32_t t = a.round_ptr ? *a.round_ptr : a.round;
+    int x = -1;
+    if (has_q) {
+        x = a.draft_tokens[(size_t)b * a.gamma + i];
+        if (x < 0 || x >= a.V) x = -1;
+    }
+    const float u_final = a.uniforms ? a.uniforms[(size_t)b * (a.gamma + 1) + a.gamma]
+                                     : u_closed_open(philox_word(a.seed, (uint32_t)b, t, 0u, PURPOSE_FINAL));
+    const RowResult r = process_row<T, NG, CACHED>(p, q, has_q, a.V, a.inv_temp, x, u_final, sh);
+    if (threadIdx.x == 0) {
+        int accept = 0;
+        if (has_q) {
+            const float u = a.uniforms ? a.uniforms[(size_t)b * (a.gamma + 1) + i]
+                                       : u_open_closed(philox_word(a.seed, (uint32_t)b, t, (uint32_t)i, PURPOSE_ACCEPT));
+            accept = (x >= 0) && (u * r.q_x <= r.p_x);
+            if (a.margins) {
+                const float ratio = (r.q_x > 0.f) ? fminf(1.f, r.p_x / r.q_x) : 1.f;
+                a.margins[(size_t)b * a.gamma + i] = (x >= 0) ? ratio - u : -1.f;
+            }
+        }
+        a.flags[row] = accept | (r.fallback << 1);
+        a.cand[row] = r.token;
+    }
+}
+
+__global__ void spec_resolve_kernel(const int32_t* __restrict__ flags, const int32_t* __restrict__ cand, int B,
+                                    int gamma, int32_t* __restrict__ accept_len, int32_t* __restrict__ next_token) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int tau = 0;
+    while (tau < gamma && (flags[(size_t)b * (gamma + 1) + tau] & 1)) ++tau;
+    accept_len[b] = tau;
+    next_token[b] = cand[(size_t)b * (gamma + 1) + tau];
+}
+
+// Draft-step draw: x~ ~ softmax(logits[b] / T) with the Philox uniform (b, t, slot, DRAFT).
+__global__ __launch_bounds__(ST) void draw_kernel(DrawParams a) {
+    __shared__ RowShared sh;
+    const int b = blockIdx.x;
+    const float* p = a.logits + (size_t)b * a.row_stride;
+    const uint32_t t = a.round_ptr ? *a.round_ptr : a.round;
+    const float u = u_closed_open(philox_word(a.seed, (uint32_t)b, t, a.slot, PURPOSE_DRAFT));
+    RowResult r;
+    if (a.V <= 2 * ST * GE && a.V % GE == 0 && a.row_stride % 4 == 0 && ((uintptr_t)a.logits & 15) == 0)
+        r = process_row<float, 2, true>(p, nullptr, false, a.V, a.inv_temp, -1, u, sh);
+    else
+        r = process_row<float, 1, false>(p, nullptr, false, a.V, a.inv_temp, -1, u, sh);
+    if (threadIdx.x == 0) {
+        if (a.out0) a.out0[(size_t)b * a.stride0 + a.off0] = r.token;
+        if (a.out1) a.out1[(size_t)b * a.stride1 + a.off1] = r.token;
+        if (a.out2) a.out2[(size_t)b * a.stride2 + a.off2] = r.token;
+    }
+}
+
+int launch_draw(const DrawParams& a, int B, hipStream_t stream) {
+    if (B <= 0) return BS_OK;
+    hipLaunchKernelGGL(draw_kernel, dim3(B), dim3(ST), 0, stream, a);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+int launch_spec_rows(const void* p_logits, const void* q_logits, const int32_t* draft_tokens, int B, int gamma, int V,
+                     int dtype, float temperature, const float* uniforms, uint64_t seed, const uint32_t* round_ptr,
+                     uint32_t round, int32_t* flags, int32_t* cand, float* margins, hipStream_t stream) {
+    if (B <= 0) return BS_OK;
+    SampleParams a;
+    a.p_logits = p_logits; a.q_logits = q_logits; a.draft_tokens = draft_tokens; a.uniforms = uniforms;
+    a.seed = seed; a.round_ptr = round_ptr; a.round = round; a.gamma = gamma; a.V = V;
+    a.inv_temp = 1.0f / temperature; a.flags = flags; a.cand = cand; a.margins = margins;
+    const dim3 grid((unsigned)(B * (gamma + 1))), block(ST);
+    // register-resident rows: 8 groups per lane of bf16 (V <= 32768), 2 groups per lane of float
+    const size_t esz = dtype == BS_BF16 ? 2 : 4;
+    const bool aligned = V % GE == 0 && ((uintptr_t)p_logits & 15) == 0 && ((uintptr_t)q_logits & 15) == 0;
+    (void)esz;
+    const bool cached = aligned && V <= (dtype == BS_BF16 ? 8 : 2) * ST * GE;
+    if (dtype == BS_BF16) {
+        if (cached) hipLaunchKernelGGL((spec_rowpair_kernel<uint16_t, 8, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((spec_rowpair_kernel<uint16_t, 1, false>), grid, block, 0, stream, a);
+    } else {
+        if (cached) hipLaunchKernelGGL((spec_rowpair_kernel<float, 2, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((spec_rowpair_kernel<float, 1, false>), grid, block, 0, stream, a);
+    }
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+int launch_spec_resolve(const int32_t* flags, const int32_t* cand, int B, int gamma, int32_t* accept_len,
+                        int32_t* next_token, hipStream_t stream) {
+    if (B <= 0) return BS_OK;
+    hipLaunchKernelGGL(spec_resolve_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, flags, cand, B, gamma,
+                       accept_len, next_token);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+}  // namespace bs
+
+extern "C" __attribute__((visibility("default"))) size_t bs_spec_sample_workspace_bytes(int B, int gamma) {
+    if (B < 0 || gamma < 0) return 0;
+    return bs::align_up((size_t)B * (size_t)(gamma + 1) * sizeof(int32_t), 256) * 2;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
+                              const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype, float temperature,
+                              const float* dev_uniforms, uint64_t seed, uint32_t round, int32_t* dev_accept_len,
+                              int32_t* dev_next_token, float* dev_margins, void* dev_workspace,
+                              size_t workspace_bytes, void* stream) {
+    BS_REQUIRE(B >= 0 && gamma >= 0, BS_EINVAL, "bs_spec_sample: B=%d gamma=%d must be >= 0", B, gamma);
+    BS_REQUIRE(V >= 1 && V <= (1 << 20), BS_ESHAPE, "bs_spec_sample: V=%d outside [1, 2^20]", V);
+    BS_REQUIRE(gamma <= 1024, BS_ESHAPE, "bs_spec_sample: gamma=%d too large", gamma);
+    BS_REQUIRE((long long)B * (gamma + 1) < (1LL << 31), BS_ESHAPE, "bs_spec_sample: B*(gamma+1) overflows");
+    BS_REQUIRE(dtype == BS_F32 || dtype == BS_BF16, BS_EDTYPE, "bs_spec_sample: dtype %d", dtype);
+    BS_REQUIRE(temperature > 0.f && isfinite(temperature), BS_EINVAL, "bs_spec_sample: temperature %g", (double)temperature);
+    if (B == 0) return BS_OK;
+    BS_REQUIRE(dev_target_logits && dev_accept_len && dev_next_token && dev_workspace, BS_EINVAL,
+               "bs_spec_sample: NULL pointer");
+    BS_REQUIRE(gamma == 0 || (dev_draft_logits && dev_draft_tokens), BS_EINVAL, "bs_spec_sample: NULL draft input");
+    BS_REQUIRE(workspace_bytes >= bs_spec_sample_workspace_bytes(B, gamma), BS_EWORKSPACE,
+               "bs_spec_sample: workspace %zu < %zu bytes", workspace_bytes, bs_spec_sample_workspace_bytes(B, gamma));
+    BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 15) == 0, BS_EWORKSPACE, "bs_spec_sample: workspace misaligned");
+    int32_t* flags = reinterpret_cast<int32_t*>(dev_workspace);
+    int32_t* cand = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev_workspace) +
+                                               bs::align_up((size_t)B * (gamma + 1) * sizeof(int32_t), 256));
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    int rc = bs::launch_spec_rows(dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype, temperature,
+                                  dev_uniforms, seed, nullptr, round, flags, cand, dev_margins, s);
+    if (rc != BS_OK) return rc;
+    return bs::launch_spec_resolve(flags, cand, B, gamma, dev_accept_len, dev_next_token, s);
+}

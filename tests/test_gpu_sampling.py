@@ -1,0 +1,149 @@
+"""GPU parity: bs_spec_sample against the oracle's accept/reject + residual/bonus sampling (App. A)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import philox
+from oracle.sampling import spec_sample_batch, draw_from_logits, softmax_t
+from paper_2505_15141_amd import synth
+from helpers import judge_sampling, MARGIN
+
+pytestmark = pytest.mark.gpu
+
+
+def bs():
+    from paper_2505_15141_amd import binding
+    return binding
+
+
+def draft_tokens_from(q_logits, seed, temperature=1.0):
+    rng = np.random.default_rng(seed)
+    B, gamma, _ = q_logits.shape
+    out = np.zeros((B, gamma), dtype=np.int32)
+    for b in range(B):
+        for i in range(gamma):
+            out[b, i] = draw_from_logits(q_logits[b, i], rng.random(), temperature)[0]
+    return out
+
+
+def run_case(B, gamma, V, dtype, seed, temperature=1.0, noise=0.5, use_philox=False):
+    t, q = synth.make_sampling_logits(B, gamma, V, seed, 2.0, noise, dtype)
+    toks = draft_tokens_from(q, seed + 1, temperature)
+    if use_philox:
+        pseed, rnd = 12345 + seed, 7
+        u = np.zeros((B, gamma + 1))
+        for b in range(B):
+            for i in range(gamma):
+                u[b, i] = philox.accept_uniform(pseed, b, rnd, i)
+            u[b, gamma] = philox.final_uniform(pseed, b, rnd)
+    else:
+        u = synth.make_uniforms(B, gamma, seed + 2).astype(np.float64)
+    acc_o, tok_o, infos = spec_sample_batch(t.astype(np.float64), q.astype(np.float64), toks, u, temperature)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dt = torch.from_numpy(t).cuda().to(td).contiguous()
+    dq = torch.from_numpy(q).cuda().to(td).contiguous() if gamma > 0 else torch.zeros(1, dtype=td, device="cuda")
+    dtok = torch.from_numpy(toks).cuda() if gamma > 0 else torch.zeros(1, dtype=torch.int32, device="cuda")
+    if use_philox:
+        acc, tok, mg = bs().spec_sample(dt, dq, dtok, temperature, None, pseed, rnd, want_margins=gamma > 0)
+    else:
+        du = torch.from_numpy(u.astype(np.float32)).cuda()
+        acc, tok, mg = bs().spec_sample(dt, dq, dtok, temperature, du, want_margins=gamma > 0)
+    torch.cuda.synchronize()
+    acc, tok = acc.cpu().numpy(), tok.cpu().numpy()
+    compared, excused = judge_sampling(infos, u[:, gamma], acc, tok)
+    if gamma > 0:
+        mg = mg.cpu().numpy()
+        for b, r in enumerate(infos):              # margins of the positions the oracle tested
+            k = ~np.isnan(r["margins"])
+            assert np.allclose(mg[b][k], r["margins"][k], atol=2e-4), (b, mg[b], r["margins"])
+    assert tok.min() >= 0 and tok.max() < V and acc.min() >= 0 and acc.max() <= gamma
+    return compared, excused, acc_o
+
+
+def test_full_size_sampling_workload_bf16():
+    # B=64, gamma=8, V=32000, bf16 logits: the stand-alone sampling configuration, element by element
+    compared, excused, acc_o = run_case(64, 8, 32000, "bf16", seed=1)
+    assert compared >= 56
+    # acceptance statistics of the generator: alpha = 2*Phi(-sigma/2) = 0.803 at sigma 0.5 -> E[y] = 4.37
+    assert 2.4 < acc_o.mean() + 1 < 6.4
+
+
+@pytest.mark.parametrize("B,gamma,V,dtype", [
+    (3, 3, 1, "f32"), (5, 2, 7, "f32"), (4, 4, 513, "bf16"), (2, 1, 4097, "f32"), (3, 5, 4104, "bf16"),
+    (2, 3, 16384, "f32"), (2, 2, 40000, "bf16"), (2, 2, 32768, "bf16"), (1, 8, 128256, "bf16"), (2, 2, 128256, "f32"),
+    (7, 0, 1000, "bf16"), (1, 1, 8, "bf16"), (130, 4, 520, "f32")])
+def test_ragged_and_edge_shapes(B, gamma, V, dtype):
+    run_case(B, gamma, V, dtype, seed=B * 1000 + gamma * 10 + V % 7)
+
+
+def test_philox_uniforms_generated_in_kernel():
+    compared, _, _ = run_case(16, 4, 2048, "bf16", seed=5, use_philox=True)
+    assert compared >= 12
+    run_case(3, 6, 32000, "f32", seed=6, use_philox=True)
+
+
+@pytest.mark.parametrize("temperature", [0.5, 1.7])
+def test_temperature(temperature):
+    run_case(8, 4, 1024, "bf16", seed=9, temperature=temperature)
+
+
+def test_low_and_high_acceptance_regimes():
+    _, _, lo = run_case(32, 8, 8192, "bf16", seed=11, noise=1.5)
+    _, _, hi = run_case(32, 8, 8192, "bf16", seed=12, noise=0.2)
+    assert lo.mean() < hi.mean()
+
+
+def test_identical_models_accept_everything_and_bonus_follows_target():
+    B, gamma, V = 6, 5, 3000
+    t, _ = synth.make_sampling_logits(B, gamma, V, 3, dtype="f32")
+    q = t[:, :gamma].copy()
+    toks = draft_tokens_from(q, 4)
+    u = synth.make_uniforms(B, gamma, 5)
+    u[:, :gamma] = 1.0                                             # hardest case: r = 1 must still accept
+    acc, tok, _ = bs().spec_sample(torch.from_numpy(t).cuda(), torch.from_numpy(q).cuda(), torch.from_numpy(toks).cuda(),
+                                   1.0, torch.from_numpy(u).cuda())
+    assert (acc.cpu().numpy() == gamma).all()
+    _, tok_o, infos = spec_sample_batch(t.astype(np.float64), q.astype(np.float64), toks, u.astype(np.float64))
+    judge_sampling(infos, u[:, gamma].astype(np.float64), acc.cpu().numpy(), tok.cpu().numpy())
+
+
+def test_disjoint_supports_reject_immediately():
+    B, gamma, V = 4, 3, 640
+    t = np.full((B, gamma + 1, V), -60.0, dtype=np.float32); q = np.full((B, gamma, V), -60.0, dtype=np.float32)
+    t[:, :, :100] = 0.0; q[:, :, 300:400] = 0.0
+    toks = np.full((B, gamma), 333, dtype=np.int32)
+    u = synth.make_uniforms(B, gamma, 8)
+    acc, tok, _ = bs().spec_sample(torch.from_numpy(t).cuda(), torch.from_numpy(q).cuda(), torch.from_numpy(toks).cuda(),
+                                   1.0, torch.from_numpy(u).cuda())
+    assert (acc.cpu().numpy() == 0).all() and (tok.cpu().numpy() < 100).all()
+    assert np.array_equal(tok.cpu().numpy(), np.floor(u[:, gamma].astype(np.float64) * 100).astype(np.int32))
+
+
+def test_empty_batch_and_bad_arguments():
+    b = bs()
+    z = torch.zeros(16, device="cuda")
+    assert b.lib.bs_spec_sample(b.ptr(z), b.ptr(z), b.ptr(z), 0, 3, 100, 0, 1.0, None, 0, 0, b.ptr(z), b.ptr(z), None,
+                                b.ptr(z), 64, None) == 0
+    assert b.lib.bs_spec_sample(b.ptr(z), b.ptr(z), b.ptr(z), 1, 3, 100, 0, 1.0, None, 0, 0, b.ptr(z), b.ptr(z), None,
+                                b.ptr(z), 8, None) == -4        # workspace too small
+    assert "workspace" in b.last_error()
+
+
+def test_output_law_on_device_matches_target_distribution():
+    # Prop. 3.1 through the kernel: many independent sequences with the same (p, q) rows; the first emitted
+    # token must follow p_1.  Draft tokens come from q with host uniforms, so the whole chain is exercised.
+    V, gamma, B = 12, 3, 20000
+    rng = np.random.default_rng(21)
+    p = rng.normal(0, 1.0, V).astype(np.float32); q = (p + rng.normal(0, 0.8, V)).astype(np.float32)
+    pq = softmax_t(q.astype(np.float64)); pp = softmax_t(p.astype(np.float64))
+    toks = rng.choice(V, size=(B, gamma), p=pq).astype(np.int32)
+    t = np.broadcast_to(p, (B, gamma + 1, V)).copy(); qq = np.broadcast_to(q, (B, gamma, V)).copy()
+    acc, tok, _ = bs().spec_sample(torch.from_numpy(t).cuda(), torch.from_numpy(qq).cuda(), torch.from_numpy(toks).cuda(),
+                                   1.0, None, seed=99, round=3)
+    acc, tok = acc.cpu().numpy(), tok.cpu().numpy()
+    first = np.where(acc > 0, toks[:, 0], tok)
+    counts = np.bincount(first, minlength=V)
+    chi2 = float(np.sum((counts - B * pp) ** 2 / (B * pp)))
+    assert chi2 < 45.0                                             # chi^2_11 at ~1e-5
+    alpha = float(np.minimum(pp, pq).sum())
+    assert abs((acc + 1).mean() - (1 - alpha ** (gamma + 1)) / (1 - alpha)) < 0.05
