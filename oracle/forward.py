@@ -12,9 +12,11 @@ base 10000 rotating the interleaved pairs (2j, 2j+1) of each head by
 pos * base^(-2j/head_dim); attention scale 1/sqrt(head_dim).
 
 Weights are [out_features, in_features] matrices: y = x @ W.T.
-`storage` names the dtype in which the GPU path stores GEMM operands, K/V and
-rotated queries ("f32" = no rounding here, "bf16" = round-to-nearest-even to
-bfloat16 at exactly those storage points).  All arithmetic is fp64.
+`storage` names the dtype of the KV cache: "f32" = no rounding here, "bf16" =
+the rotated keys and the values are rounded to the nearest bfloat16 (ties to
+even) before they are used, because that is what a bf16 cache holds.  Weights
+arrive already on the bf16 grid.  Nothing else is rounded: activations,
+queries, scores and accumulations are exact to fp64.
 """
 import numpy as np
 
@@ -76,11 +78,11 @@ def forward(cfg, W, tokens, storage="f32", return_hidden=False):
     causal = np.tril(np.ones((n, n), dtype=bool))
     for l in range(cfg["n_layers"]):
         g = lambda name: f64(W[f"l{l}.{name}"])
-        h = _store(rmsnorm(x, g("attn_norm"), eps), storage)
+        h = rmsnorm(x, g("attn_norm"), eps)
         q = (h @ g("wq").T).reshape(n, H, hd)
         k = (h @ g("wk").T).reshape(n, KVH, hd)
         v = (h @ g("wv").T).reshape(n, KVH, hd)
-        q = _store(rope(q, pos, base), storage)
+        q = rope(q, pos, base)
         k = _store(rope(k, pos, base), storage)
         v = _store(v, storage)
         att = np.empty((n, H, hd))
@@ -92,12 +94,12 @@ def forward(cfg, W, tokens, storage="f32", return_hidden=False):
             p = np.exp(s)
             p = p / p.sum(axis=-1, keepdims=True)
             att[:, head, :] = p @ v[:, kvh, :]
-        att = _store(att.reshape(n, H * hd), storage)
+        att = att.reshape(n, H * hd)
         x = x + att @ g("wo").T
-        h = _store(rmsnorm(x, g("ffn_norm"), eps), storage)
-        a = _store(silu(h @ g("w_gate").T) * (h @ g("w_up").T), storage)
+        h = rmsnorm(x, g("ffn_norm"), eps)
+        a = silu(h @ g("w_gate").T) * (h @ g("w_up").T)
         x = x + a @ g("w_down").T
-    h = _store(rmsnorm(x, f64(W["final_norm"]), eps), storage)
+    h = rmsnorm(x, f64(W["final_norm"]), eps)
     logits = h @ f64(W["lm_head"]).T
     if return_hidden:
         return logits, x

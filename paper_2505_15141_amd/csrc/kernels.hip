@@ -3,11 +3,12 @@
 //
 //   prep        positions, clamped tokens, RoPE cos/sin table, overflow status
 //   embed       token embedding -> fp32 residual stream
-//   rmsnorm     fp32 residual -> normalised activations in the storage dtype
+//   rmsnorm     completes the fp32 residual from pending split-K partials, normalises it
 //   gemm        y = x W^T: bf16 weights streamed once from HBM through MFMA 16x16x32 tiles (the
 //               contraction is skinny: M = B*(gamma+1) rows, so it is bound by weight bandwidth),
-//               fp32 variant for the fp32 plumbing configuration
-//   rope_kv     rotate q and k, write k/v into the cache
+//               split-K partials out; fp32 variant for the fp32 plumbing configuration
+//   swiglu      sums gate/up partials, applies silu(g)*u
+//   rope_kv     sums q/k/v partials, rotates q and k, writes k/v into the cache
 //   attention   q_len causal query rows per head against the contiguous KV cache, split along the
 //               keys with online softmax; merge kernel combines the splits
 #include <math.h>
@@ -77,227 +78,254 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
     for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)m * d + i] = to_f(row[i]);
 }
 
-// ---- RMSNorm ------------------------------------------------------------------------------------
-// out row r takes input row (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out
+// ---- activation format ---------------------------------------------------------------------------
+// fp32 models keep activations as float [M, K].  bf16 models keep them as TWO bf16 planes hi, lo with
+// hi = bf16(v), lo = bf16(v - hi): the MFMA GEMM multiplies the weight tile with both planes, so the
+// activations enter the contraction with ~16 significant bits while the weights stream as bf16.  The
+// matrix cores have a 20x surplus over the weight bandwidth at these row counts, so the second plane is free.
+template <typename T> struct Act;
+template <> struct Act<float> {
+    static __device__ __forceinline__ void store(void* base, size_t plane, size_t idx, float v) {
+        reinterpret_cast<float*>(base)[idx] = v;
+    }
+};
+template <> struct Act<uint16_t> {
+    static __device__ __forceinline__ void store(void* base, size_t plane, size_t idx, float v) {
+        const uint16_t hi = from_f<uint16_t>(v);
+        const uint16_t lo = from_f<uint16_t>(v - to_f(hi));
+        reinterpret_cast<uint16_t*>(base)[idx] = hi;
+        reinterpret_cast<uint16_t*>(base)[plane + idx] = lo;
+    }
+};
+
+// ---- RMSNorm (+ pending split-K partials of the previous projection) -----------------------------
+// out row r takes input row src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out
 // (rows_out = rows_in: identity; rows_out < rows_in: the trailing rows of every sequence).
+// If pend != null the residual row is first completed: x[src] += sum_s pend[s][src][:], and written back.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      int d, float eps, int rows_in, int rows_out,
-                                                      T* __restrict__ out) {
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ pend, int pend_ks,
+                                                      size_t pend_stride, const float* __restrict__ gain, int d,
+                                                      float eps, int rows_in, int rows_out, size_t plane,
+                                                      void* __restrict__ out) {
     __shared__ float red[4];
     const int r = blockIdx.x;
     const int src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out;
-    const float* row = x + (size_t)src * d;
+    float* row = x + (size_t)src * d;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) { const float v = row[i]; ss += v * v; }
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = row[i];
+        if (pend) {
+            for (int s = 0; s < pend_ks; ++s) v += pend[(size_t)s * pend_stride + (size_t)src * d + i];
+            row[i] = v;
+        }
+        ss += v * v;
+    }
     ss = wsum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     const float tot = red[0] + red[1] + red[2] + red[3];
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) out[(size_t)r * d + i] = from_f<T>(row[i] * scale * gain[i]);
+    for (int i = threadIdx.x; i < d; i += 256) Act<T>::store(out, plane, (size_t)r * d + i, row[i] * scale * gain[i]);
 }
 
-// ---- GEMM, bf16 MFMA, weight streaming -------------------------------------------------------------
-// y[m][n] = sum_k x[m][k] * W[n][k].  One workgroup = 4 wavefronts owns 16 output columns n (16 weight
-// rows) and every one of the M <= 16*MT rows; the wavefronts split K in interleaved 128-element chunks
-// and reduce through LDS.  Weight tile -> MFMA A operand (lane = (row l%16, k-slot l/16), 16-byte loads
-// straight from HBM), activations -> B operand (L2-resident).  Up to three weight segments stacked along
-// n (fused q/k/v projection) or a gate/up pair with the SwiGLU epilogue.
-enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SWIGLU = 2 };
+// ---- SwiGLU over split-K partials: act = silu(sum_s g) * sum_s u, columns [0,ff) gate, [ff,2ff) up ------
+template <typename T>
+__global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_stride, int M, int ff, size_t plane,
+                              void* __restrict__ out) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)M * ff) return;
+    const size_t m = idx / ff, j = idx % ff;
+    float g = 0.f, u = 0.f;
+    for (int s = 0; s < ks; ++s) {
+        g += part[(size_t)s * ks_stride + m * 2 * ff + j];
+        u += part[(size_t)s * ks_stride + m * 2 * ff + ff + j];
+    }
+    Act<T>::store(out, plane, idx, g / (1.0f + __expf(-g)) * u);
+}
 
+// ---- GEMM, bf16 weights streamed through MFMA -------------------------------------------------------
+// part[ks][m][n] = sum over the K range of split ks of x[m][k] * W[n][k].
+// grid (ceil(N/64), KS), 4 wavefronts; wavefront w owns weight rows n0+16w .. n0+16w+15 (MFMA A operand:
+// lane = (row l%16, k-slot l/16), one 16-byte load per 32-wide k slice, straight from HBM into registers,
+// a whole stage of KC columns in flight per wavefront plus the next stage prefetched).  The activation
+// slice [M, KC] of both planes is staged once per workgroup in LDS (rows padded by 16 bytes so that the
+// 16 rows read by one ds_read_b128 phase fall into distinct banks) and shared by the four wavefronts.
+// Each wavefront owns its output rows, so no cross-wavefront reduction is needed; split-K partials are
+// summed by the consumer kernel.
 __device__ __forceinline__ uint4 ldg16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
-template <int MT, int EPI>
+template <int MT, int KC>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
-    constexpr int NACC = (EPI == EPI_SWIGLU) ? 2 : 1;
-    __shared__ float red[4][NACC * MT][64][4];
+    constexpr int ROW = KC + 8;                       // padded LDS row (bf16 elements)
+    constexpr int NSL = KC / 32;                      // k slices per stage
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][MT * 16][ROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    // weight rows of this tile (segment lookup; tiles never straddle segments because every segment's row
-    // count is a multiple of 16 - checked on the host)
-    const uint16_t* w0;
-    const uint16_t* w1 = nullptr;
+    const int n0 = blockIdx.x * 64 + wave * 16;
+    const uint16_t* wrow;
     {
         int n = n0 + li;
         if (n >= a.N) n = a.N - 1;
-        if (EPI == EPI_SWIGLU) {
-            w0 = reinterpret_cast<const uint16_t*>(a.w[0]) + (size_t)n * a.K;
-            w1 = reinterpret_cast<const uint16_t*>(a.w[1]) + (size_t)n * a.K;
-        } else {
-            int seg = 0, local = n;
-            if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
-            w0 = reinterpret_cast<const uint16_t*>(a.w[seg]) + (size_t)local * a.K;
-        }
+        int seg = 0, local = n;
+        if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+        wrow = reinterpret_cast<const uint16_t*>(a.w[seg]) + (size_t)local * a.K;
     }
-    const uint16_t* x = reinterpret_cast<const uint16_t*>(a.x);
-    f32x4 acc[NACC][MT];
-#pragma unroll
-    for (int s = 0; s < NACC; ++s)
-#pragma unroll
-        for (int t = 0; t < MT; ++t) acc[s][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
+    const uint16_t* xl = xh + a.x_plane;
+    // stages of this split
+    const int nstages = (a.K + KC - 1) / KC;
+    const int ks = blockIdx.y, KS = gridDim.y;
+    const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
 
-    const int nchunks = (a.K + 127) / 128;
-    for (int c = wave; c < nchunks; c += 4) {
-        const int kb = c * 128 + lq * 8;
-        uint4 wa[4], wb[4];
+    f32x4 acc[MT];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 wcur[NSL], wnext[NSL];
+    auto load_stage = [&](int st, uint4 (&dst)[NSL]) {
+        const int kb = st * KC + lq * 8;
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) {
             const int k = kb + j * 32;
-            const bool ok = k < a.K;                      // K % 8 == 0 (host check): whole 16-byte groups
-            wa[j] = ok ? ldg16(w0 + k) : make_uint4(0, 0, 0, 0);
-            if (EPI == EPI_SWIGLU) wb[j] = ok ? ldg16(w1 + k) : make_uint4(0, 0, 0, 0);
+            dst[j] = (st < st_end && k < a.K) ? ldg16(wrow + k) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    load_stage(st_begin, wcur);
+    for (int st = st_begin; st < st_end; ++st) {
+        load_stage(st + 1, wnext);                    // prefetch (all zero past the end)
+        __syncthreads();                              // previous stage's LDS reads are done
+        // stage the activation slice: 16-byte chunks, rows >= M and columns >= K are zero
+        constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
+        for (int c = threadIdx.x; c < CHUNKS; c += 256) {
+            const int plane = c / (MT * 16 * (KC / 8));
+            const int rem = c % (MT * 16 * (KC / 8));
+            const int m = rem / (KC / 8), kc = (rem % (KC / 8)) * 8;
+            const int k = st * KC + kc;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < a.M && k < a.K) v = ldg16((plane ? xl : xh) + (size_t)m * a.K + k);
+            *reinterpret_cast<uint4*>(&xs[plane][m][kc]) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) {
+            const bf16x8 A = __builtin_bit_cast(bf16x8, wcur[j]);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const uint4 bh = *reinterpret_cast<const uint4*>(&xs[0][t * 16 + li][j * 32 + lq * 8]);
+                const uint4 bl = *reinterpret_cast<const uint4*>(&xs[1][t * 16 + li][j * 32 + lq * 8]);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bh), acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bl), acc[t], 0, 0, 0);
+            }
         }
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            const int m = t * 16 + li;
-            uint4 xv[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = kb + j * 32;
-                xv[j] = (m < a.M && k < a.K) ? ldg16(x + (size_t)m * a.K + k) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const bf16x8 B = __builtin_bit_cast(bf16x8, xv[j]);
-                acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa[j]), B, acc[0][t], 0, 0, 0);
-                if (EPI == EPI_SWIGLU)
-                    acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wb[j]), B, acc[1][t], 0, 0, 0);
-            }
-        }
+        for (int j = 0; j < NSL; ++j) wcur[j] = wnext[j];
     }
-#pragma unroll
-    for (int s = 0; s < NACC; ++s)
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) red[wave][s * MT + t][lane][e] = acc[s][t][e];
-    __syncthreads();
-    // thread -> (e = wave, lane): D[n = 4*(lane/16)+e][m = lane%16] of every m-tile
-    const int e = wave;
-    const int n = n0 + 4 * lq + e;
+    // D[n = n0 + 4*lq + e][m = 16t + li]: four consecutive n per lane -> one 16-byte store
+    float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride;
+    const int nb = n0 + 4 * lq;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         const int m = t * 16 + li;
-        float v0 = red[0][t][lane][e] + red[1][t][lane][e] + red[2][t][lane][e] + red[3][t][lane][e];
-        if (m >= a.M || n >= a.N) continue;
-        if (EPI == EPI_SWIGLU) {
-            const float up = red[0][MT + t][lane][e] + red[1][MT + t][lane][e] + red[2][MT + t][lane][e] + red[3][MT + t][lane][e];
-            const float act = v0 / (1.0f + __expf(-v0)) * up;
-            reinterpret_cast<uint16_t*>(a.out)[(size_t)m * a.ldo + n] = from_f<uint16_t>(act);
-        } else if (EPI == EPI_ADD) {
-            float* o = reinterpret_cast<float*>(a.out) + (size_t)m * a.ldo + n;
-            *o += v0;
+        if (m >= a.M) continue;
+        float* o = out + (size_t)m * a.ldo + nb;
+        if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
+            *reinterpret_cast<float4*>(o) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
         } else {
-            reinterpret_cast<float*>(a.out)[(size_t)m * a.ldo + n] = v0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (nb + e < a.N) o[e] = acc[t][e];
         }
     }
 }
 
-// ---- GEMM, fp32 (plumbing configuration) ----------------------------------------------------------
-// One wavefront per output column n, lanes stride K, 8 rows of x at a time.
-template <int EPI>
+// ---- GEMM, fp32 (plumbing configuration): one wavefront per output column, lanes stride K ----------
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = blockIdx.x * 4 + wave;
     if (n >= a.N) return;
-    const float* w0;
-    const float* w1 = nullptr;
-    if (EPI == EPI_SWIGLU) {
-        w0 = reinterpret_cast<const float*>(a.w[0]) + (size_t)n * a.K;
-        w1 = reinterpret_cast<const float*>(a.w[1]) + (size_t)n * a.K;
-    } else {
-        int seg = 0, local = n;
-        if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
-        w0 = reinterpret_cast<const float*>(a.w[seg]) + (size_t)local * a.K;
-    }
+    int seg = 0, local = n;
+    if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+    const float* w0 = reinterpret_cast<const float*>(a.w[seg]) + (size_t)local * a.K;
     const float* x = reinterpret_cast<const float*>(a.x);
     for (int m0 = 0; m0 < a.M; m0 += 8) {
-        float acc0[8], acc1[8];
+        float acc[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) { acc0[r] = 0.f; acc1[r] = 0.f; }
+        for (int r = 0; r < 8; ++r) acc[r] = 0.f;
         for (int k = lane; k < a.K; k += 64) {
             const float wv = w0[k];
-            const float uv = (EPI == EPI_SWIGLU) ? w1[k] : 0.f;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const float xv = (m0 + r < a.M) ? x[(size_t)(m0 + r) * a.K + k] : 0.f;
-                acc0[r] = fmaf(xv, wv, acc0[r]);
-                if (EPI == EPI_SWIGLU) acc1[r] = fmaf(xv, uv, acc1[r]);
+                acc[r] = fmaf(xv, wv, acc[r]);
             }
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const float v0 = wsum(acc0[r]);
-            const float v1 = (EPI == EPI_SWIGLU) ? wsum(acc1[r]) : 0.f;
-            if (lane == 0 && m0 + r < a.M) {
-                float* o = reinterpret_cast<float*>(a.out) + (size_t)(m0 + r) * a.ldo + n;
-                if (EPI == EPI_SWIGLU) *o = v0 / (1.0f + __expf(-v0)) * v1;
-                else if (EPI == EPI_ADD) *o += v0;
-                else *o = v0;
-            }
+            const float v = wsum(acc[r]);
+            if (lane == 0 && m0 + r < a.M) reinterpret_cast<float*>(a.out)[(size_t)(m0 + r) * a.ldo + n] = v;
         }
     }
 }
 
-template <int EPI>
-static int launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
-    const dim3 grid((a.N + 15) / 16), block(256);
-    const int mt = (a.M + 15) / 16;
-    if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, EPI>), grid, block, 0, s, a);
-    else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, EPI>), grid, block, 0, s, a);
-    else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, EPI>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<6, EPI>), grid, block, 0, s, a);
-    BS_LAUNCH_CHECK();
-    return BS_OK;
+// Split-K factor: enough workgroups to cover the chip a few times, at least two stages per split.
+int gemm_splits(int dtype, int N, int K) {
+    if (dtype != BS_BF16) return 1;
+    const int tiles = (N + 63) / 64;
+    const int stages = (K + 255) / 256;
+    int ks = (768 + tiles - 1) / tiles;
+    if (ks > stages / 2) ks = stages / 2;
+    if (ks > 16) ks = 16;
+    if (ks < 1) ks = 1;
+    return ks;
 }
 
-int launch_gemm(int dtype, int epi, GemmArgs a, hipStream_t s) {
+int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return BS_OK;
     if (dtype == BS_F32) {
-        const dim3 grid((a.N + 3) / 4), block(256);
-        if (epi == EPI_STORE) hipLaunchKernelGGL((gemm_f32_kernel<EPI_STORE>), grid, block, 0, s, a);
-        else if (epi == EPI_ADD) hipLaunchKernelGGL((gemm_f32_kernel<EPI_ADD>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gemm_f32_kernel<EPI_SWIGLU>), grid, block, 0, s, a);
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3((a.N + 3) / 4), dim3(256), 0, s, a);
         BS_LAUNCH_CHECK();
         return BS_OK;
     }
-    // bf16: at most GEMM_MAX_ROWS rows per launch (accumulators live in registers)
-    const size_t xrow = (size_t)a.K * 2;
-    const size_t orow = (size_t)a.ldo * (epi == EPI_SWIGLU ? 2 : 4);
+    // bf16: at most GEMM_MAX_ROWS rows per launch (accumulators live in registers, the slice in LDS)
     for (int m0 = 0; m0 < a.M; m0 += GEMM_MAX_ROWS) {
         GemmArgs c = a;
         c.M = (a.M - m0 < GEMM_MAX_ROWS) ? a.M - m0 : GEMM_MAX_ROWS;
-        c.x = reinterpret_cast<const char*>(a.x) + (size_t)m0 * xrow;
-        c.out = reinterpret_cast<char*>(a.out) + (size_t)m0 * orow;
-        int rc;
-        if (epi == EPI_STORE) rc = launch_gemm_bf16<EPI_STORE>(c, s);
-        else if (epi == EPI_ADD) rc = launch_gemm_bf16<EPI_ADD>(c, s);
-        else rc = launch_gemm_bf16<EPI_SWIGLU>(c, s);
-        if (rc != BS_OK) return rc;
+        c.x = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m0 * a.K;
+        c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
+        const dim3 grid((a.N + 63) / 64, a.KS), block(256);
+        const int mt = (c.M + 15) / 16;
+        if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256>), grid, block, 0, s, c);
+        else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 256>), grid, block, 0, s, c);
+        else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 128>), grid, block, 0, s, c);
+        else hipLaunchKernelGGL((gemm_bf16_kernel<6, 128>), grid, block, 0, s, c);
+        BS_LAUNCH_CHECK();
     }
     return BS_OK;
 }
 
 // ---- RoPE + KV append -----------------------------------------------------------------------------
-// grid (M, H + 2*KVH); thread = one rotation pair.  qkv row layout: [q heads | k heads | v heads].
+// grid (M, H + 2*KVH); thread = one rotation pair.  Row layout of the projection: [q heads | k heads | v heads],
+// given as split-K partials that are summed here.  q stays fp32; k and v are rounded to the cache dtype.
 template <typename T>
-__global__ void rope_kv_kernel(const float* __restrict__ qkv, const int32_t* __restrict__ pos,
+__global__ void rope_kv_kernel(const float* __restrict__ part, int ks, size_t ks_stride, const int32_t* __restrict__ pos,
                                const float2* __restrict__ rope, int q_len, int H, int KVH, int hd, int max_len,
-                               T* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+                               float* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
     const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;       // i < hd/2
     const int p = pos[m];
     const int b = m / q_len;
     const int ld = (H + 2 * KVH) * hd;
-    const float* src = qkv + (size_t)m * ld + (size_t)head * hd;
-    const float x0 = src[2 * i], x1 = src[2 * i + 1];
+    const float* src = part + (size_t)m * ld + (size_t)head * hd;
+    float x0 = 0.f, x1 = 0.f;
+    for (int s = 0; s < ks; ++s) {
+        const float2 v = *reinterpret_cast<const float2*>(src + (size_t)s * ks_stride + 2 * i);
+        x0 += v.x; x1 += v.y;
+    }
     if (head < H + KVH) {
         const float2 cs = rope[(size_t)m * (hd / 2) + i];
         const float r0 = x0 * cs.x - x1 * cs.y, r1 = x0 * cs.y + x1 * cs.x;
         if (head < H) {
-            T* dst = q_out + (size_t)m * H * hd + (size_t)head * hd;
-            dst[2 * i] = from_f<T>(r0); dst[2 * i + 1] = from_f<T>(r1);
+            float* dst = q_out + (size_t)m * H * hd + (size_t)head * hd;
+            dst[2 * i] = r0; dst[2 * i + 1] = r1;
         } else if (p >= 0) {
             T* dst = k_cache + (((size_t)b * KVH + (head - H)) * max_len + p) * hd;
             dst[2 * i] = from_f<T>(r0); dst[2 * i + 1] = from_f<T>(r1);
@@ -332,7 +360,7 @@ __device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float out[8])
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void attn_kernel(const T* __restrict__ q, const T* __restrict__ k_cache,
+__global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, const T* __restrict__ k_cache,
                                                    const T* __restrict__ v_cache, const int32_t* __restrict__ pos,
                                                    int q_len, int H, int KVH, int hd, int max_len, float scale,
                                                    float* __restrict__ part) {
@@ -367,7 +395,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const T* __restrict__ q, cons
         __syncthreads();
         for (int idx = threadIdx.x; idx < ATT_RB * hd; idx += 256) {
             const int r = idx / hd, d = idx % hd;
-            qs[r][d] = (r < nr) ? to_f(q[((size_t)(m_first + r0 + r) * H + h) * hd + d]) * scale : 0.f;
+            qs[r][d] = (r < nr) ? q[((size_t)(m_first + r0 + r) * H + h) * hd + d] * scale : 0.f;
         }
         __syncthreads();
         float mrow[ATT_RB], lrow[ATT_RB], o0[ATT_RB], o1[ATT_RB];
@@ -456,7 +484,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const T* __restrict__ q, cons
 
 // grid (M*H), threads hd: combine the splits, normalise, store in the storage dtype.
 template <typename T>
-__global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, T* __restrict__ out) {
+__global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, size_t plane, void* __restrict__ out) {
     const size_t mh = blockIdx.x;
     const int d = threadIdx.x;
     const size_t pstride = (size_t)hd + 2;
@@ -470,7 +498,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
         l += base[s * pstride + 1] * f;
         o += base[s * pstride + 2 + d] * f;
     }
-    out[mh * hd + d] = from_f<T>(l > 0.f ? o / l : 0.f);
+    Act<T>::store(out, plane, mh * hd + d, l > 0.f ? o / l : 0.f);
 }
 
 // ---- launchers -----------------------------------------------------------------------------------
@@ -492,46 +520,57 @@ int launch_embed(int dtype, const int32_t* tok, const void* embed, int M, int d,
     return BS_OK;
 }
 
-int launch_rmsnorm(int dtype, const float* x, const float* gain, int d, float eps, int n_seq, int rows_in,
-                   int rows_out, void* out, hipStream_t s) {
+int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d,
+                   float eps, int n_seq, int rows_in, int rows_out, size_t plane, void* out, hipStream_t s) {
     const int rows = n_seq * rows_out;
     if (rows <= 0) return BS_OK;
     if (dtype == BS_BF16)
-        hipLaunchKernelGGL((rmsnorm_kernel<uint16_t>), dim3(rows), dim3(256), 0, s, x, gain, d, eps, rows_in, rows_out, (uint16_t*)out);
+        hipLaunchKernelGGL((rmsnorm_kernel<uint16_t>), dim3(rows), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
     else
-        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(256), 0, s, x, gain, d, eps, rows_in, rows_out, (float*)out);
+        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
 
-int launch_rope_kv(int dtype, const float* qkv, const int32_t* pos, const float2* rope, int M, int q_len, int H,
-                   int KVH, int hd, int max_len, void* q_out, void* k_cache, void* v_cache, hipStream_t s) {
+int launch_swiglu(int dtype, const float* part, int ks, size_t ks_stride, int M, int ff, size_t plane, void* out,
+                  hipStream_t s) {
+    const size_t n = (size_t)M * ff;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (dtype == BS_BF16) hipLaunchKernelGGL((swiglu_kernel<uint16_t>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out);
+    else hipLaunchKernelGGL((swiglu_kernel<float>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const int32_t* pos, const float2* rope, int M,
+                   int q_len, int H, int KVH, int hd, int max_len, float* q_out, void* k_cache, void* v_cache,
+                   hipStream_t s) {
     const dim3 grid(M, H + 2 * KVH), block(hd / 2);
     if (dtype == BS_BF16)
-        hipLaunchKernelGGL((rope_kv_kernel<uint16_t>), grid, block, 0, s, qkv, pos, rope, q_len, H, KVH, hd, max_len,
-                           (uint16_t*)q_out, (uint16_t*)k_cache, (uint16_t*)v_cache);
+        hipLaunchKernelGGL((rope_kv_kernel<uint16_t>), grid, block, 0, s, part, ks, ks_stride, pos, rope, q_len, H, KVH, hd,
+                           max_len, q_out, (uint16_t*)k_cache, (uint16_t*)v_cache);
     else
-        hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, qkv, pos, rope, q_len, H, KVH, hd, max_len,
-                           (float*)q_out, (float*)k_cache, (float*)v_cache);
+        hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, part, ks, ks_stride, pos, rope, q_len, H, KVH, hd,
+                           max_len, q_out, (float*)k_cache, (float*)v_cache);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
 
-int launch_attention(int dtype, const void* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
-                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, void* out,
+int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
+                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,
                      hipStream_t s) {
     const float scale = 1.0f / sqrtf((float)hd);
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
-        hipLaunchKernelGGL((attn_kernel<uint16_t>), grid, block, 0, s, (const uint16_t*)q, (const uint16_t*)k_cache,
+        hipLaunchKernelGGL((attn_kernel<uint16_t>), grid, block, 0, s, q, (const uint16_t*)k_cache,
                            (const uint16_t*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);
         BS_LAUNCH_CHECK();
-        hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, (uint16_t*)out);
+        hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {
-        hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, (const float*)q, (const float*)k_cache,
+        hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
                            (const float*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);
         BS_LAUNCH_CHECK();
-        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, (float*)out);
+        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     }
     BS_LAUNCH_CHECK();
     return BS_OK;

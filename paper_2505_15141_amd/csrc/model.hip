@@ -95,14 +95,21 @@ static int attn_splits(int B, int H, int max_len) {
 }
 
 struct FwdWs {
-    int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* qkv; void* q; void* att; void* act;
-    float* part; size_t total;
+    int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* q; void* att; void* act;
+    float *part_qkv, *part_o, *part_gu, *part_d, *part_attn;
+    int ks_qkv, ks_o, ks_gu, ks_d;
+    size_t total;
 };
 
+// Activations take 4 bytes per element in either dtype: float, or a bf16 (hi, lo) pair of planes.
 static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* base) {
     FwdWs w;
-    const size_t M = (size_t)B * q_len, es = esize(c.dtype);
+    const size_t M = (size_t)B * q_len;
     const size_t nq = (size_t)c.n_heads * c.head_dim, nkv = (size_t)c.n_kv_heads * c.head_dim;
+    w.ks_qkv = gemm_splits(c.dtype, (int)(nq + 2 * nkv), c.d_model);
+    w.ks_o = gemm_splits(c.dtype, c.d_model, (int)nq);
+    w.ks_gu = gemm_splits(c.dtype, 2 * c.d_ff, c.d_model);
+    w.ks_d = gemm_splits(c.dtype, c.d_model, c.d_ff);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return base ? base + o : (char*)nullptr; };
     w.status = (int32_t*)take(256);
@@ -110,12 +117,15 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.tok = (int32_t*)take(M * 4);
     w.rope = (float2*)take(M * (c.head_dim / 2) * 8);
     w.x = (float*)take(M * c.d_model * 4);
-    w.h = take(M * c.d_model * es);
-    w.qkv = (float*)take(M * (nq + 2 * nkv) * 4);
-    w.q = take(M * nq * es);
-    w.att = take(M * nq * es);
-    w.act = take(M * c.d_ff * es);
-    w.part = (float*)take(M * c.n_heads * attn_splits(B, c.n_heads, max_len) * (size_t)(c.head_dim + 2) * 4);
+    w.h = take(M * c.d_model * 4);
+    w.q = (float*)take(M * nq * 4);
+    w.att = take(M * nq * 4);
+    w.act = take(M * c.d_ff * 4);
+    w.part_qkv = (float*)take(M * (nq + 2 * nkv) * 4 * w.ks_qkv);
+    w.part_o = (float*)take(M * c.d_model * 4 * w.ks_o);
+    w.part_gu = (float*)take(M * 2 * c.d_ff * 4 * w.ks_gu);
+    w.part_d = (float*)take(M * c.d_model * 4 * w.ks_d);
+    w.part_attn = (float*)take(M * c.n_heads * attn_splits(B, c.n_heads, max_len) * (size_t)(c.head_dim + 2) * 4);
     w.total = off;
     return w;
 }
@@ -136,8 +146,8 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
     BS_REQUIRE(ws_bytes >= need, BS_EWORKSPACE, "forward: workspace %zu < %zu bytes", ws_bytes, need);
     BS_REQUIRE((reinterpret_cast<uintptr_t>(ws) & 255) == 0, BS_EWORKSPACE, "forward: workspace not 256-byte aligned");
     FwdWs w = carve(c, B, q_len, kv->max_len, reinterpret_cast<char*>(ws));
-    const int H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim;
-    const int nq = H * hd, nkv = KVH * hd;
+    const int H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim, d = c.d_model, ff = c.d_ff;
+    const int nq = H * hd, nkv = KVH * hd, nqkv = nq + 2 * nkv;
     const size_t es = esize(dt);
     const size_t kv_layer = (size_t)2 * B * KVH * (size_t)kv->max_len * hd * es;
     const int splits = attn_splits(B, H, kv->max_len);
@@ -145,51 +155,56 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
 #define BS_TRY(expr) do { rc = (expr); if (rc != BS_OK) return rc; } while (0)
     BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
                        w.rope, w.status, s));
-    BS_TRY(launch_embed(dt, w.tok, m->embed, M, c.d_model, w.x, s));
+    BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
+    const float* pend = nullptr;      // split-K partials of the last residual projection, not yet added to x
     for (int l = 0; l < c.n_layers; ++l) {
         const bs_layer_weights& L = m->layers[l];
         char* kc = kv->buf + (size_t)l * kv_layer;
         char* vc = kc + kv_layer / 2;
-        BS_TRY(launch_rmsnorm(dt, w.x, L.attn_norm, c.d_model, c.norm_eps, B, q_len, q_len, w.h, s));
+        BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, c.norm_eps, B, q_len, q_len,
+                              (size_t)M * d, w.h, s));
         GemmArgs g;
-        g.x = w.h; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
-        g.out = w.qkv; g.M = M; g.N = nq + 2 * nkv; g.K = c.d_model; g.ldo = nq + 2 * nkv;
-        BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
-        BS_TRY(launch_rope_kv(dt, w.qkv, w.pos, w.rope, M, q_len, H, KVH, hd, kv->max_len, w.q, kc, vc, s));
-        BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, kv->max_len, splits, w.part, w.att, s));
-        g.x = w.att; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.d_model; g.seg_rows[1] = 0;
-        g.out = w.x; g.M = M; g.N = c.d_model; g.K = nq; g.ldo = c.d_model;
-        BS_TRY(launch_gemm(dt, GEMM_ADD, g, s));
-        BS_TRY(launch_rmsnorm(dt, w.x, L.ffn_norm, c.d_model, c.norm_eps, B, q_len, q_len, w.h, s));
-        g.x = w.h; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = c.d_ff; g.seg_rows[1] = 0;
-        g.out = w.act; g.M = M; g.N = c.d_ff; g.K = c.d_model; g.ldo = c.d_ff;
-        BS_TRY(launch_gemm(dt, GEMM_SWIGLU, g, s));
-        g.x = w.act; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.d_model; g.seg_rows[1] = 0;
-        g.out = w.x; g.M = M; g.N = c.d_model; g.K = c.d_ff; g.ldo = c.d_model;
-        BS_TRY(launch_gemm(dt, GEMM_ADD, g, s));
+        g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
+        g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
+        BS_TRY(launch_gemm(dt, g, s));
+        BS_TRY(launch_rope_kv(dt, w.part_qkv, w.ks_qkv, (size_t)M * nqkv, w.pos, w.rope, M, q_len, H, KVH, hd, kv->max_len,
+                              w.q, kc, vc, s));
+        BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, kv->max_len, splits, w.part_attn,
+                                (size_t)M * nq, w.att, s));
+        g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
+        g.out = w.part_o; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = nq; g.ldo = d; g.KS = w.ks_o;
+        BS_TRY(launch_gemm(dt, g, s));
+        BS_TRY(launch_rmsnorm(dt, w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, c.norm_eps, B, q_len, q_len,
+                              (size_t)M * d, w.h, s));
+        g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = ff; g.seg_rows[1] = ff;
+        g.out = w.part_gu; g.ks_stride = (size_t)M * 2 * ff; g.M = M; g.N = 2 * ff; g.K = d; g.ldo = 2 * ff; g.KS = w.ks_gu;
+        BS_TRY(launch_gemm(dt, g, s));
+        BS_TRY(launch_swiglu(dt, w.part_gu, w.ks_gu, (size_t)M * 2 * ff, M, ff, (size_t)M * ff, w.act, s));
+        g.x = w.act; g.x_plane = (size_t)M * ff; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
+        g.out = w.part_d; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = ff; g.ldo = d; g.KS = w.ks_d;
+        BS_TRY(launch_gemm(dt, g, s));
+        pend = w.part_d;
     }
     if (logit_rows > 0) {
-        BS_TRY(launch_rmsnorm(dt, w.x, m->final_norm, c.d_model, c.norm_eps, B, q_len, logit_rows, w.h, s));
-        // one GEMM per sequence when the caller's rows of one sequence are not contiguous with the next
-        const bool contiguous = logits_bstride == (size_t)logit_rows * c.vocab;
+        const int R = B * logit_rows;
+        BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, m->final_norm, d, c.norm_eps, B, q_len, logit_rows,
+                              (size_t)R * d, w.h, s));
         GemmArgs g;
+        g.x_plane = (size_t)R * d;
         g.w[0] = m->lm_head; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.vocab; g.seg_rows[1] = 0;
-        g.N = c.vocab; g.K = c.d_model; g.ldo = c.vocab;
-        if (contiguous || logit_rows > 1) {
-            if (contiguous) {
-                g.x = w.h; g.out = logits; g.M = B * logit_rows;
-                BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
-            } else {
-                for (int b = 0; b < B; ++b) {
-                    g.x = reinterpret_cast<char*>(w.h) + (size_t)b * logit_rows * c.d_model * es;
-                    g.out = logits + (size_t)b * logits_bstride; g.M = logit_rows;
-                    BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
-                }
-            }
-        } else {
-            // one row per sequence, rows strided in the output: a single GEMM with ldo = batch stride
+        g.N = c.vocab; g.K = d; g.KS = 1; g.ks_stride = 0;
+        if (logits_bstride == (size_t)logit_rows * c.vocab) {            // rows of all sequences contiguous
+            g.x = w.h; g.out = logits; g.M = R; g.ldo = c.vocab;
+            BS_TRY(launch_gemm(dt, g, s));
+        } else if (logit_rows == 1) {                                     // one row per sequence, strided output
             g.x = w.h; g.out = logits; g.M = B; g.ldo = (int)logits_bstride;
-            BS_TRY(launch_gemm(dt, GEMM_STORE, g, s));
+            BS_TRY(launch_gemm(dt, g, s));
+        } else {
+            for (int b = 0; b < B; ++b) {
+                g.x = reinterpret_cast<char*>(w.h) + (size_t)b * logit_rows * d * (dt == BS_BF16 ? 2 : 4);
+                g.out = logits + (size_t)b * logits_bstride; g.M = logit_rows; g.ldo = c.vocab;
+                BS_TRY(launch_gemm(dt, g, s));
+            }
         }
     }
 #undef BS_TRY
@@ -400,7 +415,7 @@ extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_r
 extern "C" __attribute__((visibility("default"))) int bs_round_destroy(bs_round* r) {
     if (r) {
         for (auto& g : r->graphs)
-            if (g.exec) hipGraphExecDestroy(g.exec);
+            if (g.exec) (void)hipGraphExecDestroy(g.exec);
         delete r;
     }
     return BS_OK;
@@ -467,7 +482,7 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r,
     BS_REQUIRE(s != nullptr, BS_EINVAL, "bs_spec_round: graph mode needs a non-null stream");
     ArmGraph& g = r->graphs[arm];
     if (g.exec && (g.emitted != dev_emitted || g.n_emitted != dev_n_emitted)) {
-        hipGraphExecDestroy(g.exec);
+        (void)hipGraphExecDestroy(g.exec);
         g.exec = nullptr;
     }
     if (!g.exec) {
@@ -475,10 +490,10 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r,
         BS_HIP(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
         const int rc = enqueue_round(r, arm, dev_emitted, dev_n_emitted, s);
         const hipError_t e = hipStreamEndCapture(s, &graph);
-        if (rc != BS_OK) { if (graph) hipGraphDestroy(graph); return rc; }
+        if (rc != BS_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
         if (e != hipSuccess) BS_FAIL(BS_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
         const hipError_t e2 = hipGraphInstantiate(&g.exec, graph, nullptr, nullptr, 0);
-        hipGraphDestroy(graph);
+        (void)hipGraphDestroy(graph);
         if (e2 != hipSuccess) { g.exec = nullptr; BS_FAIL(BS_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e2)); }
         g.emitted = dev_emitted; g.n_emitted = dev_n_emitted;
     }

@@ -89,10 +89,10 @@ def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed
                     err = float(np.max(np.abs(dl[b, i] - r["draft_logits"][i])))
                     stats["max_logit_err"] = max(stats["max_logit_err"], err)
                     assert err < logit_tol, f"round {t} seq {b} draft logits row {i}: {err}"
-                if int(dt[b, i]) != int(r["draft_tokens"][i]):
-                    assert same_drafts and draw_is_valid(r["draft_probs"][i], r["draft_uniforms"][i], int(dt[b, i]), BIN_TOL), \
+                if same_drafts and int(dt[b, i]) != int(r["draft_tokens"][i]):
+                    assert draw_is_valid(r["draft_probs"][i], r["draft_uniforms"][i], int(dt[b, i]), BIN_TOL), \
                         f"round {t} seq {b}: draft token {i} {int(dt[b, i])} vs {int(r['draft_tokens'][i])}"
-                    same_drafts = False
+                    same_drafts = False          # later positions are conditioned on different prefixes
             if not same_drafts:                      # a draw on a bin edge: both are valid, histories diverge
                 stats["excused"] += 1; need_sync = True
             else:
@@ -138,9 +138,12 @@ def test_tiny_fp32_configuration_full_run_ucbspec():
 
 def test_tiny_fp32_batch_exp3spec_with_graph_replay():
     b = bs()
-    stats, seqs = lockstep(synth.TINY_TARGET, [synth.TINY_DRAFT], [0, 0, 0], [1, 3, 4], EXP3Spec(3, 4),
-                           b.Bandit(b.BS_EXP3SPEC, 3, 4, seed=31), 3, 12, 30, seed=31, storage="f32", logit_tol=1e-5,
-                           use_graph=True)
+    side = torch.cuda.Stream()                      # stream capture needs a non-null stream
+    with torch.cuda.stream(side):
+        stats, seqs = lockstep(synth.TINY_TARGET, [synth.TINY_DRAFT], [0, 0, 0], [1, 3, 4], EXP3Spec(3, 4),
+                               b.Bandit(b.BS_EXP3SPEC, 3, 4, seed=31), 3, 12, 30, seed=31, storage="f32",
+                               logit_tol=1e-5, use_graph=True)
+    side.synchronize()
     assert all(len(s) == 42 for s in seqs) and stats["decisions"] > 10
 
 
