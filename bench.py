@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the BanditSpec hot path on one MI355X.
+
+A step = one speculative round of the whole hot path on the Llama-7B-shaped workload: UCBSpec arm
+selection on the host, gamma draft steps, one target verification pass over gamma+1 positions,
+accept/reject + residual/bonus sampling, commit, accepted length back to the bandit.  Weights are
+random-init, the prompt is 1024 uniform token ids, everything is resident in HBM before timing.
+
+Prints ONE JSON line (metric = generated tokens/s) with
+  roofline      the weight-streaming GEMM (dominant kernel): algorithmic bytes / HIP-event time
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def gpu_weights(c, seed, torch, std=0.02):
+    """Random-init weights generated on the device (same recipe as synth.make_weights: N(0, 0.02), gains 1)."""
+    from paper_2505_15141_amd import synth
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    W = {}
+    for name, shape in synth.weight_shapes(c).items():
+        if name.endswith("norm"):
+            W[name] = torch.ones(shape, dtype=torch.float32, device="cuda")
+        else:
+            W[name] = (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+    return W
+
+
+def cpu_baseline(tc, dc, prefix, gamma, mean_y):
+    """Oracle (fp64 numpy, full recompute) on one-layer slices of the same shapes, extrapolated to the full depth."""
+    import numpy as np
+    from oracle.forward import forward
+    from oracle.sampling import spec_sample
+    from paper_2505_15141_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rng = np.random.default_rng(0)
+    toks = rng.integers(0, tc["vocab"], prefix + gamma)
+
+    def timed(c, n_layers, n_tokens):
+        cc = dict(c, n_layers=n_layers)
+        W = synth.make_weights(cc, 5)
+        t0 = time.perf_counter()
+        lg = forward(cc, W, toks[:n_tokens], storage="bf16")
+        return time.perf_counter() - t0, lg
+
+    t_t0, _ = timed(tc, 0, prefix + gamma)          # embedding + final norm + LM head
+    t_t1, lg_t = timed(tc, 1, prefix + gamma)
+    t_d0, _ = timed(dc, 0, prefix + gamma - 1)
+    t_d1, lg_d = timed(dc, 1, prefix + gamma - 1)
+    t0 = time.perf_counter()
+    spec_sample(lg_t[-(gamma + 1):], lg_d[-gamma:], toks[-gamma:], np.full(gamma, 0.5), 0.5)
+    t_s = time.perf_counter() - t0
+    t_target = t_t0 + tc["n_layers"] * max(t_t1 - t_t0, 0.0)
+    t_draft = t_d0 + dc["n_layers"] * max(t_d1 - t_d0, 0.0)
+    t_round = t_target + gamma * t_draft + t_s
+    return {"value": mean_y / t_round, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": (f"oracle forward timed on 0- and 1-layer slices of the target and draft shapes at {prefix + gamma} tokens "
+                       f"(full recompute, fp64) plus one accept/reject call, extrapolated to {tc['n_layers']}/{dc['n_layers']} layers "
+                       f"and gamma={gamma}: {t_round:.1f} s per round; tokens per round taken from the GPU run"),
+            "seconds_measured": round(t_t0 + t_t1 + t_d0 + t_d1 + t_s, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--profile-rounds", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the round shards by sequence across GPUs without exchange; "
+              "nothing is launched on more than one device). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2505_15141_amd import binding as bs, synth
+
+    torch.cuda.set_device(0)
+    tc, dc = synth.LLAMA7B_TARGET, synth.LLAMA7B_DRAFT
+    gammas = [2, 4, 6, 8]
+    L, B, prefix = max(gammas), 1, 1024
+    total_rounds = args.warmup + args.steps + args.profile_rounds + 4
+    max_len = prefix + (L + 1) * total_rounds + L + 2
+    seed = 2025
+
+    target = bs.Model(tc, gpu_weights(tc, 1, torch))
+    draft = bs.Model(dc, gpu_weights(dc, 2, torch))
+    tkv, dkv = bs.KV(target, B, max_len), bs.KV(draft, B, max_len)
+    tokens = torch.zeros(B, max_len, dtype=torch.int32, device="cuda")
+    tokens[:, :prefix] = torch.from_numpy(synth.make_prompts(B, prefix, tc["vocab"], 3).astype(np.int32)).cuda()
+    total = torch.full((B,), prefix, dtype=torch.int32, device="cuda")
+    goal = torch.full((B,), max_len, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        t0 = time.perf_counter()
+        bs.prefill(target, tkv, tokens, prefix - 1)
+        bs.prefill(draft, dkv, tokens, prefix - 1)
+        stream.synchronize()
+        prefill_s = time.perf_counter() - t0
+        rnd = bs.Round(target, tkv, [draft], [dkv], [0] * len(gammas), gammas, tokens, total, goal, 1.0, seed,
+                       use_graph=not args.no_graph)
+        rnd.reset(0)
+        bandit = bs.Bandit(bs.BS_UCBSPEC, len(gammas), L, 0.5)
+        host_y = torch.zeros(B, dtype=torch.int32).pin_memory()
+
+        def one_round():
+            arm = bandit.select()
+            _, n_emitted = rnd.spec_round(arm)
+            host_y.copy_(n_emitted, non_blocking=True)
+            stream.synchronize()                      # the next arm choice depends on y (Alg. 3)
+            y = float(host_y.float().mean())
+            bandit.update(arm, y)
+            return arm, y
+
+        for _ in range(args.warmup):
+            one_round()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ys, arms = [], []
+        for _ in range(args.steps):
+            arm, y = one_round()
+            ys.append(y); arms.append(arm)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        gen_tokens = float(np.sum(ys)) * B
+
+        # ---- verify-step latency (eager, HIP events on this stream), per gamma ----
+        verify_ms = {}
+        kvl = (total - 1).to(torch.int32)       # current cache length; rows written here are overwritten by later rounds
+        for g in gammas:
+            q = tokens[:, prefix - 1:prefix + g].contiguous()
+            ws = torch.empty(target.forward_workspace_bytes(B, g + 1, max_len), dtype=torch.uint8, device="cuda")
+            lg = torch.empty(B, g + 1, tc["vocab"], dtype=torch.float32, device="cuda")
+            ts = []
+            for it in range(6):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                bs.verify_forward(target, tkv, q, kvl, workspace=ws, logits=lg)
+                e1.record(stream)
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            verify_ms[str(g)] = round(float(np.median(ts[1:])), 4)
+
+        # ---- roofline of the dominant kernel: eager rounds with HIP events around every GEMM launch ----
+        rnd_eager = bs.Round(target, tkv, [draft], [dkv], [0] * len(gammas), gammas, tokens, total, goal, 1.0, seed,
+                             use_graph=False)
+        rnd_eager.reset(total_rounds)
+        stream.synchronize()
+        bs.profile_enable(True)
+        for i in range(args.profile_rounds):
+            rnd_eager.spec_round(i % len(gammas))
+            stream.synchronize()
+        ms1, by1, n1 = bs.profile_collect(1)
+        bs.profile_enable(False)
+
+    weights_bytes = sum(v.numel() * v.element_size() for k, v in target.weights.items() if not k.endswith("norm") and k != "embed")
+    achieved = by1 / (ms1 * 1e-3) / 1e9 if ms1 > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel<1,256> (weight-streaming MFMA GEMM, <=16 activation rows)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "launches": int(n1), "avg_us": round(ms1 * 1e3 / max(n1, 1), 3),
+                "avg_algorithmic_bytes": round(by1 / max(n1, 1), 1)}
+    mean_y = float(np.mean(ys))
+    out = {"metric": "generated tokens/s at 1 GPU", "value": round(gen_tokens / elapsed, 2), "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "Llama-7B-shaped verification (32x4096, 32 heads x128, FFN 11008, vocab 32000) with a 12-layer "
+                                  "d=768 draft, batch 1, prefix 1024, UCBSpec over gamma in {2,4,6,8}, random-init bf16 weights",
+                      "batch": B, "prefix": prefix, "arms_gamma": gammas, "bandit": "UCBSpec", "graph": not args.no_graph},
+           "mean_accepted_tokens": round(mean_y, 4), "generated_tokens": int(gen_tokens),
+           "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
+           "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
+           "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "prefill_s": round(prefill_s, 3), "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(tc, dc, prefix, 4, mean_y)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

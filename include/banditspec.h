@@ -211,6 +211,17 @@ int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emi
 int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const float** dev_draft_logits,
                          const int32_t** dev_draft_tokens, const float** dev_margins);
 
+/* ------------------------------------------------------------------------------------------------
+ * Measurement hook (not part of the method): while enabled, every launch of the bf16 weight-streaming
+ * GEMM made OUTSIDE a graph capture is bracketed by HIP events on its own stream.  bs_profile_collect
+ * synchronises on those events and returns, for launches whose row-tile count (1, 2, 4 or 6 tiles of
+ * 16 activation rows; 0 = all) matches, the summed kernel time in ms, the summed algorithmic bytes
+ * (each weight element once: N*K*2) and the launch count.  Enabling clears earlier records.  Do not
+ * enable while a graph is being captured.
+ * ---------------------------------------------------------------------------------------------- */
+int bs_profile_enable(int on);
+int bs_profile_collect(int row_tiles, double* host_total_ms, double* host_total_bytes, long long* host_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -78,6 +78,8 @@ _sig("bs_round_create", C.c_int, C.POINTER(RoundCfg), C.POINTER(vp))
 _sig("bs_round_destroy", C.c_int, vp)
 _sig("bs_round_reset", C.c_int, vp, u32, vp)
 _sig("bs_spec_round", C.c_int, vp, C.c_int, vp, vp, vp)
+_sig("bs_profile_enable", C.c_int, C.c_int)
+_sig("bs_profile_collect", C.c_int, C.c_int, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_longlong))
 _sig("bs_round_debug_views", C.c_int, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp))
 
 
@@ -306,3 +308,14 @@ class Round:
         if getattr(self, "h", None) and lib is not None:
             lib.bs_round_destroy(self.h)
             self.h = None
+
+
+def profile_enable(on=True):
+    check(lib.bs_profile_enable(int(on)))
+
+
+def profile_collect(row_tiles=0):
+    """(total_ms, total_bytes, launches) of the timed weight-streaming GEMM launches."""
+    ms, by, n = f64(), f64(), C.c_longlong()
+    check(lib.bs_profile_collect(row_tiles, C.byref(ms), C.byref(by), C.byref(n)))
+    return ms.value, by.value, n.value

@@ -17,6 +17,8 @@ struct GemmArgs {
 };
 
 int gemm_splits(int dtype, int N, int K);
+int profile_enable(int on);
+int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches);
 int launch_gemm(int dtype, GemmArgs a, hipStream_t s);
 
 int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, int kv_base, int B, int q_len,

@@ -12,6 +12,7 @@
 //   attention   q_len causal query rows per head against the contiguous KV cache, split along the
 //               keys with online softmax; merge kernel combines the splits
 #include <math.h>
+#include <vector>
 #include "common.h"
 #include "kernels.h"
 
@@ -103,29 +104,48 @@ template <> struct Act<uint16_t> {
 // (rows_out = rows_in: identity; rows_out < rows_in: the trailing rows of every sequence).
 // If pend != null the residual row is first completed: x[src] += sum_s pend[s][src][:], and written back.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ pend, int pend_ks,
-                                                      size_t pend_stride, const float* __restrict__ gain, int d,
-                                                      float eps, int rows_in, int rows_out, size_t plane,
-                                                      void* __restrict__ out) {
-    __shared__ float red[4];
+__global__ __launch_bounds__(1024) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ pend, int pend_ks,
+                                                       size_t pend_stride, const float* __restrict__ gain, int d,
+                                                       float eps, int rows_in, int rows_out, size_t plane,
+                                                       void* __restrict__ out) {
+    __shared__ float red[16];
     const int r = blockIdx.x;
     const int src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out;
     float* row = x + (size_t)src * d;
+    const float* prow = pend ? pend + (size_t)src * d : nullptr;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = row[i];
-        if (pend) {
-            for (int s = 0; s < pend_ks; ++s) v += pend[(size_t)s * pend_stride + (size_t)src * d + i];
-            row[i] = v;
+    // d % 8 == 0 (host check): float4 granules; the split-K partials are independent loads
+    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+        float4 v = *reinterpret_cast<const float4*>(row + i);
+        if (prow) {
+            for (int s0 = 0; s0 < pend_ks; s0 += 4) {
+                float4 p[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    p[u] = (s0 + u < pend_ks) ? *reinterpret_cast<const float4*>(prow + (size_t)(s0 + u) * pend_stride + i)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
+            }
+            *reinterpret_cast<float4*>(row + i) = v;
         }
-        ss += v * v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = wsum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
     const float scale = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += 256) Act<T>::store(out, plane, (size_t)r * d + i, row[i] * scale * gain[i]);
+    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+        const float4 v = *reinterpret_cast<const float4*>(row + i);        // own earlier write, or the input
+        const float4 g = *reinterpret_cast<const float4*>(gain + i);
+        Act<T>::store(out, plane, (size_t)r * d + i, v.x * scale * g.x);
+        Act<T>::store(out, plane, (size_t)r * d + i + 1, v.y * scale * g.y);
+        Act<T>::store(out, plane, (size_t)r * d + i + 2, v.z * scale * g.z);
+        Act<T>::store(out, plane, (size_t)r * d + i + 3, v.w * scale * g.w);
+    }
 }
 
 // ---- SwiGLU over split-K partials: act = silu(sum_s g) * sum_s u, columns [0,ff) gate, [ff,2ff) up ------
@@ -279,6 +299,39 @@ int gemm_splits(int dtype, int N, int K) {
     return ks;
 }
 
+// ---- optional per-launch timing of the weight-streaming GEMM (measurement hook) ----------------------
+struct GemmProfile {
+    bool on = false;
+    std::vector<hipEvent_t> ev;       // pairs (start, stop)
+    std::vector<double> bytes;        // algorithmic bytes of each timed launch: the weight tile once
+    std::vector<int> mt;
+};
+static GemmProfile g_prof;
+
+int profile_enable(int on) {
+    g_prof.on = on != 0;
+    if (!on) return BS_OK;
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof.ev.clear(); g_prof.bytes.clear(); g_prof.mt.clear();
+    return BS_OK;
+}
+
+int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches) {
+    double ms = 0.0, by = 0.0;
+    long long n = 0;
+    for (size_t i = 0; i < g_prof.bytes.size(); ++i) {
+        if (mt_filter > 0 && g_prof.mt[i] != mt_filter) continue;
+        BS_HIP(hipEventSynchronize(g_prof.ev[2 * i + 1]));
+        float t = 0.f;
+        BS_HIP(hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]));
+        ms += t; by += g_prof.bytes[i]; ++n;
+    }
+    if (total_ms) *total_ms = ms;
+    if (total_bytes) *total_bytes = by;
+    if (launches) *launches = n;
+    return BS_OK;
+}
+
 int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return BS_OK;
     if (dtype == BS_F32) {
@@ -294,13 +347,39 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
         const dim3 grid((a.N + 63) / 64, a.KS), block(256);
         const int mt = (c.M + 15) / 16;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (g_prof.on) {
+            BS_HIP(hipEventCreate(&e0));
+            BS_HIP(hipEventCreate(&e1));
+            BS_HIP(hipEventRecord(e0, s));
+        }
         if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256>), grid, block, 0, s, c);
         else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 256>), grid, block, 0, s, c);
         else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 128>), grid, block, 0, s, c);
         else hipLaunchKernelGGL((gemm_bf16_kernel<6, 128>), grid, block, 0, s, c);
         BS_LAUNCH_CHECK();
+        if (g_prof.on) {
+            BS_HIP(hipEventRecord(e1, s));
+            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+            g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
+            g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : 6);
+        }
     }
     return BS_OK;
+}
+
+// ---- KV cache layout --------------------------------------------------------------------------------
+// Per (sequence, kv head): K is [cache_len][hd] (a key's row is contiguous: MFMA A operand of K.Q^T).
+// V of a bf16 cache is stored transposed in blocks of 32 keys, [cache_len/32][hd][32], and inside a block
+// the key k = 16t + 4q + e sits at slot 8q + 4t + e: lane (d, q) of the MFMA A operand of V^T.P^T then
+// finds its 8 keys in one 16-byte load, in exactly the key order in which the score accumulators of
+// K.Q^T hold the probabilities.  cache_len is a multiple of 32.  fp32 caches keep V as [cache_len][hd].
+template <typename T> __device__ __forceinline__ size_t v_index(int key, int d, int hd);
+template <> __device__ __forceinline__ size_t v_index<float>(int key, int d, int hd) { return (size_t)key * hd + d; }
+template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, int hd) {
+    const int k = key & 31;
+    const int slot = ((k & 15) >> 2) * 8 + (k >> 4) * 4 + (k & 3);
+    return ((size_t)(key >> 5) * hd + d) * 32 + slot;
 }
 
 // ---- RoPE + KV append -----------------------------------------------------------------------------
@@ -331,8 +410,9 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int ks, size_t ks
             dst[2 * i] = from_f<T>(r0); dst[2 * i + 1] = from_f<T>(r1);
         }
     } else if (p >= 0) {
-        T* dst = v_cache + (((size_t)b * KVH + (head - H - KVH)) * max_len + p) * hd;
-        dst[2 * i] = from_f<T>(x0); dst[2 * i + 1] = from_f<T>(x1);
+        T* base = v_cache + ((size_t)b * KVH + (head - H - KVH)) * (size_t)max_len * hd;
+        base[v_index<T>(p, 2 * i, hd)] = from_f<T>(x0);
+        base[v_index<T>(p, 2 * i + 1, hd)] = from_f<T>(x1);
     }
 }
 
@@ -444,9 +524,9 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const bool okk = kk + u < kmax;
-                    const T* vrow = vb + (size_t)(t * 64 + kk + u) * hd;
-                    v0[u] = (okk && d0 < hd) ? to_f(vrow[d0]) : 0.f;
-                    v1[u] = (okk && d1 < hd) ? to_f(vrow[d1]) : 0.f;
+                    const int vk = t * 64 + kk + u;
+                    v0[u] = (okk && d0 < hd) ? to_f(vb[v_index<T>(vk, d0, hd)]) : 0.f;
+                    v1[u] = (okk && d1 < hd) ? to_f(vb[v_index<T>(vk, d1, hd)]) : 0.f;
                 }
 #pragma unroll
                 for (int r = 0; r < ATT_RB; ++r) {
@@ -478,6 +558,183 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
             float* dst = part + ((((size_t)(m_first + r0 + r)) * H + h) * n_splits + split) * pstride;
             dst[2 + d] = o;
             if (d == 0) { dst[0] = mm; dst[1] = l; }
+        }
+    }
+}
+
+// ---- attention, bf16 cache, MFMA ---------------------------------------------------------------------
+// grid (n_splits, KVH, B), 4 wavefronts.  Rows of the score matrix = the q_len query positions of the
+// H/KVH query heads that share this kv head (16 rows per MFMA tile).  The wavefronts take the 32-key
+// blocks of their split in turn:
+//   S^T = K . Q^T      A = K rows straight from the cache, B = Q (fp32 queries as a bf16 hi/lo pair)
+//   online softmax     a row lives in one lane column (l % 16); its 32 scores sit in 4 lanes -> 2 shuffles
+//   O^T += V^T . P^T   A = transposed V block (one 16-byte load per lane), B = P^T taken from the score
+//                      accumulators as they are (hi/lo pair), no LDS, no transposes
+// Bytes: every K and V element is read once per 16 rows.  Un-normalised partials (m, l, o[hd]) per split.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    return (uint32_t)from_f<uint16_t>(a) | ((uint32_t)from_f<uint16_t>(b) << 16);
+}
+__device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
+    float r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = v[e] - to_f(from_f<uint16_t>(v[e]));
+    hi = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    lo = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict__ q, const uint16_t* __restrict__ k_cache,
+                                                        const uint16_t* __restrict__ v_cache,
+                                                        const int32_t* __restrict__ pos, int q_len, int H, int KVH,
+                                                        int cache_len, float scale, float* __restrict__ part) {
+    constexpr int DS = HD / 32, DT = HD / 16;
+    __shared__ float wm[4][16], wl[4][16];
+    __shared__ float wo[4][16][HD + 1];
+    const int split = blockIdx.x, n_splits = gridDim.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int G = H / KVH, R = G * q_len;
+    const int m_first = b * q_len;
+    const int pos0 = pos[m_first];
+    const size_t pstride = (size_t)HD + 2;
+    if (pos0 < 0) {                                  // sequence skipped: empty partials
+        for (int r = threadIdx.x; r < R; r += 256) {
+            const int g = r / q_len, qi = r % q_len;
+            float* dst = part + ((((size_t)(m_first + qi)) * H + kvh * G + g) * n_splits + split) * pstride;
+            dst[0] = -INFINITY; dst[1] = 0.f;
+        }
+        return;
+    }
+    const int n_keys = pos0 + q_len;
+    const int nblk = (n_keys + 31) / 32;
+    const int per = (nblk + n_splits - 1) / n_splits;
+    const int b_begin = split * per, b_end = min(nblk, b_begin + per);
+    const uint16_t* kb = k_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
+    const uint16_t* vb = v_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
+
+    for (int r0 = 0; r0 < R; r0 += 16) {
+        const int row = r0 + li;
+        const bool rvalid = row < R;
+        const int g = rvalid ? row / q_len : 0, qi = rvalid ? row % q_len : 0;
+        const int row_pos = pos0 + qi;
+        uint4 qh[DS], ql[DS];
+        {
+            const float* qrow = q + ((size_t)(m_first + qi) * H + kvh * G + g) * HD;
+#pragma unroll
+            for (int ds = 0; ds < DS; ++ds) {
+                float v[8];
+                const float4 a = *reinterpret_cast<const float4*>(qrow + ds * 32 + lq * 8);
+                const float4 c = *reinterpret_cast<const float4*>(qrow + ds * 32 + lq * 8 + 4);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = rvalid ? v[e] * scale : 0.f;
+                split8(v, qh[ds], ql[ds]);
+            }
+        }
+        float m_run = -INFINITY, l_run = 0.f;
+        f32x4 o[DT];
+#pragma unroll
+        for (int t = 0; t < DT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int blk = b_begin + wave; blk < b_end; blk += 4) {
+            const int key0 = blk * 32;
+            // ---- scores of 32 keys x 16 rows ----
+            f32x4 sc[2];
+            uint4 kf[2][DS];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int krow = min(key0 + t * 16 + li, n_keys - 1);
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) kf[t][ds] = ldg16(kb + (size_t)krow * HD + ds * 32 + lq * 8);
+            }
+            uint4 vf[DT];
+#pragma unroll
+            for (int t = 0; t < DT; ++t) vf[t] = ldg16(vb + ((size_t)blk * HD + t * 16 + li) * 32 + lq * 8);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ds = 0; ds < DS; ++ds) {
+                    const bf16x8 A = __builtin_bit_cast(bf16x8, kf[t][ds]);
+                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, qh[ds]), sc[t], 0, 0, 0);
+                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ql[ds]), sc[t], 0, 0, 0);
+                }
+            }
+            // lane holds S^T[key0 + 16t + 4lq + e][row li]
+            float sv[8];
+            float bm = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = key0 + t * 16 + 4 * lq + e;
+                    const bool vis = rvalid && key < n_keys && key <= row_pos;       // causal
+                    sv[t * 4 + e] = vis ? sc[t][e] : -INFINITY;
+                    bm = fmaxf(bm, sv[t * 4 + e]);
+                }
+            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+            const float m_new = fmaxf(m_run, bm);
+            float pv[8];
+            float alpha = 1.f, psum = 0.f;
+            if (m_new == -INFINITY) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pv[e] = 0.f;
+            } else {
+                alpha = __expf(m_run - m_new);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { pv[e] = __expf(sv[e] - m_new); psum += pv[e]; }
+            }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+            uint4 ph, pl;
+            split8(pv, ph, pl);
+            // ---- values: keys past n_keys may hold anything, even NaN patterns: zero them ----
+            if (key0 + 32 > n_keys) {
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    uint32_t w[4] = {vf[t].x, vf[t].y, vf[t].z, vf[t].w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int key = key0 + (e >> 2) * 16 + 4 * lq + (e & 3);
+                        if (key >= n_keys) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+                    }
+                    vf[t] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                o[t][0] *= alpha; o[t][1] *= alpha; o[t][2] *= alpha; o[t][3] *= alpha;
+                const bf16x8 A = __builtin_bit_cast(bf16x8, vf[t]);
+                o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ph), o[t], 0, 0, 0);
+                o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, pl), o[t], 0, 0, 0);
+            }
+        }
+        // ---- combine the 4 wavefronts: lane holds O^T[d = 16t + 4lq + e][row li] ----
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        __syncthreads();
+        if (lq == 0) { wm[wave][li] = m_run; wl[wave][li] = l_run; }
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) wo[wave][li][t * 16 + 4 * lq + e] = o[t][e];
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+            const int r = idx / HD, d = idx % HD;
+            if (r0 + r >= R) continue;
+            const float mm = fmaxf(fmaxf(wm[0][r], wm[1][r]), fmaxf(wm[2][r], wm[3][r]));
+            float ov = 0.f, lv = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float f = (wm[w][r] == -INFINITY) ? 0.f : __expf(wm[w][r] - mm);
+                ov += wo[w][r][d] * f;
+                lv += wl[w][r] * f;
+            }
+            const int gg = (r0 + r) / q_len, qq = (r0 + r) % q_len;
+            float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
+            dst[2 + d] = ov;
+            if (d == 0) { dst[0] = mm; dst[1] = lv; }
         }
     }
 }
@@ -525,9 +782,9 @@ int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t p
     const int rows = n_seq * rows_out;
     if (rows <= 0) return BS_OK;
     if (dtype == BS_BF16)
-        hipLaunchKernelGGL((rmsnorm_kernel<uint16_t>), dim3(rows), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
+        hipLaunchKernelGGL((rmsnorm_kernel<uint16_t>), dim3(rows), dim3(1024), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
     else
-        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
+        hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(1024), 0, s, x, pend, pend_ks, pend_stride, gain, d, eps, rows_in, rows_out, plane, out);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
@@ -562,8 +819,15 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
     const float scale = 1.0f / sqrtf((float)hd);
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
-        hipLaunchKernelGGL((attn_kernel<uint16_t>), grid, block, 0, s, q, (const uint16_t*)k_cache,
-                           (const uint16_t*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);
+        const dim3 mgrid(n_splits, KVH, B);
+        if (hd == 128)
+            hipLaunchKernelGGL((attn_mfma_kernel<128>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part);
+        else if (hd == 64)
+            hipLaunchKernelGGL((attn_mfma_kernel<64>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part);
+        else
+            BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
         BS_LAUNCH_CHECK();
         hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {

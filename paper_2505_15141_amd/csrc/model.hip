@@ -25,6 +25,7 @@ struct bs_kv {
 };
 
 static size_t esize(int dtype) { return dtype == BS_BF16 ? 2 : 4; }
+static int cache_rows(int max_len) { return (max_len + 31) / 32 * 32; }   // V is stored in blocks of 32 keys
 
 static int check_cfg(const bs_model_cfg* c, const char* who) {
     BS_REQUIRE(c, BS_EINVAL, "%s: cfg is NULL", who);
@@ -34,6 +35,8 @@ static int check_cfg(const bs_model_cfg* c, const char* who) {
     BS_REQUIRE(c->n_heads % c->n_kv_heads == 0, BS_ESHAPE, "%s: n_heads %d not a multiple of n_kv_heads %d", who, c->n_heads, c->n_kv_heads);
     BS_REQUIRE(c->head_dim % 8 == 0 && c->head_dim >= 8 && c->head_dim <= 128, BS_ESHAPE,
                "%s: head_dim %d must be a multiple of 8 in [8,128]", who, c->head_dim);
+    BS_REQUIRE(c->dtype != BS_BF16 || c->head_dim == 64 || c->head_dim == 128, BS_ESHAPE,
+               "%s: bf16 models need head_dim 64 or 128 (MFMA attention), got %d", who, c->head_dim);
     BS_REQUIRE(c->d_model % 8 == 0 && c->d_ff % 8 == 0, BS_ESHAPE, "%s: d_model and d_ff must be multiples of 8", who);
     BS_REQUIRE(c->vocab <= (1 << 20), BS_ESHAPE, "%s: vocab %d > 2^20", who, c->vocab);
     BS_REQUIRE(c->rope_base > 1.f && c->norm_eps > 0.f, BS_EINVAL, "%s: rope_base/norm_eps out of range", who);
@@ -67,7 +70,7 @@ extern "C" __attribute__((visibility("default"))) int bs_model_destroy(bs_model*
 
 extern "C" __attribute__((visibility("default"))) size_t bs_kv_bytes(const bs_model_cfg* c, int B, int max_len) {
     if (!c || B < 1 || max_len < 1) return 0;
-    return (size_t)c->n_layers * 2 * B * c->n_kv_heads * (size_t)max_len * c->head_dim * esize(c->dtype);
+    return (size_t)c->n_layers * 2 * B * c->n_kv_heads * (size_t)cache_rows(max_len) * c->head_dim * esize(c->dtype);
 }
 
 extern "C" __attribute__((visibility("default"))) int bs_kv_bind(const bs_model* m, int B, int max_len, void* dev_buf, size_t bytes, bs_kv** out) {
@@ -86,7 +89,7 @@ extern "C" __attribute__((visibility("default"))) int bs_kv_destroy(bs_kv* kv) {
 
 // ---- forward workspace ----------------------------------------------------------------------------
 static int attn_splits(int B, int H, int max_len) {
-    int by_len = (max_len + 255) / 256;              // at least ~4 tiles of 64 keys per split at full length
+    int by_len = (max_len + 127) / 128;              // at least one 32-key block per wavefront at full length
     int by_fill = (1024 + B * H - 1) / (B * H);      // enough workgroups to cover 256 CUs a few times
     int s = by_len < by_fill ? by_len : by_fill;
     if (s < 1) s = 1;
@@ -149,7 +152,8 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
     const int H = c.n_heads, KVH = c.n_kv_heads, hd = c.head_dim, d = c.d_model, ff = c.d_ff;
     const int nq = H * hd, nkv = KVH * hd, nqkv = nq + 2 * nkv;
     const size_t es = esize(dt);
-    const size_t kv_layer = (size_t)2 * B * KVH * (size_t)kv->max_len * hd * es;
+    const int crow = cache_rows(kv->max_len);
+    const size_t kv_layer = (size_t)2 * B * KVH * (size_t)crow * hd * es;
     const int splits = attn_splits(B, H, kv->max_len);
     int rc;
 #define BS_TRY(expr) do { rc = (expr); if (rc != BS_OK) return rc; } while (0)
@@ -167,9 +171,9 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
         g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
         BS_TRY(launch_gemm(dt, g, s));
-        BS_TRY(launch_rope_kv(dt, w.part_qkv, w.ks_qkv, (size_t)M * nqkv, w.pos, w.rope, M, q_len, H, KVH, hd, kv->max_len,
+        BS_TRY(launch_rope_kv(dt, w.part_qkv, w.ks_qkv, (size_t)M * nqkv, w.pos, w.rope, M, q_len, H, KVH, hd, crow,
                               w.q, kc, vc, s));
-        BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, kv->max_len, splits, w.part_attn,
+        BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
                                 (size_t)M * nq, w.att, s));
         g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_o; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = nq; g.ldo = d; g.KS = w.ks_o;
@@ -508,4 +512,9 @@ extern "C" __attribute__((visibility("default"))) int bs_round_debug_views(bs_ro
     if (dt) *dt = r->ws.draft_tokens;
     if (mg) *mg = r->ws.margins;
     return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_profile_enable(int on) { return bs::profile_enable(on); }
+extern "C" __attribute__((visibility("default"))) int bs_profile_collect(int row_tiles, double* total_ms, double* total_bytes, long long* launches) {
+    return bs::profile_collect(row_tiles, total_ms, total_bytes, launches);
 }
