@@ -16,7 +16,7 @@ struct GemmArgs {
     int M, N, K, ldo, KS;
 };
 
-int gemm_splits(int dtype, int N, int K);
+int gemm_splits(int dtype, int N, int K, int M);
 int profile_enable(int on);
 int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches);
 int launch_gemm(int dtype, GemmArgs a, hipStream_t s);

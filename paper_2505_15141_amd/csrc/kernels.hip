@@ -258,6 +258,94 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
     }
 }
 
+// ---- GEMM for at most 16 activation rows (verification of one sequence, draft steps) -----------------
+// Same operand mapping as above, but the whole K range of the workgroup (at most M16_KMAX columns) is
+// staged in LDS once, behind the first weight loads, and the loop over 32-wide k slices then runs without
+// barriers: each wavefront keeps a ring of M16_DEPTH weight loads (16 rows x 64 bytes each) in flight and
+// retires them in order against the in-order memory counter.
+constexpr int M16_KMAX = 512;
+constexpr int M16_DEPTH = 8;
+
+__global__ __launch_bounds__(256) void gemm_bf16_m16_kernel(GemmArgs a, int kper) {
+    constexpr int ROW = M16_KMAX + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][16][ROW];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int n0 = blockIdx.x * 64 + wave * 16;
+    const int ks = blockIdx.y;
+    const int k_lo = ks * kper, k_hi = min(a.K, k_lo + kper);       // this workgroup's columns
+    const uint16_t* wrow;
+    {
+        int n = n0 + li;
+        if (n >= a.N) n = a.N - 1;
+        int seg = 0, local = n;
+        if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+        wrow = reinterpret_cast<const uint16_t*>(a.w[seg]) + (size_t)local * a.K + lq * 8;
+    }
+    const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
+    const uint16_t* xl = xh + a.x_plane;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    // phases of at most M16_KMAX columns (one phase unless the caller asked for few splits)
+    for (int k_begin = k_lo; k_begin < k_hi; k_begin += M16_KMAX) {
+        const int k_end = min(k_hi, k_begin + M16_KMAX);
+        const int nsl = (k_end - k_begin + 31) / 32;
+        auto wload = [&](int j) {
+            const int k = k_begin + j * 32;
+            return (j < nsl && k + lq * 8 < k_end) ? ldg16(wrow + k) : make_uint4(0, 0, 0, 0);
+        };
+        uint4 w[M16_DEPTH];
+#pragma unroll
+        for (int u = 0; u < M16_DEPTH; ++u) w[u] = wload(u);
+        if (k_begin != k_lo) __syncthreads();              // the previous phase's LDS reads are done
+        // stage the activation slice [16][k_begin..k_end) of both planes; rows >= M and the tail are zero
+        const int chunks_per_row = nsl * 4;                // 16-byte chunks
+        for (int c = threadIdx.x; c < 2 * 16 * chunks_per_row; c += 256) {
+            const int plane = c / (16 * chunks_per_row);
+            const int rem = c % (16 * chunks_per_row);
+            const int m = rem / chunks_per_row, kc = (rem % chunks_per_row) * 8;
+            const int k = k_begin + kc;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < a.M && k < k_end) v = ldg16((plane ? xl : xh) + (size_t)m * a.K + k);
+            *reinterpret_cast<uint4*>(&xs[plane][m][kc]) = v;
+        }
+        __syncthreads();
+        for (int j0 = 0; j0 < nsl; j0 += M16_DEPTH) {
+#pragma unroll
+            for (int u = 0; u < M16_DEPTH; ++u) {
+                const bf16x8 A = __builtin_bit_cast(bf16x8, w[u]);
+                w[u] = wload(j0 + M16_DEPTH + u);
+                const int j = j0 + u;
+                if (j < nsl) {
+                    const uint4 bh = *reinterpret_cast<const uint4*>(&xs[0][li][j * 32 + lq * 8]);
+                    const uint4 bl = *reinterpret_cast<const uint4*>(&xs[1][li][j * 32 + lq * 8]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+                }
+            }
+        }
+    }
+    float* out = a.out + (size_t)ks * a.ks_stride;
+    const int nb = n0 + 4 * lq;
+    if (li < a.M) {
+        float* o = out + (size_t)li * a.ldo + nb;
+        if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
+            *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (nb + e < a.N) o[e] = acc[e];
+        }
+    }
+}
+
+// Columns per split of the 16-row kernel: 512, or 256 when that is needed to reach ~1000 workgroups.
+static int m16_kper(int N, int K) {
+    const int tiles = (N + 63) / 64;
+    int kper = M16_KMAX;
+    if ((long long)tiles * ((K + kper - 1) / kper) < 1024 && K > 256) kper = 256;
+    return kper;
+}
+
 // ---- GEMM, fp32 (plumbing configuration): one wavefront per output column, lanes stride K ----------
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -288,8 +376,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
 }
 
 // Split-K factor: enough workgroups to cover the chip a few times, at least two stages per split.
-int gemm_splits(int dtype, int N, int K) {
+int gemm_splits(int dtype, int N, int K, int M) {
     if (dtype != BS_BF16) return 1;
+    if (M <= 16) { const int kper = m16_kper(N, K); return (K + kper - 1) / kper; }
     const int tiles = (N + 63) / 64;
     const int stages = (K + 255) / 256;
     int ks = (768 + tiles - 1) / tiles;
@@ -347,13 +436,16 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
         const dim3 grid((a.N + 63) / 64, a.KS), block(256);
         const int mt = (c.M + 15) / 16;
+        const int kper = ((a.K + a.KS - 1) / a.KS + 31) / 32 * 32;      // columns per split, whole k slices
+        const bool m16 = a.M <= 16;
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (g_prof.on) {
             BS_HIP(hipEventCreate(&e0));
             BS_HIP(hipEventCreate(&e1));
             BS_HIP(hipEventRecord(e0, s));
         }
-        if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256>), grid, block, 0, s, c);
+        if (m16) hipLaunchKernelGGL(gemm_bf16_m16_kernel, grid, block, 0, s, c, kper);
+        else if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256>), grid, block, 0, s, c);
         else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 256>), grid, block, 0, s, c);
         else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 128>), grid, block, 0, s, c);
         else hipLaunchKernelGGL((gemm_bf16_kernel<6, 128>), grid, block, 0, s, c);
@@ -746,14 +838,31 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
     const int d = threadIdx.x;
     const size_t pstride = (size_t)hd + 2;
     const float* base = part + mh * n_splits * pstride;
+    // loads of up to 8 splits are issued together (they are independent), then combined
     float mm = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mm = fmaxf(mm, base[s * pstride]);
+    for (int s0 = 0; s0 < n_splits; s0 += 8) {
+        float mv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mv[u] = (s0 + u < n_splits) ? base[(s0 + u) * pstride] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mm = fmaxf(mm, mv[u]);
+    }
     float o = 0.f, l = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float ms = base[s * pstride];
-        const float f = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-        l += base[s * pstride + 1] * f;
-        o += base[s * pstride + 2 + d] * f;
+    for (int s0 = 0; s0 < n_splits; s0 += 8) {
+        float mv[8], lv[8], ov[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = s0 + u < n_splits;
+            mv[u] = ok ? base[(s0 + u) * pstride] : -INFINITY;
+            lv[u] = ok ? base[(s0 + u) * pstride + 1] : 0.f;
+            ov[u] = ok ? base[(s0 + u) * pstride + 2 + d] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float f = (mv[u] == -INFINITY) ? 0.f : __expf(mv[u] - mm);
+            l += lv[u] * f;
+            o += ov[u] * f;
+        }
     }
     Act<T>::store(out, plane, mh * hd + d, l > 0.f ? o / l : 0.f);
 }

@@ -109,10 +109,10 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     FwdWs w;
     const size_t M = (size_t)B * q_len;
     const size_t nq = (size_t)c.n_heads * c.head_dim, nkv = (size_t)c.n_kv_heads * c.head_dim;
-    w.ks_qkv = gemm_splits(c.dtype, (int)(nq + 2 * nkv), c.d_model);
-    w.ks_o = gemm_splits(c.dtype, c.d_model, (int)nq);
-    w.ks_gu = gemm_splits(c.dtype, 2 * c.d_ff, c.d_model);
-    w.ks_d = gemm_splits(c.dtype, c.d_model, c.d_ff);
+    w.ks_qkv = gemm_splits(c.dtype, (int)(nq + 2 * nkv), c.d_model, (int)M);
+    w.ks_o = gemm_splits(c.dtype, c.d_model, (int)nq, (int)M);
+    w.ks_gu = gemm_splits(c.dtype, 2 * c.d_ff, c.d_model, (int)M);
+    w.ks_d = gemm_splits(c.dtype, c.d_model, c.d_ff, (int)M);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return base ? base + o : (char*)nullptr; };
     w.status = (int32_t*)take(256);
@@ -133,9 +133,19 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     return w;
 }
 
+// The split-K factors depend on the row count, so the need is not monotone in q_len: take the largest.
+static size_t carve_max(const bs_model_cfg& c, int B, int max_q_len, int max_len) {
+    size_t need = 0;
+    for (int q = 1; q <= max_q_len; ++q) {
+        const size_t t = carve(c, B, q, max_len, nullptr).total;
+        if (t > need) need = t;
+    }
+    return need;
+}
+
 extern "C" __attribute__((visibility("default"))) size_t bs_forward_workspace_bytes(const bs_model_cfg* c, int B, int max_q_len, int max_len) {
     if (!c || B < 1 || max_q_len < 1 || max_len < 1) return 0;
-    return carve(*c, B, max_q_len, max_len, nullptr).total;
+    return carve_max(*c, B, max_q_len, max_len);
 }
 
 // One pass of the model over q_len tokens per sequence (see bs_verify_forward).  kv position of query j is
@@ -286,9 +296,9 @@ static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* dra
     w.margins = (float*)take((size_t)B * L * 4);
     w.draft_logits = (float*)take((size_t)B * L * t.vocab * 4);
     w.target_logits = (float*)take((size_t)B * (L + 1) * t.vocab * 4);
-    size_t f = carve(t, B, L + 1, max_len, nullptr).total;
+    size_t f = carve_max(t, B, L + 1, max_len);
     for (int i = 0; i < n_drafts; ++i) {
-        size_t fd = carve(*drafts[i], B, 2, max_len, nullptr).total;
+        size_t fd = carve_max(*drafts[i], B, 2, max_len);
         if (fd > f) f = fd;
     }
     w.fwd = take(f); w.fwd_bytes = f;
