@@ -172,7 +172,7 @@ def main():
 
     weights_bytes = sum(v.numel() * v.element_size() for k, v in target.weights.items() if not k.endswith("norm") and k != "embed")
     achieved = by1 / (ms1 * 1e-3) / 1e9 if ms1 > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel<1,256> (weight-streaming MFMA GEMM, <=16 activation rows)",
+    roofline = {"bound": "hbm", "kernel": "bs::gemm_bf16_m16_kernel (weight-streaming MFMA GEMM, <=16 activation rows; all launches of target and draft)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None, "launches": int(n1), "avg_us": round(ms1 * 1e3 / max(n1, 1), 3),
                 "avg_algorithmic_bytes": round(by1 / max(n1, 1), 1)}
