@@ -67,7 +67,8 @@ uint32_t bs_philox_word(uint64_t seed, uint32_t b, uint32_t t, uint32_t slot, ui
  *  dev_accept_len    [B] int32 out (tau);  dev_next_token [B] int32 out
  *  dev_margins       [B, gamma] float32 out or NULL: min(1,p/q) - u for every position (all tested)
  *  dev_workspace     bs_spec_sample_workspace_bytes(B, gamma) bytes, 16-byte aligned, contents ignored
- * gamma >= 0, B >= 0 (B == 0 is a no-op), 1 <= V <= 2^20, temperature > 0.
+ *                    (per-row softmax statistics)
+ * 0 <= gamma <= 512, B >= 0 (B == 0 is a no-op), 1 <= V <= 2^20, temperature > 0.
  * ---------------------------------------------------------------------------------------------- */
 size_t bs_spec_sample_workspace_bytes(int B, int gamma);
 int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
@@ -129,7 +130,9 @@ typedef struct bs_model bs_model;
 int bs_model_create(const bs_model_cfg* cfg, const bs_model_weights* dev_weights, bs_model** out);
 int bs_model_destroy(bs_model* m);
 
-/* KV cache bound to caller memory.  Layout [layer][K|V][B][kv_head][max_len][head_dim], model dtype. */
+/* KV cache bound to caller memory, model dtype, opaque to the caller.  Per layer K then V, each
+ * [B][kv_head][rows][head_dim] with rows = max_len rounded up to 32; in a bf16 cache V is held transposed in
+ * blocks of 32 keys ([rows/32][head_dim][32]) so that the matrix-core attention reads it without transposes. */
 typedef struct bs_kv bs_kv;
 size_t bs_kv_bytes(const bs_model_cfg* cfg, int B, int max_len);
 int bs_kv_bind(const bs_model* m, int B, int max_len, void* dev_buf, size_t bytes, bs_kv** out);

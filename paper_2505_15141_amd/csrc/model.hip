@@ -274,7 +274,7 @@ extern "C" __attribute__((visibility("default"))) int bs_prefill(const bs_model*
 struct RoundWs {
     uint32_t* round; int32_t* status;
     int32_t *q_draft2, *q_draft1, *q_target, *draft_tokens, *kvlen_draft, *kvlen_target, *flags, *cand, *active;
-    float *draft_logits, *target_logits, *margins;
+    float *draft_logits, *target_logits, *margins; void* stats;
     char* fwd; size_t fwd_bytes; size_t total;
 };
 
@@ -294,6 +294,7 @@ static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* dra
     w.cand = (int32_t*)take((size_t)B * (L + 1) * 4);
     w.active = (int32_t*)take((size_t)B * 4);
     w.margins = (float*)take((size_t)B * L * 4);
+    w.stats = take(spec_scratch_bytes(B, L));
     w.draft_logits = (float*)take((size_t)B * L * t.vocab * 4);
     w.target_logits = (float*)take((size_t)B * (L + 1) * t.vocab * 4);
     size_t f = carve_max(t, B, L + 1, max_len);
@@ -475,8 +476,8 @@ static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emit
                  (size_t)(gamma + 1) * V, w.fwd, w.fwd_bytes, s);
     if (rc != BS_OK) return rc;
     // ---- accept / reject, residual and bonus candidates ----
-    rc = launch_spec_rows(w.target_logits, w.draft_logits, w.draft_tokens, B, gamma, V, BS_F32, c.temperature, nullptr,
-                          c.seed, w.round, 0, w.flags, w.cand, w.margins, s);
+    rc = launch_spec_sample(w.target_logits, w.draft_logits, w.draft_tokens, B, gamma, V, BS_F32, c.temperature, nullptr,
+                            c.seed, w.round, 0, w.stats, w.flags, w.cand, nullptr, nullptr, w.margins, s);
     if (rc != BS_OK) return rc;
     // ---- commit ----
     hipLaunchKernelGGL(bs::round_commit_kernel, dim3((B + 127) / 128), dim3(128), 0, s, w.flags, w.cand, w.draft_tokens,

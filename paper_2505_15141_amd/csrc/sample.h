@@ -19,11 +19,14 @@ struct DrawParams {
 
 int launch_draw(const DrawParams& a, int B, hipStream_t stream);
 
-int launch_spec_rows(const void* p_logits, const void* q_logits, const int32_t* draft_tokens, int B, int gamma, int V,
-                     int dtype, float temperature, const float* uniforms, uint64_t seed, const uint32_t* round_ptr,
-                     uint32_t round, int32_t* flags, int32_t* cand, float* margins, hipStream_t stream);
+// Scratch for the per-row softmax statistics of one sampling call.
+size_t spec_scratch_bytes(int B, int gamma);
 
-int launch_spec_resolve(const int32_t* flags, const int32_t* cand, int B, int gamma, int32_t* accept_len,
-                        int32_t* next_token, hipStream_t stream);
+// Accept/reject + residual/bonus draw.  flags/cand [B, gamma+1] (round driver) and accept_len/next_token [B]
+// (stand-alone call) are optional outputs.
+int launch_spec_sample(const void* p_logits, const void* q_logits, const int32_t* draft_tokens, int B, int gamma, int V,
+                       int dtype, float temperature, const float* uniforms, uint64_t seed, const uint32_t* round_ptr,
+                       uint32_t round, void* stats_scratch, int32_t* flags, int32_t* cand, int32_t* accept_len,
+                       int32_t* next_token, float* margins, hipStream_t stream);
 
 }  // namespace bs

@@ -2,14 +2,13 @@
 // decoding: the loop over draft positions and the bonus draw), and the categorical draw used by
 // the draft steps.
 //
-// One workgroup of 512 lanes owns one (sequence, position) row pair (target row p, draft row q).
-// It reads both rows from HBM exactly once with 16-byte loads, keeps them in registers when the
-// vocabulary fits (V <= 32768), and produces
-//   * the acceptance decision  u * q(x~) <= p(x~)      (positions i < gamma)
-//   * the token an inverse-CDF draw would give if this position turned out to be the deciding one:
-//     from [p - q]_+ for i < gamma, from p for the bonus position i = gamma.
-// A second, tiny kernel walks the gamma flags of each sequence and picks the deciding position.
-// All positions are processed in parallel: nothing waits on the sequential accept chain.
+// Two kernels.  Phase A streams every logit row once (one workgroup per row) and leaves its softmax
+// statistics (max, sum of exp): this is the HBM-bound part, about 2 exponentials per logit.  Phase B runs
+// one workgroup per sequence: the gamma acceptance tests u * q(x~) <= p(x~) need only those statistics and
+// two logits each; the first failure fixes the deciding position, and only that row pair is read again
+// (from cache, it was just streamed), kept in registers when the vocabulary fits (V <= 32768), and sampled:
+// from [p - q]_+ if a draft token was rejected, from p at the bonus position otherwise.  The sequential
+// accept chain of the algorithm costs gamma scalar tests; the vocabulary-wide work is parallel.
 //
 // Reductions: per-lane online softmax (max, sum) -> wavefront shuffles -> LDS across 8 wavefronts.
 // Inverse CDF in increasing token id: lane t owns 8-token groups t, t+512, ...; "slab" k is the
@@ -138,7 +137,7 @@ struct RowResult {
 // x = drafted token for the acceptance test, or -1.
 template <typename T, int NG, bool CACHED>
 __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ q, bool has_q, int V, float inv_temp,
-                                 int x, float u_final, RowShared& sh) {
+                                 int x, float u_final, RowShared& sh, const float* known = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int ngroups = (V + GE - 1) / GE;
     const int nslabs = (ngroups + ST - 1) / ST;
@@ -171,13 +170,15 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
             pv[k] = (g < ngroups) ? load_raw_vec(p, g) : neg_inf_raw(p);
             qv[k] = (has_q && g < ngroups) ? load_raw_vec(q, g) : neg_inf_raw(p);
         }
+        if (!known) {
 #pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            online(mp, sp, pv[k]);
-            if (has_q) online(mq, sq, qv[k]);
-            __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the live set small
+            for (int k = 0; k < NG; ++k) {
+                online(mp, sp, pv[k]);
+                if (has_q) online(mq, sq, qv[k]);
+                __builtin_amdgcn_sched_barrier(0);   // one group at a time: keeps the live set small
+            }
         }
-    } else {
+    } else if (!known) {
         for (int g = tid; g < ngroups; g += ST) {
             online(mp, sp, load_raw(p, g, V, vec_p));
             if (has_q) online(mq, sq, load_raw(q, g, V, vec_q));
@@ -188,8 +189,10 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
 #pragma unroll
         for (int k = 0; k < NG; ++k) { keep_opaque(pv[k]); keep_opaque(qv[k]); }
     }
-    // block combine of (max, sum): maxima first, then rescaled sums
-    {
+    // block combine of (max, sum): maxima first, then rescaled sums (skipped when the row statistics are given)
+    if (known) {
+        mp = known[0]; sp = known[1]; mq = known[2]; sq = known[3];
+    } else {
         const float wmp = wave_max(mp), wmq = wave_max(mq);
         if (lane == 0) { sh.red[0][wid] = wmp; sh.red[1][wid] = wmq; }
         __syncthreads();
@@ -409,7 +412,58 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
     return res;
 }
 
-struct SampleParams {
+// ---- phase A: softmax statistics (max, sum of exp) of every logit row, target and draft alike ----------
+// One workgroup of 256 lanes per row, pure streaming: 16-byte loads, four in flight per lane, per-lane online
+// (max, sum), wavefront shuffles, LDS across the 4 wavefronts.  Rows: B*(gamma+1) target rows, then B*gamma
+// draft rows.  This is where the HBM bytes of the sampling step are read.
+template <typename T>
+__global__ __launch_bounds__(256) void row_stats_kernel(const T* __restrict__ p_logits, const T* __restrict__ q_logits,
+                                                        int n_p_rows, int V, float inv_temp, float2* __restrict__ stats) {
+    __shared__ float red[2][4];
+    const int r = blockIdx.x;
+    const T* row = r < n_p_rows ? p_logits + (size_t)r * V : q_logits + (size_t)(r - n_p_rows) * V;
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int ngroups = (V + GE - 1) / GE;
+    const bool vec = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
+    float m = -INFINITY, sum = 0.f;
+    auto online = [&](const Raw<T>& raw) {
+        float v[GE];
+        expand(raw, inv_temp, v);
+        float gm = v[0];
+#pragma unroll
+        for (int e = 1; e < GE; ++e) gm = fmaxf(gm, v[e]);
+        const float mn = fmaxf(m, gm);
+        if (mn == -INFINITY) return;
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < GE; ++e) acc += __expf(v[e] - mn);
+        sum = sum * __expf(m - mn) + acc;
+        m = mn;
+    };
+    int g = tid;
+    if (vec && V % GE == 0) {
+        for (; g + 3 * 256 < ngroups; g += 4 * 256) {
+            Raw<T> a0 = load_raw_vec(row, g), a1 = load_raw_vec(row, g + 256), a2 = load_raw_vec(row, g + 512),
+                   a3 = load_raw_vec(row, g + 768);
+            online(a0); online(a1); online(a2); online(a3);
+        }
+    }
+    for (; g < ngroups; g += 256) online(load_raw(row, g, V, vec));
+    const float bm = wave_max(m);
+    if (lane == 0) red[0][wid] = bm;
+    __syncthreads();
+    const float mm = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    const float rs = wave_sum(m == -INFINITY ? 0.f : sum * __expf(m - mm));
+    if (lane == 0) red[1][wid] = rs;
+    __syncthreads();
+    if (tid == 0) stats[r] = make_float2(mm, red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+}
+
+// ---- phase B: acceptance tests and the one draw each sequence needs -------------------------------------
+// One workgroup per sequence.  Lanes 0..gamma-1 evaluate  u_i * q_i(x~_i) <= p_i(x~_i)  from the row statistics
+// (two scalar loads each); tau = number of leading acceptances; then the workgroup re-reads only the deciding
+// row pair (tau < gamma: residual [p - q]_+, else the bonus row) and draws by inverse CDF.
+struct DecideParams {
     const void* p_logits;
     const void* q_logits;
     const int32_t* draft_tokens;
@@ -417,54 +471,62 @@ struct SampleParams {
     uint64_t seed;
     const uint32_t* round_ptr;
     uint32_t round;
-    int gamma, V;
+    int gamma, V, n_p_rows;
     float inv_temp;
-    int32_t* flags;      // [B, gamma+1]
-    int32_t* cand;       // [B, gamma+1]
-    float* margins;      // [B, gamma] or null
+    const float2* stats;
+    int32_t* flags;        // [B, gamma+1] or null: bit 0 accepted, bit 1 residual fallback (at the deciding row)
+    int32_t* cand;         // [B, gamma+1] or null: token written at the deciding row
+    int32_t* accept_len;   // [B] or null
+    int32_t* next_token;   // [B] or null
+    float* margins;        // [B, gamma] or null
 };
 
 template <typename T, int NG, bool CACHED>
-__global__ __launch_bounds__(ST) void spec_rowpair_kernel(SampleParams a) {
+__global__ __launch_bounds__(ST) void spec_decide_kernel(DecideParams a) {
     __shared__ RowShared sh;
-    const int row = blockIdx.x;
-    const int b = row / (a.gamma + 1), i = row % (a.gamma + 1);
-    const bool has_q = i < a.gamma;
-    const T* p = reinterpret_cast<const T*>(a.p_logits) + (size_t)row * a.V;
-    const T* q = has_q ? reinterpret_cast<const T*>(a.q_logits) + ((size_t)b * a.gamma + i) * a.V : nullptr;
+    __shared__ int s_acc[ST];
+    __shared__ float s_known[4];
+    const int b = blockIdx.x, tid = threadIdx.x, gamma = a.gamma;
+    const T* P = reinterpret_cast<const T*>(a.p_logits) + (size_t)b * (gamma + 1) * a.V;
+    const T* Q = reinterpret_cast<const T*>(a.q_logits) + (size_t)b * gamma * a.V;
     const uint32_t t = a.round_ptr ? *a.round_ptr : a.round;
-    int x = -1;
-    if (has_q) {
-        x = a.draft_tokens[(size_t)b * a.gamma + i];
-        if (x < 0 || x >= a.V) x = -1;
+    for (int i = tid; i < gamma; i += ST) {
+        int x = a.draft_tokens[(size_t)b * gamma + i];
+        const bool okx = x >= 0 && x < a.V;
+        if (!okx) x = 0;
+        const float2 sp = a.stats[(size_t)b * (gamma + 1) + i], sq = a.stats[a.n_p_rows + (size_t)b * gamma + i];
+        const float px = __expf(load_one<T>(P + (size_t)i * a.V, x) * a.inv_temp - sp.x) / sp.y;
+        const float qx = __expf(load_one<T>(Q + (size_t)i * a.V, x) * a.inv_temp - sq.x) / sq.y;
+        const float u = a.uniforms ? a.uniforms[(size_t)b * (gamma + 1) + i]
+                                   : u_open_closed(philox_word(a.seed, (uint32_t)b, t, (uint32_t)i, PURPOSE_ACCEPT));
+        const int acc = okx && (u * qx <= px);
+        s_acc[i] = acc;
+        if (a.flags) a.flags[(size_t)b * (gamma + 1) + i] = acc;
+        if (a.margins) a.margins[(size_t)b * gamma + i] = okx ? ((qx > 0.f) ? fminf(1.f, px / qx) : 1.f) - u : -1.f;
     }
-    const float u_final = a.uniforms ? a.uniforms[(size_t)b * (a.gamma + 1) + a.gamma]
-                                     : u_closed_open(philox_word(a.seed, (uint32_t)b, t, 0u, PURPOSE_FINAL));
-    const RowResult r = process_row<T, NG, CACHED>(p, q, has_q, a.V, a.inv_temp, x, u_final, sh);
-    if (threadIdx.x == 0) {
-        int accept = 0;
-        if (has_q) {
-            const float u = a.uniforms ? a.uniforms[(size_t)b * (a.gamma + 1) + i]
-                                       : u_open_closed(philox_word(a.seed, (uint32_t)b, t, (uint32_t)i, PURPOSE_ACCEPT));
-            accept = (x >= 0) && (u * r.q_x <= r.p_x);
-            if (a.margins) {
-                const float ratio = (r.q_x > 0.f) ? fminf(1.f, r.p_x / r.q_x) : 1.f;
-                a.margins[(size_t)b * a.gamma + i] = (x >= 0) ? ratio - u : -1.f;
-            }
-        }
-        a.flags[row] = accept | (r.fallback << 1);
-        a.cand[row] = r.token;
-    }
-}
-
-__global__ void spec_resolve_kernel(const int32_t* __restrict__ flags, const int32_t* __restrict__ cand, int B,
-                                    int gamma, int32_t* __restrict__ accept_len, int32_t* __restrict__ next_token) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
+    __syncthreads();
     int tau = 0;
-    while (tau < gamma && (flags[(size_t)b * (gamma + 1) + tau] & 1)) ++tau;
-    accept_len[b] = tau;
-    next_token[b] = cand[(size_t)b * (gamma + 1) + tau];
+    while (tau < gamma && s_acc[tau]) ++tau;
+    const bool has_q = tau < gamma;
+    if (tid == 0) {
+        const float2 sp = a.stats[(size_t)b * (gamma + 1) + tau];
+        s_known[0] = sp.x; s_known[1] = sp.y; s_known[2] = 0.f; s_known[3] = 1.f;
+        if (has_q) {
+            const float2 sq = a.stats[a.n_p_rows + (size_t)b * gamma + tau];
+            s_known[2] = sq.x; s_known[3] = sq.y;
+        }
+    }
+    __syncthreads();
+    const float u_final = a.uniforms ? a.uniforms[(size_t)b * (gamma + 1) + gamma]
+                                     : u_closed_open(philox_word(a.seed, (uint32_t)b, t, 0u, PURPOSE_FINAL));
+    const RowResult r = process_row<T, NG, CACHED>(P + (size_t)tau * a.V, has_q ? Q + (size_t)tau * a.V : nullptr, has_q,
+                                                   a.V, a.inv_temp, -1, u_final, sh, s_known);
+    if (tid == 0) {
+        if (a.flags) a.flags[(size_t)b * (gamma + 1) + tau] = (r.fallback << 1);     // bit 0 clear: not accepted / bonus row
+        if (a.cand) a.cand[(size_t)b * (gamma + 1) + tau] = r.token;
+        if (a.accept_len) a.accept_len[b] = tau;
+        if (a.next_token) a.next_token[b] = r.token;
+    }
 }
 
 // Draft-step draw: x~ ~ softmax(logits[b] / T) with the Philox uniform (b, t, slot, DRAFT).
@@ -493,36 +555,40 @@ int launch_draw(const DrawParams& a, int B, hipStream_t stream) {
     return BS_OK;
 }
 
-int launch_spec_rows(const void* p_logits, const void* q_logits, const int32_t* draft_tokens, int B, int gamma, int V,
-                     int dtype, float temperature, const float* uniforms, uint64_t seed, const uint32_t* round_ptr,
-                     uint32_t round, int32_t* flags, int32_t* cand, float* margins, hipStream_t stream) {
-    if (B <= 0) return BS_OK;
-    SampleParams a;
-    a.p_logits = p_logits; a.q_logits = q_logits; a.draft_tokens = draft_tokens; a.uniforms = uniforms;
-    a.seed = seed; a.round_ptr = round_ptr; a.round = round; a.gamma = gamma; a.V = V;
-    a.inv_temp = 1.0f / temperature; a.flags = flags; a.cand = cand; a.margins = margins;
-    const dim3 grid((unsigned)(B * (gamma + 1))), block(ST);
-    // register-resident rows: 8 groups per lane of bf16 (V <= 32768), 2 groups per lane of float
-    const size_t esz = dtype == BS_BF16 ? 2 : 4;
-    const bool aligned = V % GE == 0 && ((uintptr_t)p_logits & 15) == 0 && ((uintptr_t)q_logits & 15) == 0;
-    (void)esz;
-    const bool cached = aligned && V <= (dtype == BS_BF16 ? 8 : 2) * ST * GE;
-    if (dtype == BS_BF16) {
-        if (cached) hipLaunchKernelGGL((spec_rowpair_kernel<uint16_t, 8, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((spec_rowpair_kernel<uint16_t, 1, false>), grid, block, 0, stream, a);
-    } else {
-        if (cached) hipLaunchKernelGGL((spec_rowpair_kernel<float, 2, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((spec_rowpair_kernel<float, 1, false>), grid, block, 0, stream, a);
-    }
-    BS_LAUNCH_CHECK();
-    return BS_OK;
+size_t spec_scratch_bytes(int B, int gamma) {
+    return align_up((size_t)B * (2 * (size_t)gamma + 1) * sizeof(float2), 256);
 }
 
-int launch_spec_resolve(const int32_t* flags, const int32_t* cand, int B, int gamma, int32_t* accept_len,
-                        int32_t* next_token, hipStream_t stream) {
+int launch_spec_sample(const void* p_logits, const void* q_logits, const int32_t* draft_tokens, int B, int gamma, int V,
+                       int dtype, float temperature, const float* uniforms, uint64_t seed, const uint32_t* round_ptr,
+                       uint32_t round, void* stats_scratch, int32_t* flags, int32_t* cand, int32_t* accept_len,
+                       int32_t* next_token, float* margins, hipStream_t stream) {
     if (B <= 0) return BS_OK;
-    hipLaunchKernelGGL(spec_resolve_kernel, dim3((B + 255) / 256), dim3(256), 0, stream, flags, cand, B, gamma,
-                       accept_len, next_token);
+    const int n_p = B * (gamma + 1), n_rows = n_p + B * gamma;
+    float2* stats = reinterpret_cast<float2*>(stats_scratch);
+    const float inv_temp = 1.0f / temperature;
+    if (dtype == BS_BF16)
+        hipLaunchKernelGGL((row_stats_kernel<uint16_t>), dim3(n_rows), dim3(256), 0, stream, (const uint16_t*)p_logits,
+                           (const uint16_t*)q_logits, n_p, V, inv_temp, stats);
+    else
+        hipLaunchKernelGGL((row_stats_kernel<float>), dim3(n_rows), dim3(256), 0, stream, (const float*)p_logits,
+                           (const float*)q_logits, n_p, V, inv_temp, stats);
+    BS_LAUNCH_CHECK();
+    DecideParams a;
+    a.p_logits = p_logits; a.q_logits = q_logits; a.draft_tokens = draft_tokens; a.uniforms = uniforms; a.seed = seed;
+    a.round_ptr = round_ptr; a.round = round; a.gamma = gamma; a.V = V; a.n_p_rows = n_p; a.inv_temp = inv_temp;
+    a.stats = stats; a.flags = flags; a.cand = cand; a.accept_len = accept_len; a.next_token = next_token; a.margins = margins;
+    // register-resident deciding row: 8 groups per lane of bf16 (V <= 32768), 2 groups per lane of float
+    const bool aligned = V % GE == 0 && ((uintptr_t)p_logits & 15) == 0 && ((uintptr_t)q_logits & 15) == 0;
+    const bool cached = aligned && V <= (dtype == BS_BF16 ? 8 : 2) * ST * GE;
+    const dim3 grid(B), block(ST);
+    if (dtype == BS_BF16) {
+        if (cached) hipLaunchKernelGGL((spec_decide_kernel<uint16_t, 8, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((spec_decide_kernel<uint16_t, 1, false>), grid, block, 0, stream, a);
+    } else {
+        if (cached) hipLaunchKernelGGL((spec_decide_kernel<float, 2, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((spec_decide_kernel<float, 1, false>), grid, block, 0, stream, a);
+    }
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
@@ -531,7 +597,7 @@ int launch_spec_resolve(const int32_t* flags, const int32_t* cand, int B, int ga
 
 extern "C" __attribute__((visibility("default"))) size_t bs_spec_sample_workspace_bytes(int B, int gamma) {
     if (B < 0 || gamma < 0) return 0;
-    return bs::align_up((size_t)B * (size_t)(gamma + 1) * sizeof(int32_t), 256) * 2;
+    return bs::spec_scratch_bytes(B, gamma);
 }
 
 extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
@@ -541,7 +607,7 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void*
                               size_t workspace_bytes, void* stream) {
     BS_REQUIRE(B >= 0 && gamma >= 0, BS_EINVAL, "bs_spec_sample: B=%d gamma=%d must be >= 0", B, gamma);
     BS_REQUIRE(V >= 1 && V <= (1 << 20), BS_ESHAPE, "bs_spec_sample: V=%d outside [1, 2^20]", V);
-    BS_REQUIRE(gamma <= 1024, BS_ESHAPE, "bs_spec_sample: gamma=%d too large", gamma);
+    BS_REQUIRE(gamma <= 512, BS_ESHAPE, "bs_spec_sample: gamma=%d > 512", gamma);
     BS_REQUIRE((long long)B * (gamma + 1) < (1LL << 31), BS_ESHAPE, "bs_spec_sample: B*(gamma+1) overflows");
     BS_REQUIRE(dtype == BS_F32 || dtype == BS_BF16, BS_EDTYPE, "bs_spec_sample: dtype %d", dtype);
     BS_REQUIRE(temperature > 0.f && isfinite(temperature), BS_EINVAL, "bs_spec_sample: temperature %g", (double)temperature);
@@ -552,12 +618,7 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void*
     BS_REQUIRE(workspace_bytes >= bs_spec_sample_workspace_bytes(B, gamma), BS_EWORKSPACE,
                "bs_spec_sample: workspace %zu < %zu bytes", workspace_bytes, bs_spec_sample_workspace_bytes(B, gamma));
     BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 15) == 0, BS_EWORKSPACE, "bs_spec_sample: workspace misaligned");
-    int32_t* flags = reinterpret_cast<int32_t*>(dev_workspace);
-    int32_t* cand = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(dev_workspace) +
-                                               bs::align_up((size_t)B * (gamma + 1) * sizeof(int32_t), 256));
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    int rc = bs::launch_spec_rows(dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype, temperature,
-                                  dev_uniforms, seed, nullptr, round, flags, cand, dev_margins, s);
-    if (rc != BS_OK) return rc;
-    return bs::launch_spec_resolve(flags, cand, B, gamma, dev_accept_len, dev_next_token, s);
+    return bs::launch_spec_sample(dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype, temperature,
+                                  dev_uniforms, seed, nullptr, round, dev_workspace, nullptr, nullptr, dev_accept_len,
+                                  dev_next_token, dev_margins, reinterpret_cast<hipStream_t>(stream));
 }

@@ -96,5 +96,5 @@ def test_host_side_argument_checks_launch_nothing():
     assert bs.lib.bs_model_create(C.byref(cfg), C.byref(mw), C.byref(h)) == -2
     cfg.head_dim = 32
     assert bs.lib.bs_model_create(C.byref(cfg), C.byref(mw), C.byref(h)) == -1     # NULL weights
-    assert bs.lib.bs_kv_bytes(C.byref(cfg), 2, 100) == 1 * 2 * 2 * 2 * 100 * 32 * 4
+    assert bs.lib.bs_kv_bytes(C.byref(cfg), 2, 100) == 1 * 2 * 2 * 2 * 128 * 32 * 4    # rows padded to a multiple of 32
     assert bs.lib.bs_forward_workspace_bytes(C.byref(cfg), 2, 5, 100) > 0
