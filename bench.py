@@ -74,6 +74,63 @@ def cpu_baseline(tc, dc, prefix, gamma, mean_y):
             "seconds_measured": round(t_t0 + t_t1 + t_d0 + t_d1 + t_s, 2)}
 
 
+def stage_probes(bs, synth, torch, np, stream):
+    """HBM rates of the two other bandwidth-bound stages at the sizes where they matter (HIP-event timed):
+    the stand-alone sampling workload (B=64, gamma=8, V=32000, bf16 logits) and the verification attention
+    of one 7B-shaped layer at batch 16 with 4096 cached tokens per sequence."""
+    out = {}
+    with torch.cuda.stream(stream):
+        # ---- accept/reject + residual sampling ----
+        B, gamma, V, copies = 64, 8, 32000, 5                     # 5 x 70 MB of logits: more than the 256 MB last-level cache
+        g = torch.Generator(device="cuda"); g.manual_seed(7)
+        T = [(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 2).to(torch.bfloat16) for _ in range(copies)]
+        Q = [(t[:, :gamma].float() + 0.5 * torch.randn(B, gamma, V, generator=g, device="cuda")).to(torch.bfloat16) for t in T]
+        toks = [torch.multinomial(torch.softmax(q.float().view(-1, V), -1), 1).view(B, gamma).to(torch.int32) for q in Q]
+        u = torch.rand(B, gamma + 1, generator=g, device="cuda").clamp_(1e-6, 1 - 1e-6)
+        ws = torch.empty(bs.spec_sample_workspace_bytes(B, gamma), dtype=torch.uint8, device="cuda")
+        res = (torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
+        for i in range(3):
+            bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps, alg = 20, 0.0
+        e0.record(stream)
+        for i in range(reps):
+            bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
+        e1.record(stream); e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        acc = res[0].cpu().numpy()
+        alg = float(np.sum((acc + 1) + np.minimum(acc + 1, gamma))) * V * 2      # rows up to the deciding one
+        touched = B * (2 * gamma + 1) * V * 2
+        out["sampling"] = {"workload": "B=64 gamma=8 V=32000 bf16 logits", "us": round(us, 2),
+                           "touched_GBps": round(touched / us / 1e3, 1), "algorithmic_GBps": round(alg / us / 1e3, 1),
+                           "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4)}
+        del T, Q, toks
+        # ---- verification attention at batch 16, 4096 cached tokens, one 7B-shaped layer ----
+        c1 = dict(synth.LLAMA7B_TARGET, n_layers=1, vocab=1024)
+        m1 = bs.Model(c1, gpu_weights(c1, 9, torch))
+        Bb, ctx, q_len = 16, 4096, 9
+        kv1 = bs.KV(m1, Bb, ctx + 64)
+        kv1.buf.view(torch.int16).random_(-3000, 3000)            # small finite bf16 patterns in K and V
+        qtok = torch.randint(0, 1024, (Bb, q_len), dtype=torch.int32, device="cuda")
+        kvl = torch.full((Bb,), ctx, dtype=torch.int32, device="cuda")
+        wsf = torch.empty(m1.forward_workspace_bytes(Bb, q_len, ctx + 64), dtype=torch.uint8, device="cuda")
+        lg = torch.empty(Bb, q_len, 1024, dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            bs.verify_forward(m1, kv1, qtok, kvl, workspace=wsf, logits=lg)
+        stream.synchronize()
+        bs.profile_enable(True)
+        for _ in range(5):
+            bs.verify_forward(m1, kv1, qtok, kvl, workspace=wsf, logits=lg)
+            stream.synchronize()
+        ms_a, _, n_a = bs.profile_collect(100)
+        bs.profile_enable(False)
+        kv_bytes = 2 * (ctx + q_len) * c1["n_kv_heads"] * c1["head_dim"] * 2 * Bb
+        us_a = ms_a * 1e3 / max(n_a, 1)
+        out["attention_b16_ctx4096"] = {"us": round(us_a, 2), "kv_bytes": int(kv_bytes), "GBps": round(kv_bytes / us_a / 1e3, 1),
+                                        "frac_hbm": round(kv_bytes / us_a / 1e3 / HBM_PEAK_GBS, 4)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,6 +227,28 @@ def main():
         ms1, by1, n1 = bs.profile_collect(1)
         bs.profile_enable(False)
 
+        # target-shape launches only (the draft's 1-7 MB launches are latency-bound and pull the average down)
+        stream.synchronize()
+        kvl2 = (total - 1).to(torch.int32)
+        q9 = tokens[:, prefix - 1:prefix + 8].contiguous()
+        ws9 = torch.empty(target.forward_workspace_bytes(B, 9, max_len), dtype=torch.uint8, device="cuda")
+        lg9 = torch.empty(B, 9, tc["vocab"], dtype=torch.float32, device="cuda")
+        bs.profile_enable(True)
+        for _ in range(3):
+            bs.verify_forward(target, tkv, q9, kvl2, workspace=ws9, logits=lg9)
+            stream.synchronize()
+        ms_t, by_t, n_t = bs.profile_collect(1)
+        ms_a, _, n_a = bs.profile_collect(100)
+        bs.profile_enable(False)
+        n_keys = int(total[0].item()) - 1 + 9
+        attn_bytes_b1 = 2 * n_keys * tc["n_kv_heads"] * tc["head_dim"] * 2
+        stages = {"target_gemm": {"GBps": round(by_t / (ms_t * 1e-3) / 1e9, 1), "frac_hbm": round(by_t / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  "launches": int(n_t), "avg_us": round(ms_t * 1e3 / max(n_t, 1), 2)},
+                  "attention_b1": {"keys": n_keys, "avg_us": round(ms_a * 1e3 / max(n_a, 1), 2),
+                                   "GBps": round(attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9, 1)}}
+        del ws9, lg9
+
+    stages.update(stage_probes(bs, synth, torch, np, stream))
     weights_bytes = sum(v.numel() * v.element_size() for k, v in target.weights.items() if not k.endswith("norm") and k != "embed")
     achieved = by1 / (ms1 * 1e-3) / 1e9 if ms1 > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "bs::gemm_bf16_m16_kernel (weight-streaming MFMA GEMM, <=16 activation rows; all launches of target and draft)",
@@ -187,7 +266,7 @@ def main():
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-           "prefill_s": round(prefill_s, 3), "roofline": roofline}
+           "prefill_s": round(prefill_s, 3), "stages": stages, "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(tc, dc, prefix, 4, mean_y)
     print(json.dumps(out))

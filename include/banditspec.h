@@ -216,11 +216,13 @@ int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const flo
 
 /* ------------------------------------------------------------------------------------------------
  * Measurement hook (not part of the method): while enabled, every launch of the bf16 weight-streaming
- * GEMM made OUTSIDE a graph capture is bracketed by HIP events on its own stream.  bs_profile_collect
- * synchronises on those events and returns, for launches whose row-tile count (1, 2, 4 or 6 tiles of
- * 16 activation rows; 0 = all) matches, the summed kernel time in ms, the summed algorithmic bytes
- * (each weight element once: N*K*2) and the launch count.  Enabling clears earlier records.  Do not
- * enable while a graph is being captured.
+ * GEMM and of the bf16 attention kernel made OUTSIDE a graph capture is bracketed by HIP events on its
+ * own stream.  bs_profile_collect synchronises on those events and returns, for launches of the asked
+ * class, the summed kernel time in ms, the summed algorithmic bytes and the launch count.  Classes:
+ * 1, 2, 4, 6 = GEMM launches with that many tiles of 16 activation rows (bytes: each weight element
+ * once, N*K*2); 100 = attention (bytes reported as 0: the cache lengths live on the device, the caller
+ * knows them); 0 = everything.  Enabling clears earlier records.  Do not enable while a graph is being
+ * captured.
  * ---------------------------------------------------------------------------------------------- */
 int bs_profile_enable(int on);
 int bs_profile_collect(int row_tiles, double* host_total_ms, double* host_total_bytes, long long* host_launches);

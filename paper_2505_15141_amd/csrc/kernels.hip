@@ -960,6 +960,12 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
         const dim3 mgrid(n_splits, KVH, B);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (g_prof.on) {
+            BS_HIP(hipEventCreate(&e0));
+            BS_HIP(hipEventCreate(&e1));
+            BS_HIP(hipEventRecord(e0, s));
+        }
         if (hd == 128)
             hipLaunchKernelGGL((attn_mfma_kernel<128>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
                                (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part);
@@ -969,6 +975,12 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         else
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
         BS_LAUNCH_CHECK();
+        if (g_prof.on) {                                   // class 100: the split attention kernel (bytes known to the caller)
+            BS_HIP(hipEventRecord(e1, s));
+            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+            g_prof.bytes.push_back(0.0);
+            g_prof.mt.push_back(100);
+        }
         hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
