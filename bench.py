@@ -74,6 +74,18 @@ def cpu_baseline(tc, dc, prefix, gamma, mean_y):
             "seconds_measured": round(t_t0 + t_t1 + t_d0 + t_d1 + t_s, 2)}
 
 
+def pmc_traffic_ratio():
+    """HBM traffic / algorithmic bytes of the 16-row GEMM, from the committed counter summary (None if absent)."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "gemm_m16_hbm_traffic_pmc.txt")) as f:
+            for line in f:
+                if line.startswith("traffic_over_algorithmic="):
+                    return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def stage_probes(bs, synth, torch, np, stream):
     """HBM rates of the two other bandwidth-bound stages at the sizes where they matter (HIP-event timed):
     the stand-alone sampling workload (B=64, gamma=8, V=32000, bf16 logits) and the verification attention
@@ -139,7 +151,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=8)
+    ap.add_argument("--pmc-mode", action="store_true",
+                    help="for `rocprofv3 --pmc` runs: only the eager, event-timed rounds are executed, so the 16-row GEMM "
+                         "dispatches of the counter file are exactly the launches whose algorithmic bytes are printed")
     args = ap.parse_args()
+    if args.pmc_mode:
+        args.steps, args.warmup, args.no_cpu_baseline = 0, 0, True
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the round shards by sequence across GPUs without exchange; "
               "nothing is launched on more than one device). Use --gpus 1.", file=sys.stderr)
@@ -201,7 +218,7 @@ def main():
         # ---- verify-step latency (eager, HIP events on this stream), per gamma ----
         verify_ms = {}
         kvl = (total - 1).to(torch.int32)       # current cache length; rows written here are overwritten by later rounds
-        for g in gammas:
+        for g in ([] if args.pmc_mode else gammas):
             q = tokens[:, prefix - 1:prefix + g].contiguous()
             ws = torch.empty(target.forward_workspace_bytes(B, g + 1, max_len), dtype=torch.uint8, device="cuda")
             lg = torch.empty(B, g + 1, tc["vocab"], dtype=torch.float32, device="cuda")
@@ -227,37 +244,46 @@ def main():
         ms1, by1, n1 = bs.profile_collect(1)
         bs.profile_enable(False)
 
+        stages = {}
         # target-shape launches only (the draft's 1-7 MB launches are latency-bound and pull the average down)
         stream.synchronize()
         kvl2 = (total - 1).to(torch.int32)
         q9 = tokens[:, prefix - 1:prefix + 8].contiguous()
         ws9 = torch.empty(target.forward_workspace_bytes(B, 9, max_len), dtype=torch.uint8, device="cuda")
         lg9 = torch.empty(B, 9, tc["vocab"], dtype=torch.float32, device="cuda")
-        bs.profile_enable(True)
-        for _ in range(3):
-            bs.verify_forward(target, tkv, q9, kvl2, workspace=ws9, logits=lg9)
-            stream.synchronize()
-        ms_t, by_t, n_t = bs.profile_collect(1)
-        ms_a, _, n_a = bs.profile_collect(100)
-        bs.profile_enable(False)
-        n_keys = int(total[0].item()) - 1 + 9
-        attn_bytes_b1 = 2 * n_keys * tc["n_kv_heads"] * tc["head_dim"] * 2
-        stages = {"target_gemm": {"GBps": round(by_t / (ms_t * 1e-3) / 1e9, 1), "frac_hbm": round(by_t / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                  "launches": int(n_t), "avg_us": round(ms_t * 1e3 / max(n_t, 1), 2)},
-                  "attention_b1": {"keys": n_keys, "avg_us": round(ms_a * 1e3 / max(n_a, 1), 2),
-                                   "GBps": round(attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9, 1)}}
+        if not args.pmc_mode:
+            bs.profile_enable(True)
+            for _ in range(3):
+                bs.verify_forward(target, tkv, q9, kvl2, workspace=ws9, logits=lg9)
+                stream.synchronize()
+            ms_t, by_t, n_t = bs.profile_collect(1)
+            ms_a, _, n_a = bs.profile_collect(100)
+            bs.profile_enable(False)
+            n_keys = int(total[0].item()) - 1 + 9
+            attn_bytes_b1 = 2 * n_keys * tc["n_kv_heads"] * tc["head_dim"] * 2
+            stages = {"target_gemm": {"GBps": round(by_t / (ms_t * 1e-3) / 1e9, 1), "frac_hbm": round(by_t / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                      "launches": int(n_t), "avg_us": round(ms_t * 1e3 / max(n_t, 1), 2)},
+                      "attention_b1": {"keys": n_keys, "avg_us": round(ms_a * 1e3 / max(n_a, 1), 2),
+                                       "GBps": round(attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9, 1)}}
         del ws9, lg9
 
-    stages.update(stage_probes(bs, synth, torch, np, stream))
+    if not args.pmc_mode:
+        stages.update(stage_probes(bs, synth, torch, np, stream))
+    # a plain device copy of known size: the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a --pmc run
+    cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     weights_bytes = sum(v.numel() * v.element_size() for k, v in target.weights.items() if not k.endswith("norm") and k != "embed")
     achieved = by1 / (ms1 * 1e-3) / 1e9 if ms1 > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "bs::gemm_bf16_m16_kernel (weight-streaming MFMA GEMM, <=16 activation rows; all launches of target and draft)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "launches": int(n1), "avg_us": round(ms1 * 1e3 / max(n1, 1), 3),
+                "traffic": (round(by1 / max(n1, 1) * pmc_traffic_ratio(), 1) if pmc_traffic_ratio() else None), "launches": int(n1), "avg_us": round(ms1 * 1e3 / max(n1, 1), 3),
                 "avg_algorithmic_bytes": round(by1 / max(n1, 1), 1)}
-    mean_y = float(np.mean(ys))
-    out = {"metric": "generated tokens/s at 1 GPU", "value": round(gen_tokens / elapsed, 2), "unit": "tokens/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+    mean_y = float(np.mean(ys)) if ys else 0.0
+    out = {"metric": "generated tokens/s at 1 GPU", "value": round(gen_tokens / elapsed, 2) if args.steps else 0.0, "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / max(args.steps, 1) * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "Llama-7B-shaped verification (32x4096, 32 heads x128, FFN 11008, vocab 32000) with a 12-layer "
                                   "d=768 draft, batch 1, prefix 1024, UCBSpec over gamma in {2,4,6,8}, random-init bf16 weights",
@@ -265,7 +291,7 @@ def main():
            "mean_accepted_tokens": round(mean_y, 4), "generated_tokens": int(gen_tokens),
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
-           "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
            "prefill_s": round(prefill_s, 3), "stages": stages, "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(tc, dc, prefix, 4, mean_y)
