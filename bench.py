@@ -119,7 +119,7 @@ def stage_probes(bs, synth, torch, np, stream):
         del T, Q, toks
         # ---- verification attention at batch 16, 4096 cached tokens, one 7B-shaped layer ----
         c1 = dict(synth.LLAMA7B_TARGET, n_layers=1, vocab=1024)
-        m1 = bs.Model(c1, gpu_weights(c1, 9, torch))
+        m1 = bs.Model(c1, gpu_weights(c1, 9, torch)).pack(release_originals=True)
         Bb, ctx, q_len = 16, 4096, 9
         kv1 = bs.KV(m1, Bb, ctx + 64)
         kv1.buf.view(torch.int16).random_(-3000, 3000)            # small finite bf16 patterns in K and V
@@ -174,8 +174,9 @@ def main():
     max_len = prefix + (L + 1) * total_rounds + L + 2
     seed = 2025
 
-    target = bs.Model(tc, gpu_weights(tc, 1, torch))
-    draft = bs.Model(dc, gpu_weights(dc, 2, torch))
+    # projections in the library's tiled layout (bs_model_pack); the row-major originals are released
+    target = bs.Model(tc, gpu_weights(tc, 1, torch)).pack(release_originals=True)
+    draft = bs.Model(dc, gpu_weights(dc, 2, torch)).pack(release_originals=True)
     tkv, dkv = bs.KV(target, B, max_len), bs.KV(draft, B, max_len)
     tokens = torch.zeros(B, max_len, dtype=torch.int32, device="cuda")
     tokens[:, :prefix] = torch.from_numpy(synth.make_prompts(B, prefix, tc["vocab"], 3).astype(np.int32)).cuda()
@@ -275,7 +276,9 @@ def main():
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
     del cal_src, cal_dst
-    weights_bytes = sum(v.numel() * v.element_size() for k, v in target.weights.items() if not k.endswith("norm") and k != "embed")
+    nq_t, nkv_t = tc["n_heads"] * tc["head_dim"], tc["n_kv_heads"] * tc["head_dim"]
+    weights_bytes = 2 * (tc["n_layers"] * (tc["d_model"] * (nq_t + 2 * nkv_t) + nq_t * tc["d_model"] + 3 * tc["d_model"] * tc["d_ff"])
+                         + tc["vocab"] * tc["d_model"])            # every projection and the LM head once, bf16
     achieved = by1 / (ms1 * 1e-3) / 1e9 if ms1 > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "bs::gemm_bf16_m16_kernel (weight-streaming MFMA GEMM, <=16 activation rows; all launches of target and draft)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -130,6 +130,20 @@ typedef struct bs_model bs_model;
 int bs_model_create(const bs_model_cfg* cfg, const bs_model_weights* dev_weights, bs_model** out);
 int bs_model_destroy(bs_model* m);
 
+/* Optional re-layout of a bf16 model's projection matrices and LM head for the verification pass (App. A: the
+ * target scores gamma+1 positions at once, so every weight is read exactly once per pass and the pass runs at
+ * the speed the weights stream from HBM).  The copy is cut into 64-row x 32-column blocks,
+ * [rows/64][cols/32][4][64][8] bf16 with rows padded to 64, so that each matrix-core operand is one
+ * contiguous kilobyte.  bs_model_packed_bytes: size of the copy, 0 if the model cannot be packed (fp32, or
+ * d_model / n_heads*head_dim / d_ff not multiples of 32, or n_kv_heads*head_dim not a multiple of 16).
+ * bs_model_pack: dev_buf is device memory of at least that size, 256-byte aligned, owned by the caller and
+ * kept alive for the model's lifetime; the copy is enqueued on `stream` (a hipStream_t, NULL = default).
+ * After it completes the model no longer reads the row-major projections (embedding and norm gains are still
+ * read from the original pointers), so the caller may free them.  Results are bit-identical to the unpacked
+ * model.  Errors: BS_EINVAL (NULL), BS_ESTATE (already packed), BS_ESHAPE, BS_EWORKSPACE. */
+size_t bs_model_packed_bytes(const bs_model_cfg* cfg);
+int bs_model_pack(bs_model* m, void* dev_buf, size_t bytes, void* stream);
+
 /* KV cache bound to caller memory, model dtype, opaque to the caller.  Per layer K then V, each
  * [B][kv_head][rows][head_dim] with rows = max_len rounded up to 32; in a bf16 cache V is held transposed in
  * blocks of 32 keys ([rows/32][head_dim][32]) so that the matrix-core attention reads it without transposes. */

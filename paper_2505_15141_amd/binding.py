@@ -18,6 +18,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 BS_OK = 0
+BS_EINVAL, BS_ESHAPE, BS_EDTYPE, BS_EWORKSPACE, BS_ESTATE, BS_EHIP = -1, -2, -3, -4, -5, -6
 BS_F32, BS_BF16 = 0, 1
 BS_UCBSPEC, BS_EXP3SPEC = 0, 1
 DTYPES = {"f32": BS_F32, "bf16": BS_BF16, torch.float32: BS_F32, torch.bfloat16: BS_BF16}
@@ -67,6 +68,8 @@ _sig("bs_bandit_probs", C.c_int, vp, C.POINTER(f64))
 _sig("bs_bandit_stats", C.c_int, vp, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_int64))
 _sig("bs_model_create", C.c_int, C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(vp))
 _sig("bs_model_destroy", C.c_int, vp)
+_sig("bs_model_packed_bytes", sz, C.POINTER(ModelCfg))
+_sig("bs_model_pack", C.c_int, vp, vp, sz, vp)
 _sig("bs_kv_bytes", sz, C.POINTER(ModelCfg), C.c_int, C.c_int)
 _sig("bs_kv_bind", C.c_int, vp, C.c_int, C.c_int, vp, sz, C.POINTER(vp))
 _sig("bs_kv_destroy", C.c_int, vp)
@@ -201,6 +204,23 @@ class Model:
             t = torch.from_numpy(v).to(device)
             dev[k] = t.float().contiguous() if k.endswith("norm") else t.to(td).contiguous()
         return Model(c, dev)
+
+    def packed_bytes(self):
+        return lib.bs_model_packed_bytes(C.byref(self.cfg))
+
+    def pack(self, release_originals=False):
+        """Re-layout the projections for the weight-streaming kernels (bs_model_pack); the copy lives in self.packed."""
+        n = self.packed_bytes()
+        if n == 0:
+            raise RuntimeError("this model cannot be packed (needs bf16 and dimensions that are multiples of 32)")
+        self.packed = torch.empty(n, dtype=torch.uint8, device=self.weights["embed"].device)
+        check(lib.bs_model_pack(self.h, ptr(self.packed), n, vp(torch.cuda.current_stream().cuda_stream)))
+        torch.cuda.current_stream().synchronize()
+        if release_originals:
+            for k in list(self.weights):
+                if not k.endswith("norm") and k != "embed":
+                    del self.weights[k]
+        return self
 
     def kv_bytes(self, B, max_len):
         return lib.bs_kv_bytes(C.byref(self.cfg), B, max_len)

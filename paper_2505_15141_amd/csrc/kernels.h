@@ -14,12 +14,15 @@ struct GemmArgs {
     float* out;           // split-K partials [KS][M][ldo] float32 (slice stride ks_stride elements)
     size_t ks_stride;
     int M, N, K, ldo, KS;
+    int tiled;            // weights are in the 64x32-block layout written by launch_pack_weights
 };
 
 int gemm_splits(int dtype, int N, int K, int M);
 int profile_enable(int on);
 int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches);
 int launch_gemm(int dtype, GemmArgs a, hipStream_t s);
+size_t packed_elems(int N, int K);                       // elements of the tiled copy of an [N][K] matrix
+int launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
 
 int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, int kv_base, int B, int q_len,
                 int max_len, int V, int hd, float rope_base, int32_t* pos, int32_t* tok, float2* rope,

@@ -14,7 +14,8 @@ struct bs_model {
     const void* embed;
     const float* final_norm;
     const void* lm_head;
-    std::vector<bs_layer_weights> layers;
+    std::vector<bs_layer_weights> layers;   // projections point into the packed copy once bs_model_pack has run
+    bool packed = false;
 };
 
 struct bs_kv {
@@ -67,6 +68,53 @@ extern "C" __attribute__((visibility("default"))) int bs_model_create(const bs_m
 }
 
 extern "C" __attribute__((visibility("default"))) int bs_model_destroy(bs_model* m) { delete m; return BS_OK; }
+
+// ---- tiled copy of the projection matrices -----------------------------------------------------------
+static bool packable(const bs_model_cfg& c) {
+    const int nq = c.n_heads * c.head_dim, nkv = c.n_kv_heads * c.head_dim;
+    return c.dtype == BS_BF16 && c.d_model % 32 == 0 && nq % 32 == 0 && c.d_ff % 32 == 0 && nq % 16 == 0 && nkv % 16 == 0 && c.d_ff % 16 == 0;
+}
+
+extern "C" __attribute__((visibility("default"))) size_t bs_model_packed_bytes(const bs_model_cfg* c) {
+    if (!c || !packable(*c)) return 0;
+    const int nq = c->n_heads * c->head_dim, nkv = c->n_kv_heads * c->head_dim;
+    size_t per_layer = 0;
+    auto add = [&](int N, int K) { per_layer += align_up(packed_elems(N, K) * 2, 256); };
+    add(nq, c->d_model); add(nkv, c->d_model); add(nkv, c->d_model); add(c->d_model, nq);
+    add(c->d_ff, c->d_model); add(c->d_ff, c->d_model); add(c->d_model, c->d_ff);
+    return per_layer * c->n_layers + align_up(packed_elems(c->vocab, c->d_model) * 2, 256);
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_model_pack(bs_model* m, void* dev_buf, size_t bytes, void* stream) {
+    BS_REQUIRE(m && dev_buf, BS_EINVAL, "bs_model_pack: NULL argument");
+    BS_REQUIRE(!m->packed, BS_ESTATE, "bs_model_pack: model is already packed");
+    const bs_model_cfg& c = m->cfg;
+    const size_t need = bs_model_packed_bytes(&c);
+    BS_REQUIRE(need > 0, BS_ESHAPE, "bs_model_pack: needs a bf16 model whose d_model, n_heads*head_dim and d_ff are multiples of 32 "
+                                    "and whose n_kv_heads*head_dim is a multiple of 16");
+    BS_REQUIRE(bytes >= need, BS_EWORKSPACE, "bs_model_pack: buffer %zu < %zu bytes", bytes, need);
+    BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_buf) & 255) == 0, BS_EWORKSPACE, "bs_model_pack: buffer not 256-byte aligned");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const int nq = c.n_heads * c.head_dim, nkv = c.n_kv_heads * c.head_dim;
+    char* cur = reinterpret_cast<char*>(dev_buf);
+    int rc = BS_OK;
+    auto pack = [&](const void*& w, int N, int K) {
+        if (rc != BS_OK) return;
+        rc = launch_pack_weights(w, cur, N, K, s);
+        w = cur;
+        cur += align_up(packed_elems(N, K) * 2, 256);
+    };
+    std::vector<bs_layer_weights> layers = m->layers;
+    const void* head = m->lm_head;
+    for (bs_layer_weights& L : layers) {
+        pack(L.wq, nq, c.d_model); pack(L.wk, nkv, c.d_model); pack(L.wv, nkv, c.d_model); pack(L.wo, c.d_model, nq);
+        pack(L.w_gate, c.d_ff, c.d_model); pack(L.w_up, c.d_ff, c.d_model); pack(L.w_down, c.d_model, c.d_ff);
+    }
+    pack(head, c.vocab, c.d_model);
+    if (rc != BS_OK) return rc;
+    m->layers = layers; m->lm_head = head; m->packed = true;
+    return BS_OK;
+}
 
 extern "C" __attribute__((visibility("default"))) size_t bs_kv_bytes(const bs_model_cfg* c, int B, int max_len) {
     if (!c || B < 1 || max_len < 1) return 0;
@@ -178,6 +226,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, c.norm_eps, B, q_len, q_len,
                               (size_t)M * d, w.h, s));
         GemmArgs g;
+        g.tiled = m->packed ? 1 : 0;
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
         g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
         BS_TRY(launch_gemm(dt, g, s));
@@ -204,6 +253,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, m->final_norm, d, c.norm_eps, B, q_len, logit_rows,
                               (size_t)R * d, w.h, s));
         GemmArgs g;
+        g.tiled = m->packed ? 1 : 0;
         g.x_plane = (size_t)R * d;
         g.w[0] = m->lm_head; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = c.vocab; g.seg_rows[1] = 0;
         g.N = c.vocab; g.K = d; g.KS = 1; g.ks_stride = 0;

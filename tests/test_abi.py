@@ -98,3 +98,8 @@ def test_host_side_argument_checks_launch_nothing():
     assert bs.lib.bs_model_create(C.byref(cfg), C.byref(mw), C.byref(h)) == -1     # NULL weights
     assert bs.lib.bs_kv_bytes(C.byref(cfg), 2, 100) == 1 * 2 * 2 * 2 * 128 * 32 * 4    # rows padded to a multiple of 32
     assert bs.lib.bs_forward_workspace_bytes(C.byref(cfg), 2, 5, 100) > 0
+    assert bs.lib.bs_model_packed_bytes(C.byref(cfg)) == 0                           # fp32: no tiled copy
+    big = bs.model_cfg(dict(n_layers=2, d_model=96, n_heads=2, n_kv_heads=1, head_dim=64, d_ff=160, vocab=1000, dtype="bf16"))
+    per_layer = (128 * 96 + 2 * 64 * 96 + 128 * 128 + 2 * 192 * 96 + 128 * 160) * 2   # rows padded to multiples of 64
+    assert bs.lib.bs_model_packed_bytes(C.byref(big)) == 2 * per_layer + 1024 * 96 * 2
+    assert bs.lib.bs_model_pack(None, None, 0, None) == -1

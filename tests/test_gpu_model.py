@@ -20,22 +20,27 @@ MID = synth.cfg(4, 512, 8, 64, 1408, 4096, dtype="bf16")
 MID_GQA = synth.cfg(3, 512, 8, 64, 1024, 2048, n_kv_heads=2, dtype="bf16")
 WIDE = synth.cfg(2, 1024, 8, 128, 2816, 8192, n_kv_heads=2, dtype="bf16")
 ODD_F32 = synth.cfg(2, 72, 3, 24, 104, 130, dtype="f32")
+ODD_BF16 = synth.cfg(2, 96, 2, 64, 160, 1000, n_kv_heads=1, dtype="bf16")   # row counts that are not multiples of 64
 
 
-def setup(c, B, max_len, seed, std=None):
+def setup(c, B, max_len, seed, std=None, packed=False):
     W = synth.make_weights(c, seed, std if std is not None else 0.02 * (4096 / c["d_model"]) ** 0.5 if c["dtype"] == "bf16" else 0.02)
     if c["dtype"] == "bf16":
         W = {k: (v if k.endswith("norm") else synth.to_bf16_grid(v)) for k, v in W.items()}
     m = bs().Model.from_numpy(c, W)
+    if packed:
+        m.pack(release_originals=True)
     kv = bs().KV(m, B, max_len)
     return W, m, kv
 
 
-@pytest.mark.parametrize("c,B,n_prefix,q_len", [
-    (synth.TINY_TARGET, 1, 32, 5), (synth.TINY_DRAFT, 2, 9, 3), (ODD_F32, 3, 17, 4),
-    (MID, 1, 70, 9), (MID_GQA, 2, 130, 5), (WIDE, 1, 200, 9), (MID, 3, 1, 2)])
-def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len):
-    W, m, kv = setup(c, B, 300, seed=3)
+@pytest.mark.parametrize("c,B,n_prefix,q_len,packed", [
+    (synth.TINY_TARGET, 1, 32, 5, False), (synth.TINY_DRAFT, 2, 9, 3, False), (ODD_F32, 3, 17, 4, False),
+    (MID, 1, 70, 9, False), (MID_GQA, 2, 130, 5, False), (WIDE, 1, 200, 9, False), (MID, 3, 1, 2, False),
+    (MID, 1, 70, 9, True), (MID_GQA, 2, 130, 5, True), (WIDE, 1, 200, 9, True), (MID, 3, 1, 2, True),
+    (ODD_BF16, 1, 40, 7, False), (ODD_BF16, 2, 150, 3, True)])
+def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
+    W, m, kv = setup(c, B, 300, seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
     dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
     last = bs().prefill(m, kv, dtoks, n_prefix, want_logits=True)
@@ -50,6 +55,39 @@ def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len):
         got = logits[b].cpu().numpy()
         assert got.shape == (q_len, c["vocab"])
         assert np.max(np.abs(got - ref[n_prefix:n_prefix + q_len])) < tol, np.max(np.abs(got - ref[n_prefix:n_prefix + q_len]))
+
+
+@pytest.mark.parametrize("c,B,n_prefix,q_len", [(MID_GQA, 2, 140, 9), (ODD_BF16, 1, 33, 5), (WIDE, 1, 20, 16)])
+def test_packed_weights_give_bit_identical_logits(c, B, n_prefix, q_len):
+    """The tiled copy only changes where each weight is read from, not the order of the arithmetic."""
+    outs = []
+    for packed in (False, True):
+        W, m, kv = setup(c, B, 200, seed=11, packed=packed)
+        toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=12)
+        dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
+        last = bs().prefill(m, kv, dtoks, n_prefix, want_logits=True)
+        kvl = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
+        logits = bs().verify_forward(m, kv, dtoks[:, n_prefix:n_prefix + q_len].contiguous(), kvl)
+        torch.cuda.synchronize()
+        outs.append((last.cpu().numpy().copy(), logits.cpu().numpy().copy()))
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+
+
+def test_pack_errors():
+    b = bs()
+    m = b.Model.from_numpy(synth.TINY_TARGET, synth.make_weights(synth.TINY_TARGET, 1))
+    assert m.packed_bytes() == 0                      # fp32 models are not packed
+    with pytest.raises(RuntimeError):
+        m.pack()
+    W, m2, _ = setup(MID, 1, 64, seed=2)
+    n = m2.packed_bytes()
+    assert n >= sum(v.size for k, v in W.items() if not k.endswith("norm") and k != "embed") * 2
+    small = torch.empty(n - 256, dtype=torch.uint8, device="cuda")
+    assert b.lib.bs_model_pack(m2.h, b.ptr(small), small.numel(), None) == b.BS_EWORKSPACE
+    m2.pack()
+    again = torch.empty(n, dtype=torch.uint8, device="cuda")
+    assert b.lib.bs_model_pack(m2.h, b.ptr(again), n, None) == b.BS_ESTATE
 
 
 def test_ragged_cache_lengths_and_logit_rows():
