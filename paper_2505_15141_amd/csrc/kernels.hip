@@ -398,12 +398,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_m16_kernel(GemmArgs a, int kper
     }
 }
 
-// Columns per split of the 16-row kernel: 512, or 256 when that is needed to reach ~1000 workgroups.
-static int m16_kper(int N, int K) {
+// Split-K factor of the 16-row kernel: the smallest power of two that gives about 450 workgroups (two per
+// compute unit keep enough loads in flight; measured on the 7B shapes, more splits only add partial sums
+// for the consumer kernels to read), with at least 256 columns per split.
+static int m16_splits(int N, int K) {
     const int tiles = (N + 63) / 64;
-    int kper = M16_KMAX;
-    if ((long long)tiles * ((K + kper - 1) / kper) < 1024 && K > 256) kper = 256;
-    return kper;
+    int ks = 1;
+    while (ks * tiles < 448) ks *= 2;
+    const int cap = K / 256 > 1 ? K / 256 : 1;
+    if (ks > cap) ks = cap;
+    const int kper = ((K + ks - 1) / ks + 31) / 32 * 32;
+    return (K + kper - 1) / kper;
 }
 
 // ---- GEMM, fp32 (plumbing configuration): one wavefront per output column, lanes stride K ----------
@@ -438,7 +443,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
 // Split-K factor: enough workgroups to cover the chip a few times, at least two stages per split.
 int gemm_splits(int dtype, int N, int K, int M) {
     if (dtype != BS_BF16) return 1;
-    if (M <= 16) { const int kper = m16_kper(N, K); return (K + kper - 1) / kper; }
+    if (M <= 16) return m16_splits(N, K);
     const int tiles = (N + 63) / 64;
     const int stages = (K + 255) / 256;
     int ks = (768 + tiles - 1) / tiles;
