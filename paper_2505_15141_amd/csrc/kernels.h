@@ -17,6 +17,23 @@ struct GemmArgs {
     int tiled;            // weights are in the 64x32-block layout written by launch_pack_weights
 };
 
+// Fused projection for a handful of rows (see gemm_dec_kernel): tiled bf16 weights, activations as planes.
+constexpr int DEC_MAX_ROWS = 2;
+enum { EPI_RESID = 0, EPI_QKV = 1, EPI_SWIGLU = 2 };
+struct DecArgs {
+    const uint16_t* xh; size_t x_plane;       // input planes [M][K] (hi; lo x_plane elements further)
+    const void* w[3]; int seg_rows[2];        // tiled matrices stacked along N (QKV), or gate and up (SWIGLU)
+    int M, N, K;                              // N: output columns (per matrix for SWIGLU)
+    const float* ssq_in; int ssq_tiles; float eps;     // input rows' partial sums of squares [M][ssq_tiles] (QKV, SWIGLU)
+    float* x; const float* gain_next; uint16_t* out_planes; size_t out_plane; float* ssq_out;   // RESID; out_planes also SWIGLU
+    const int32_t* pos; const float2* rope; int q_len, H, KVH, hd, cache_len;                    // QKV
+    float* q_out; uint16_t* k_cache; uint16_t* v_cache;
+};
+bool gemm_dec_fits(int M, int K);
+int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s);
+int launch_embed_dec(const int32_t* tok, const void* embed, const float* gain, int M, int d, float* x, void* planes,
+                     size_t plane, float* ssq, hipStream_t s);
+
 int gemm_splits(int dtype, int N, int K, int M);
 int profile_enable(int on);
 int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches);

@@ -43,6 +43,20 @@ __device__ __forceinline__ float wmax(float v) {
     return v;
 }
 
+// ---- KV cache layout --------------------------------------------------------------------------------
+// Per (sequence, kv head): K is [cache_len][hd] (a key's row is contiguous: MFMA A operand of K.Q^T).
+// V of a bf16 cache is stored transposed in blocks of 32 keys, [cache_len/32][hd][32], and inside a block
+// the key k = 16t + 4q + e sits at slot 8q + 4t + e: lane (d, q) of the MFMA A operand of V^T.P^T then
+// finds its 8 keys in one 16-byte load, in exactly the key order in which the score accumulators of
+// K.Q^T hold the probabilities.  cache_len is a multiple of 32.  fp32 caches keep V as [cache_len][hd].
+template <typename T> __device__ __forceinline__ size_t v_index(int key, int d, int hd);
+template <> __device__ __forceinline__ size_t v_index<float>(int key, int d, int hd) { return (size_t)key * hd + d; }
+template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, int hd) {
+    const int k = key & 31;
+    const int slot = ((k & 15) >> 2) * 8 + (k >> 4) * 4 + (k & 3);
+    return ((size_t)(key >> 5) * hd + d) * 32 + slot;
+}
+
 // ---- prep ---------------------------------------------------------------------------------------
 // One workgroup per sequence.  pos[m] = kv_len[b] + kv_base + j, or -1 for a sequence that would run
 // past max_len (then nothing of it is written anywhere).  tok[m] = token clamped into [0, V).
@@ -98,6 +112,27 @@ template <> struct Act<uint16_t> {
         reinterpret_cast<uint16_t*>(base)[plane + idx] = lo;
     }
 };
+
+// Embedding for the fused small-batch schedule: x (fp32), the planes of gain .* x (the next projection's
+// input; its epilogue applies the row's RMS scale, the projection being linear) and the row's sum of squares.
+__global__ __launch_bounds__(256) void embed_dec_kernel(const int32_t* __restrict__ tok, const uint16_t* __restrict__ embed,
+                                                        const float* __restrict__ gain, int d, float* __restrict__ x,
+                                                        uint16_t* __restrict__ planes, size_t plane, float* __restrict__ ssq) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    const uint16_t* row = embed + (size_t)tok[m] * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        const float v = to_f(row[i]);
+        x[(size_t)m * d + i] = v;
+        Act<uint16_t>::store(planes, plane, (size_t)m * d + i, v * gain[i]);
+        ss += v * v;
+    }
+    ss = wsum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq[m] = red[0] + red[1] + red[2] + red[3];
+}
 
 // ---- RMSNorm (+ pending split-K partials of the previous projection) -----------------------------
 // out row r takes input row src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out
@@ -398,6 +433,212 @@ __global__ __launch_bounds__(256) void gemm_bf16_m16_kernel(GemmArgs a, int kper
     }
 }
 
+// ---- fused projections for very few rows (draft steps) ----------------------------------------------
+// With one or two activation rows every kernel of a layer is a few microseconds of latency, so the layer
+// time is the number of kernels.  Here a workgroup owns 16 output columns over the WHOLE K range: its
+// wavefronts split K, add their accumulators through LDS, and wavefront 0 finishes the columns in place:
+//   EPI_RESID   x += y; planes of gain_next .* x and the 16-column sums of squares for the next RMSNorm
+//   EPI_QKV     RMS scale of the input rows, RoPE on q and k, q out (fp32), k and v into the cache
+//   EPI_SWIGLU  gate and up tiles of the same columns side by side: silu(r g) * (r u) as planes
+// so a layer is 4 projections + attention + merge instead of 10 kernels.  RMSNorm commutes with the
+// projection: norm(x) W^T = r * ((gain .* x) W^T), r = rsqrt(mean(x^2) + eps) per row, so the producer of x
+// writes gain .* x and partial sums of squares, and the consumer of the projection multiplies by r.
+// The activations come straight from L2 (MFMA B operand: lane = (row l%16, k-slot l/16)); that costs twice
+// the weight bytes in L1 traffic at 16 rows, which is why this path is for a handful of rows only.
+// Weights are in the tiled layout.
+
+template <int EPI, int DEPTH>
+__global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
+    __shared__ __attribute__((aligned(16))) float red[8][256];
+    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];     // [2 planes][M][K + 8]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int WS = EPI == EPI_SWIGLU ? W / 2 : W;                 // K splits per 16-column tile
+    const int grp = wave / WS, split = wave - grp * WS;
+    const int n0 = blockIdx.x * 16;
+    const int c = n0 + 4 * lq;                                    // lane's four output columns (epilogue)
+    const bool row_ok = li < a.M;
+    const uint16_t* wmat;
+    int local = n0 + li;
+    if (EPI == EPI_SWIGLU) wmat = reinterpret_cast<const uint16_t*>(a.w[grp]);
+    else {
+        int seg = 0;
+        if (a.w[1] && local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (a.w[2] && local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+        wmat = reinterpret_cast<const uint16_t*>(a.w[seg]);
+    }
+    // Everything the epilogue needs from memory is requested now, ahead of the operand streams, so that it has
+    // arrived long before wavefront 0 gets there: the rows' sums of squares, the residual and gain (RESID),
+    // position and rotation (QKV).
+    float ss_in = 0.f;
+    float4 x_old = make_float4(0.f, 0.f, 0.f, 0.f), g_next = make_float4(0.f, 0.f, 0.f, 0.f);
+    float2 rc0 = make_float2(1.f, 0.f), rc1 = make_float2(1.f, 0.f);
+    int p_row = -1;
+    if (wave == 0) {
+        const int m = min(li, a.M - 1);
+        if (EPI != EPI_RESID)
+            for (int t = lq; t < a.ssq_tiles; t += 4) ss_in += a.ssq_in[(size_t)m * a.ssq_tiles + t];
+        if (EPI == EPI_RESID) {
+            x_old = *reinterpret_cast<const float4*>(a.x + (size_t)m * a.N + c);
+            if (a.gain_next) g_next = *reinterpret_cast<const float4*>(a.gain_next + c);
+        }
+        if (EPI == EPI_QKV) {
+            p_row = a.pos[m];
+            const int hc = c % a.hd;
+            rc0 = a.rope[(size_t)m * (a.hd / 2) + hc / 2];
+            rc1 = a.rope[(size_t)m * (a.hd / 2) + hc / 2 + 1];
+        }
+    }
+    // ---- activations: both planes of all M rows, whole K, into LDS (a few KB at these row counts) ----
+    const int row_e = a.K + 8;                                    // padded row, elements
+    {
+        const int kc8 = a.K / 8, total = 2 * a.M * kc8;           // 16-byte chunks
+        for (int c0 = 0; c0 < total; c0 += 4 * (int)blockDim.x) {
+            uint4 v[4];
+            int dst[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ch = min(c0 + u * (int)blockDim.x + (int)threadIdx.x, total - 1);     // clamped: duplicates rewrite the same value
+                const int pr = ch / kc8, kc = ch - pr * kc8;      // pr = plane * M + row
+                const int plane = pr / a.M, m = pr - plane * a.M;
+                v[u] = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc * 8);
+                dst[u] = pr * row_e + kc * 8;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(&xs[dst[u]]) = v[u];
+        }
+    }
+    const int steps = a.K / 32;
+    const int s_begin = split * steps / WS, s_end = (split + 1) * steps / WS;
+    const int n = s_end - s_begin;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    const char* wb = reinterpret_cast<const char*>(wmat);
+    // byte offsets (every matrix is below 4 GiB: host check); a k step is 4096 bytes of the tiled weights
+    uint32_t woff = (uint32_t)(((size_t)(local >> 6) * 64 * a.K + ((local >> 4) & 3) * 512 + ((local & 15) + 16 * lq) * 8 +
+                                (size_t)s_begin * 2048) * 2);
+    uint4 rw[DEPTH];
+    if (n > 0) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) rw[u] = ldg16((const uint16_t*)(wb + woff + min(u, n - 1) * 4096));   // clamped to the last step
+    }
+    __syncthreads();                                              // activations are in LDS
+    if (n > 0) {
+        // MFMA B operand: lane (row l%16, k-slot l/16); rows >= M feed unused columns of D and read row M-1
+        const uint16_t* bh = xs + (size_t)min(li, a.M - 1) * row_e + lq * 8 + s_begin * 32;
+        const uint16_t* bl = bh + (size_t)a.M * row_e;
+        int j = 0;
+        // whole groups whose prefetches (steps j + DEPTH + u) are all inside the range: no clamps, no selects
+        for (; j + 2 * DEPTH <= n; j += DEPTH) {
+            woff += DEPTH * 4096;
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                const bf16x8 A = __builtin_bit_cast(bf16x8, rw[u]);
+                const bf16x8 Bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bh + (j + u) * 32));
+                const bf16x8 Bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bl + (j + u) * 32));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);                // keep the refill behind its MFMAs: same registers, no copies
+                rw[u] = ldg16((const uint16_t*)(wb + woff + u * 4096));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // last groups: prefetches clamped to the last step, steps past the end meet zero weights
+        for (; j < n; j += DEPTH) {
+            woff += DEPTH * 4096;
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                uint4 wv = rw[u];
+                if (j + u >= n) wv = make_uint4(0u, 0u, 0u, 0u);
+                const int sj = min(j + u, n - 1);
+                const bf16x8 A = __builtin_bit_cast(bf16x8, wv);
+                const bf16x8 Bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bh + sj * 32));
+                const bf16x8 Bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bl + sj * 32));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const int st = u - max(j + DEPTH + u - (n - 1), 0);      // relative to woff; negative = back inside the range
+                rw[u] = ldg16((const uint16_t*)(wb + woff + st * 4096));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    *reinterpret_cast<f32x4*>(&red[wave][lane * 4]) = acc;
+    __syncthreads();
+    if (wave != 0) return;
+    // lane holds D[column n0 + 4*lq + e][row li]
+    f32x4 t = {0.f, 0.f, 0.f, 0.f}, t2 = {0.f, 0.f, 0.f, 0.f};
+    for (int v = 0; v < WS; ++v) {
+        const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
+        t[0] += p[0]; t[1] += p[1]; t[2] += p[2]; t[3] += p[3];
+    }
+    if (EPI == EPI_SWIGLU)
+        for (int v = WS; v < 2 * WS; ++v) {
+            const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
+            t2[0] += p[0]; t2[1] += p[1]; t2[2] += p[2]; t2[3] += p[3];
+        }
+    float rscale = 1.f;
+    if (EPI != EPI_RESID) {      // r = rsqrt(mean square + eps) of the input row
+        ss_in += __shfl_xor(ss_in, 16, 64);
+        ss_in += __shfl_xor(ss_in, 32, 64);
+        rscale = 1.0f / sqrtf(ss_in / (float)a.K + a.eps);
+    }
+    if (EPI == EPI_RESID) {
+        float ss = 0.f;
+        if (row_ok) {
+            float* xp = a.x + (size_t)li * a.N + c;
+            float4 xv = x_old;
+            xv.x += t[0]; xv.y += t[1]; xv.z += t[2]; xv.w += t[3];
+            *reinterpret_cast<float4*>(xp) = xv;
+            ss = xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
+            if (a.gain_next) {
+                const float4 g = g_next;
+                const size_t idx = (size_t)li * a.N + c;
+                Act<uint16_t>::store(a.out_planes, a.out_plane, idx, xv.x * g.x);
+                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 1, xv.y * g.y);
+                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 2, xv.z * g.z);
+                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 3, xv.w * g.w);
+            }
+        }
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (row_ok && lq == 0 && a.ssq_out) a.ssq_out[(size_t)li * (a.N / 16) + blockIdx.x] = ss;
+    } else if (EPI == EPI_SWIGLU) {
+        if (row_ok) {
+            const size_t idx = (size_t)li * a.N + c;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float g = t[e] * rscale, u = t2[e] * rscale;
+                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + e, g / (1.0f + __expf(-g)) * u);
+            }
+        }
+    } else {
+        if (row_ok) {
+            const int nq = a.H * a.hd, nkv = a.KVH * a.hd;
+            const int p = p_row, b = li / a.q_len;
+            float v[4] = {t[0] * rscale, t[1] * rscale, t[2] * rscale, t[3] * rscale};
+            if (c < nq + nkv) {
+                const int hc = c % a.hd;
+                const float2 c0 = rc0, c1 = rc1;
+                const float r0 = v[0] * c0.x - v[1] * c0.y, r1 = v[0] * c0.y + v[1] * c0.x;
+                const float r2 = v[2] * c1.x - v[3] * c1.y, r3 = v[2] * c1.y + v[3] * c1.x;
+                if (c < nq) {
+                    *reinterpret_cast<float4*>(a.q_out + (size_t)li * nq + c) = make_float4(r0, r1, r2, r3);
+                } else if (p >= 0) {
+                    const int kh = (c - nq) / a.hd;
+                    uint16_t* dst = a.k_cache + (((size_t)b * a.KVH + kh) * a.cache_len + p) * a.hd + hc;
+                    *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)from_f<uint16_t>(r0) | ((uint32_t)from_f<uint16_t>(r1) << 16),
+                                                                (uint32_t)from_f<uint16_t>(r2) | ((uint32_t)from_f<uint16_t>(r3) << 16));
+                }
+            } else if (p >= 0) {
+                const int cv = c - nq - nkv;
+                const int vh = cv / a.hd, hc = cv % a.hd;
+                uint16_t* base = a.v_cache + ((size_t)b * a.KVH + vh) * (size_t)a.cache_len * a.hd;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) base[v_index<uint16_t>(p, hc + e, a.hd)] = from_f<uint16_t>(v[e]);
+            }
+        }
+    }
+}
+
 // Split-K factor of the 16-row kernel: the smallest power of two that gives about 450 workgroups (two per
 // compute unit keep enough loads in flight; measured on the 7B shapes, more splits only add partial sums
 // for the consumer kernels to read), with at least 256 columns per split.
@@ -545,20 +786,6 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         }
     }
     return BS_OK;
-}
-
-// ---- KV cache layout --------------------------------------------------------------------------------
-// Per (sequence, kv head): K is [cache_len][hd] (a key's row is contiguous: MFMA A operand of K.Q^T).
-// V of a bf16 cache is stored transposed in blocks of 32 keys, [cache_len/32][hd][32], and inside a block
-// the key k = 16t + 4q + e sits at slot 8q + 4t + e: lane (d, q) of the MFMA A operand of V^T.P^T then
-// finds its 8 keys in one 16-byte load, in exactly the key order in which the score accumulators of
-// K.Q^T hold the probabilities.  cache_len is a multiple of 32.  fp32 caches keep V as [cache_len][hd].
-template <typename T> __device__ __forceinline__ size_t v_index(int key, int d, int hd);
-template <> __device__ __forceinline__ size_t v_index<float>(int key, int d, int hd) { return (size_t)key * hd + d; }
-template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, int hd) {
-    const int k = key & 31;
-    const int slot = ((k & 15) >> 2) * 8 + (k >> 4) * 4 + (k & 3);
-    return ((size_t)(key >> 5) * hd + d) * 32 + slot;
 }
 
 // ---- RoPE + KV append -----------------------------------------------------------------------------
@@ -961,6 +1188,52 @@ int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, in
     hipLaunchKernelGGL(prep_kernel, dim3(B), dim3(128), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
                        hd / 2, rope_base, pos, tok, rope, status);
     BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+int launch_embed_dec(const int32_t* tok, const void* embed, const float* gain, int M, int d, float* x, void* planes,
+                     size_t plane, float* ssq, hipStream_t s) {
+    hipLaunchKernelGGL(embed_dec_kernel, dim3(M), dim3(256), 0, s, tok, (const uint16_t*)embed, gain, d, x, (uint16_t*)planes, plane, ssq);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
+// LDS the fused few-row projection needs for its activations; it fits next to the 8 KiB reduction buffer
+// inside the 64 KiB a workgroup may use.
+static size_t dec_lds_bytes(int M, int K) { return (size_t)2 * M * (K + 8) * 2; }
+bool gemm_dec_fits(int M, int K) { return M >= 1 && M <= DEC_MAX_ROWS && K % 32 == 0 && dec_lds_bytes(M, K) <= 56 * 1024; }
+
+int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
+    BS_REQUIRE(gemm_dec_fits(a.M, a.K), BS_ESHAPE, "gemm_dec: %d rows x %d columns of activations do not fit LDS", a.M, a.K);
+    BS_REQUIRE(a.M >= 1 && a.M <= 16 && a.K % 32 == 0 && a.N % 16 == 0 && a.K >= 32, BS_ESHAPE, "gemm_dec: M=%d N=%d K=%d", a.M, a.N, a.K);
+    BS_REQUIRE((double)a.N * a.K * 2.0 < 4294967296.0 && (double)a.M * a.K * 2.0 < 4294967296.0, BS_ESHAPE,
+               "gemm_dec: a matrix of %d x %d exceeds the 32-bit byte offsets of this kernel", a.N, a.K);
+    BS_REQUIRE(epi != EPI_QKV || (a.hd % 16 == 0 && a.seg_rows[0] % 16 == 0 && a.seg_rows[1] % 16 == 0), BS_ESHAPE, "gemm_dec: head_dim %d", a.hd);
+    const int steps = a.K / 32;
+    // wavefronts per 16-column tile: about six k steps each, 4 or 8 of them; the gate/up pair takes 4 + 4
+    int W = (epi == EPI_SWIGLU) ? 8 : (steps >= 48 ? 8 : 4);
+    const bool deep = steps / (epi == EPI_SWIGLU ? 4 : W) > 4;      // ring of 8 unless a wavefront has at most 4 steps
+    const dim3 grid(a.N / 16), block(64 * W);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (g_prof.on) {
+        BS_HIP(hipEventCreate(&e0));
+        BS_HIP(hipEventCreate(&e1));
+        BS_HIP(hipEventRecord(e0, s));
+    }
+    const size_t lds = dec_lds_bytes(a.M, a.K);
+#define BS_DEC(E) do { if (deep) hipLaunchKernelGGL((gemm_dec_kernel<E, 8>), grid, block, lds, s, a); \
+                       else hipLaunchKernelGGL((gemm_dec_kernel<E, 4>), grid, block, lds, s, a); } while (0)
+    if (epi == EPI_RESID) BS_DEC(EPI_RESID);
+    else if (epi == EPI_QKV) BS_DEC(EPI_QKV);
+    else BS_DEC(EPI_SWIGLU);
+#undef BS_DEC
+    BS_LAUNCH_CHECK();
+    if (g_prof.on) {                                       // class 50: fused few-row projections
+        BS_HIP(hipEventRecord(e1, s));
+        g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+        g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0));
+        g_prof.mt.push_back(50);
+    }
     return BS_OK;
 }
 

@@ -146,7 +146,7 @@ static int attn_splits(int B, int H, int max_len) {
 }
 
 struct FwdWs {
-    int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* q; void* att; void* act;
+    int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* q; void* att; void* act; float* ssq;
     float *part_qkv, *part_o, *part_gu, *part_d, *part_attn;
     int ks_qkv, ks_o, ks_gu, ks_d;
     size_t total;
@@ -172,6 +172,7 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.q = (float*)take(M * nq * 4);
     w.att = take(M * nq * 4);
     w.act = take(M * c.d_ff * 4);
+    w.ssq = (float*)take(M * (c.d_model / 16 + 1) * 4);
     w.part_qkv = (float*)take(M * (nq + 2 * nkv) * 4 * w.ks_qkv);
     w.part_o = (float*)take(M * c.d_model * 4 * w.ks_o);
     w.part_gu = (float*)take(M * 2 * c.d_ff * 4 * w.ks_gu);
@@ -217,8 +218,45 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
 #define BS_TRY(expr) do { rc = (expr); if (rc != BS_OK) return rc; } while (0)
     BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
                        w.rope, w.status, s));
-    BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
     const float* pend = nullptr;      // split-K partials of the last residual projection, not yet added to x
+    // A handful of rows (draft steps): fused schedule, 6 kernels per layer; needs the tiled weights.
+    const bool few_rows = dt == BS_BF16 && m->packed && gemm_dec_fits(M, d) && gemm_dec_fits(M, nq) && gemm_dec_fits(M, ff);
+    if (few_rows) {
+        const size_t pd = (size_t)M * d;
+        uint16_t* hp = reinterpret_cast<uint16_t*>(w.h);
+        BS_TRY(launch_embed_dec(w.tok, m->embed, m->layers[0].attn_norm, M, d, w.x, hp, pd, w.ssq, s));
+        int ssq_tiles = 1;
+        for (int l = 0; l < c.n_layers; ++l) {
+            const bs_layer_weights& L = m->layers[l];
+            char* kc = kv->buf + (size_t)l * kv_layer;
+            char* vc = kc + kv_layer / 2;
+            DecArgs a = {};
+            a.xh = hp; a.x_plane = pd; a.w[0] = L.wq; a.w[1] = L.wk; a.w[2] = L.wv; a.seg_rows[0] = nq; a.seg_rows[1] = nkv;
+            a.M = M; a.N = nqkv; a.K = d; a.ssq_in = w.ssq; a.ssq_tiles = ssq_tiles; a.eps = c.norm_eps;
+            a.pos = w.pos; a.rope = w.rope; a.q_len = q_len; a.H = H; a.KVH = KVH; a.hd = hd; a.cache_len = crow;
+            a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
+            BS_TRY(launch_gemm_dec(EPI_QKV, a, s));
+            BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
+                                    (size_t)M * nq, w.att, s));
+            a = DecArgs{};
+            a.xh = reinterpret_cast<const uint16_t*>(w.att); a.x_plane = (size_t)M * nq; a.w[0] = L.wo; a.M = M; a.N = d; a.K = nq;
+            a.x = w.x; a.gain_next = L.ffn_norm; a.out_planes = hp; a.out_plane = pd; a.ssq_out = w.ssq;
+            BS_TRY(launch_gemm_dec(EPI_RESID, a, s));
+            ssq_tiles = d / 16;
+            a = DecArgs{};
+            a.xh = hp; a.x_plane = pd; a.w[0] = L.w_gate; a.w[1] = L.w_up; a.M = M; a.N = ff; a.K = d;
+            a.ssq_in = w.ssq; a.ssq_tiles = ssq_tiles; a.eps = c.norm_eps;
+            a.out_planes = reinterpret_cast<uint16_t*>(w.act); a.out_plane = (size_t)M * ff;
+            BS_TRY(launch_gemm_dec(EPI_SWIGLU, a, s));
+            const bool more = l + 1 < c.n_layers;
+            a = DecArgs{};
+            a.xh = reinterpret_cast<const uint16_t*>(w.act); a.x_plane = (size_t)M * ff; a.w[0] = L.w_down; a.M = M; a.N = d; a.K = ff;
+            a.x = w.x; a.gain_next = more ? m->layers[l + 1].attn_norm : nullptr; a.out_planes = hp; a.out_plane = pd;
+            a.ssq_out = more ? w.ssq : nullptr;
+            BS_TRY(launch_gemm_dec(EPI_RESID, a, s));
+        }
+    } else {
+    BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
     for (int l = 0; l < c.n_layers; ++l) {
         const bs_layer_weights& L = m->layers[l];
         char* kc = kv->buf + (size_t)l * kv_layer;
@@ -247,6 +285,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         g.out = w.part_d; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = ff; g.ldo = d; g.KS = w.ks_d;
         BS_TRY(launch_gemm(dt, g, s));
         pend = w.part_d;
+    }
     }
     if (logit_rows > 0) {
         const int R = B * logit_rows;

@@ -38,7 +38,10 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     (synth.TINY_TARGET, 1, 32, 5, False), (synth.TINY_DRAFT, 2, 9, 3, False), (ODD_F32, 3, 17, 4, False),
     (MID, 1, 70, 9, False), (MID_GQA, 2, 130, 5, False), (WIDE, 1, 200, 9, False), (MID, 3, 1, 2, False),
     (MID, 1, 70, 9, True), (MID_GQA, 2, 130, 5, True), (WIDE, 1, 200, 9, True), (MID, 3, 1, 2, True),
-    (ODD_BF16, 1, 40, 7, False), (ODD_BF16, 2, 150, 3, True)])
+    (ODD_BF16, 1, 40, 7, False), (ODD_BF16, 2, 150, 3, True),
+    # at most four rows on packed weights: the fused few-row schedule of the draft steps
+    (MID, 1, 70, 2, True), (MID_GQA, 2, 130, 1, True), (WIDE, 1, 200, 4, True), (ODD_BF16, 2, 150, 2, True),
+    (MID, 4, 33, 1, True), (WIDE, 1, 1, 1, True)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
     W, m, kv = setup(c, B, 300, seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
