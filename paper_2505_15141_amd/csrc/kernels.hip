@@ -134,6 +134,15 @@ __global__ __launch_bounds__(256) void embed_dec_kernel(const int32_t* __restric
     if (threadIdx.x == 0) ssq[m] = red[0] + red[1] + red[2] + red[3];
 }
 
+// four consecutive activations (index a multiple of 4) as two 8-byte stores, one per plane
+__device__ __forceinline__ void store_planes4(uint16_t* base, size_t plane, size_t idx, float v0, float v1, float v2, float v3) {
+    const uint16_t h0 = from_f<uint16_t>(v0), h1 = from_f<uint16_t>(v1), h2 = from_f<uint16_t>(v2), h3 = from_f<uint16_t>(v3);
+    const uint16_t l0 = from_f<uint16_t>(v0 - to_f(h0)), l1 = from_f<uint16_t>(v1 - to_f(h1));
+    const uint16_t l2 = from_f<uint16_t>(v2 - to_f(h2)), l3 = from_f<uint16_t>(v3 - to_f(h3));
+    *reinterpret_cast<uint2*>(base + idx) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+    *reinterpret_cast<uint2*>(base + plane + idx) = make_uint2((uint32_t)l0 | ((uint32_t)l1 << 16), (uint32_t)l2 | ((uint32_t)l3 << 16));
+}
+
 // ---- RMSNorm (+ pending split-K partials of the previous projection) -----------------------------
 // out row r takes input row src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out
 // (rows_out = rows_in: identity; rows_out < rows_in: the trailing rows of every sequence).
@@ -469,46 +478,58 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
     // Everything the epilogue needs from memory is requested now, ahead of the operand streams, so that it has
     // arrived long before wavefront 0 gets there: the rows' sums of squares, the residual and gain (RESID),
     // position and rotation (QKV).
-    float ss_in = 0.f;
+    float ssr[DEC_MAX_ROWS];                                      // this lane's share of each row's sum of squares
+#pragma unroll
+    for (int m = 0; m < DEC_MAX_ROWS; ++m) ssr[m] = 0.f;
     float4 x_old = make_float4(0.f, 0.f, 0.f, 0.f), g_next = make_float4(0.f, 0.f, 0.f, 0.f);
     float2 rc0 = make_float2(1.f, 0.f), rc1 = make_float2(1.f, 0.f);
     int p_row = -1;
+    const int hd_mask = a.hd - 1;                                 // head_dim is 64 or 128
     if (wave == 0) {
         const int m = min(li, a.M - 1);
-        if (EPI != EPI_RESID)
-            for (int t = lq; t < a.ssq_tiles; t += 4) ss_in += a.ssq_in[(size_t)m * a.ssq_tiles + t];
+        if (EPI != EPI_RESID) {
+#pragma unroll
+            for (int mm = 0; mm < DEC_MAX_ROWS; ++mm) {
+                if (mm >= a.M) break;
+                for (int t = lane; t < a.ssq_tiles; t += 256) {       // independent loads, four per lane in flight
+                    float v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int tt = t + 64 * u;
+                        v[u] = a.ssq_in[(size_t)mm * a.ssq_tiles + min(tt, a.ssq_tiles - 1)];
+                        if (tt >= a.ssq_tiles) v[u] = 0.f;
+                    }
+                    ssr[mm] += (v[0] + v[1]) + (v[2] + v[3]);
+                }
+            }
+        }
         if (EPI == EPI_RESID) {
             x_old = *reinterpret_cast<const float4*>(a.x + (size_t)m * a.N + c);
             if (a.gain_next) g_next = *reinterpret_cast<const float4*>(a.gain_next + c);
         }
         if (EPI == EPI_QKV) {
             p_row = a.pos[m];
-            const int hc = c % a.hd;
+            const int hc = c & hd_mask;
             rc0 = a.rope[(size_t)m * (a.hd / 2) + hc / 2];
             rc1 = a.rope[(size_t)m * (a.hd / 2) + hc / 2 + 1];
         }
     }
     // ---- activations: both planes of all M rows, whole K, into LDS (a few KB at these row counts) ----
+    // First round of 16-byte chunks is requested BEFORE the weight prologue and stored after it, so that the
+    // wait for it (the memory counter retires in order) leaves the weight loads in flight.
     const int row_e = a.K + 8;                                    // padded row, elements
-    {
-        const int kc8 = a.K / 8, total = 2 * a.M * kc8;           // 16-byte chunks
-        for (int c0 = 0; c0 < total; c0 += 4 * (int)blockDim.x) {
-            uint4 v[4];
-            int dst[4];
+    const int kc8 = a.K / 8;                                      // 16-byte chunks per row
+    const int kc0 = threadIdx.x < (unsigned)kc8 ? (int)threadIdx.x : 0;       // lanes past the row re-read chunk 0 (not stored)
+    uint4 xv0[2 * DEC_MAX_ROWS];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int ch = min(c0 + u * (int)blockDim.x + (int)threadIdx.x, total - 1);     // clamped: duplicates rewrite the same value
-                const int pr = ch / kc8, kc = ch - pr * kc8;      // pr = plane * M + row
-                const int plane = pr / a.M, m = pr - plane * a.M;
-                v[u] = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc * 8);
-                dst[u] = pr * row_e + kc * 8;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) *reinterpret_cast<uint4*>(&xs[dst[u]]) = v[u];
-        }
+    for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr) {               // pr = plane * M + row, clamped to the last valid pair
+        const int q = min(pr, 2 * a.M - 1);
+        const int plane = q >= a.M ? 1 : 0, m = q - plane * a.M;
+        xv0[pr] = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc0 * 8);
     }
     const int steps = a.K / 32;
-    const int s_begin = split * steps / WS, s_end = (split + 1) * steps / WS;
+    const int ws_shift = __ffs(WS) - 1;                           // WS is 4 or 8
+    const int s_begin = (split * steps) >> ws_shift, s_end = ((split + 1) * steps) >> ws_shift;
     const int n = s_end - s_begin;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     const char* wb = reinterpret_cast<const char*>(wmat);
@@ -516,9 +537,19 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
     uint32_t woff = (uint32_t)(((size_t)(local >> 6) * 64 * a.K + ((local >> 4) & 3) * 512 + ((local & 15) + 16 * lq) * 8 +
                                 (size_t)s_begin * 2048) * 2);
     uint4 rw[DEPTH];
-    if (n > 0) {
+    {
+        const int nn = max(n, 1) - 1;                             // n == 0: the wavefront re-reads step 0 of its tile and ignores it
+        const uint32_t w0 = n > 0 ? woff : (uint32_t)(((size_t)(local >> 6) * 64 * a.K + ((local >> 4) & 3) * 512 + ((local & 15) + 16 * lq) * 8) * 2);
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u) rw[u] = ldg16((const uint16_t*)(wb + woff + min(u, n - 1) * 4096));   // clamped to the last step
+        for (int u = 0; u < DEPTH; ++u) rw[u] = ldg16((const uint16_t*)(wb + w0 + min(u, nn) * 4096));   // clamped to the last step
+    }
+#pragma unroll
+    for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr)
+        if (pr < 2 * a.M && threadIdx.x < (unsigned)kc8) *reinterpret_cast<uint4*>(&xs[pr * row_e + threadIdx.x * 8]) = xv0[pr];
+    for (int pr = 0; pr < 2 * a.M; ++pr) {                        // rows longer than the workgroup (8 columns per lane): the rest
+        const int plane = pr >= a.M ? 1 : 0, m = pr - plane * a.M;
+        for (int kc = threadIdx.x + blockDim.x; kc < kc8; kc += blockDim.x)
+            *reinterpret_cast<uint4*>(&xs[pr * row_e + kc * 8]) = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc * 8);
     }
     __syncthreads();                                              // activations are in LDS
     if (n > 0) {
@@ -529,13 +560,18 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
         // whole groups whose prefetches (steps j + DEPTH + u) are all inside the range: no clamps, no selects
         for (; j + 2 * DEPTH <= n; j += DEPTH) {
             woff += DEPTH * 4096;
+            uint4 Bh[DEPTH], Bl[DEPTH];                           // the group's B operands, all LDS reads in flight together
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                Bh[u] = *reinterpret_cast<const uint4*>(bh + (j + u) * 32);
+                Bl[u] = *reinterpret_cast<const uint4*>(bl + (j + u) * 32);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
                 const bf16x8 A = __builtin_bit_cast(bf16x8, rw[u]);
-                const bf16x8 Bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bh + (j + u) * 32));
-                const bf16x8 Bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bl + (j + u) * 32));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, Bh[u]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, Bl[u]), acc, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);                // keep the refill behind its MFMAs: same registers, no copies
                 rw[u] = ldg16((const uint16_t*)(wb + woff + u * 4096));
                 __builtin_amdgcn_sched_barrier(0);
@@ -544,16 +580,21 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
         // last groups: prefetches clamped to the last step, steps past the end meet zero weights
         for (; j < n; j += DEPTH) {
             woff += DEPTH * 4096;
+            uint4 Bh[DEPTH], Bl[DEPTH];
+#pragma unroll
+            for (int u = 0; u < DEPTH; ++u) {
+                const int sj = min(j + u, n - 1);
+                Bh[u] = *reinterpret_cast<const uint4*>(bh + sj * 32);
+                Bl[u] = *reinterpret_cast<const uint4*>(bl + sj * 32);
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < DEPTH; ++u) {
                 uint4 wv = rw[u];
                 if (j + u >= n) wv = make_uint4(0u, 0u, 0u, 0u);
-                const int sj = min(j + u, n - 1);
                 const bf16x8 A = __builtin_bit_cast(bf16x8, wv);
-                const bf16x8 Bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bh + sj * 32));
-                const bf16x8 Bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(bl + sj * 32));
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bh, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, Bl, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, Bh[u]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, Bl[u]), acc, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const int st = u - max(j + DEPTH + u - (n - 1), 0);      // relative to woff; negative = back inside the range
                 rw[u] = ldg16((const uint16_t*)(wb + woff + st * 4096));
@@ -576,10 +617,14 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
             t2[0] += p[0]; t2[1] += p[1]; t2[2] += p[2]; t2[3] += p[3];
         }
     float rscale = 1.f;
-    if (EPI != EPI_RESID) {      // r = rsqrt(mean square + eps) of the input row
-        ss_in += __shfl_xor(ss_in, 16, 64);
-        ss_in += __shfl_xor(ss_in, 32, 64);
-        rscale = 1.0f / sqrtf(ss_in / (float)a.K + a.eps);
+    if (EPI != EPI_RESID) {      // r = rsqrt(mean square + eps) of the lane's input row
+        float mine = 0.f;
+#pragma unroll
+        for (int mm = 0; mm < DEC_MAX_ROWS; ++mm) {
+            const float tot = wsum(ssr[mm]);
+            if (li == mm) mine = tot;
+        }
+        rscale = 1.0f / sqrtf(mine / (float)a.K + a.eps);
     }
     if (EPI == EPI_RESID) {
         float ss = 0.f;
@@ -591,11 +636,7 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
             ss = xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
             if (a.gain_next) {
                 const float4 g = g_next;
-                const size_t idx = (size_t)li * a.N + c;
-                Act<uint16_t>::store(a.out_planes, a.out_plane, idx, xv.x * g.x);
-                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 1, xv.y * g.y);
-                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 2, xv.z * g.z);
-                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + 3, xv.w * g.w);
+                store_planes4(a.out_planes, a.out_plane, (size_t)li * a.N + c, xv.x * g.x, xv.y * g.y, xv.z * g.z, xv.w * g.w);
             }
         }
         ss += __shfl_xor(ss, 16, 64);
@@ -603,12 +644,13 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
         if (row_ok && lq == 0 && a.ssq_out) a.ssq_out[(size_t)li * (a.N / 16) + blockIdx.x] = ss;
     } else if (EPI == EPI_SWIGLU) {
         if (row_ok) {
-            const size_t idx = (size_t)li * a.N + c;
+            float h[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float g = t[e] * rscale, u = t2[e] * rscale;
-                Act<uint16_t>::store(a.out_planes, a.out_plane, idx + e, g / (1.0f + __expf(-g)) * u);
+                h[e] = g / (1.0f + __expf(-g)) * u;
             }
+            store_planes4(a.out_planes, a.out_plane, (size_t)li * a.N + c, h[0], h[1], h[2], h[3]);
         }
     } else {
         if (row_ok) {
@@ -616,21 +658,21 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
             const int p = p_row, b = li / a.q_len;
             float v[4] = {t[0] * rscale, t[1] * rscale, t[2] * rscale, t[3] * rscale};
             if (c < nq + nkv) {
-                const int hc = c % a.hd;
+                const int hc = c & hd_mask;
                 const float2 c0 = rc0, c1 = rc1;
                 const float r0 = v[0] * c0.x - v[1] * c0.y, r1 = v[0] * c0.y + v[1] * c0.x;
                 const float r2 = v[2] * c1.x - v[3] * c1.y, r3 = v[2] * c1.y + v[3] * c1.x;
                 if (c < nq) {
                     *reinterpret_cast<float4*>(a.q_out + (size_t)li * nq + c) = make_float4(r0, r1, r2, r3);
                 } else if (p >= 0) {
-                    const int kh = (c - nq) / a.hd;
+                    const int kh = (c - nq) >> (__ffs(a.hd) - 1);
                     uint16_t* dst = a.k_cache + (((size_t)b * a.KVH + kh) * a.cache_len + p) * a.hd + hc;
                     *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)from_f<uint16_t>(r0) | ((uint32_t)from_f<uint16_t>(r1) << 16),
                                                                 (uint32_t)from_f<uint16_t>(r2) | ((uint32_t)from_f<uint16_t>(r3) << 16));
                 }
             } else if (p >= 0) {
                 const int cv = c - nq - nkv;
-                const int vh = cv / a.hd, hc = cv % a.hd;
+                const int vh = cv >> (__ffs(a.hd) - 1), hc = cv & hd_mask;
                 uint16_t* base = a.v_cache + ((size_t)b * a.KVH + vh) * (size_t)a.cache_len * a.hd;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) base[v_index<uint16_t>(p, hc + e, a.hd)] = from_f<uint16_t>(v[e]);
