@@ -73,6 +73,22 @@ def make_weights(c, seed, std=WEIGHT_STD):
     return W
 
 
+def make_weights_device(c, seed, device="cuda", std=WEIGHT_STD):
+    """Same recipe as make_weights (matrices N(0, std) rounded to bf16, norm gains 1) drawn by torch's generator on
+    `device`: name -> tensor (bfloat16 matrices, float32 gains).  For the full-size shapes, where drawing 5e8 normals
+    with numpy takes minutes.  bf16 models only."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    W = {}
+    for name, shape in weight_shapes(c).items():
+        if name.endswith("norm"):
+            W[name] = torch.ones(shape, dtype=torch.float32, device=device)
+        else:
+            W[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * std).to(torch.bfloat16)
+    return W
+
+
 def make_prompts(batch, length, vocab, seed):
     rng = np.random.default_rng(seed)
     return rng.integers(0, vocab, size=(batch, length), dtype=np.int64)

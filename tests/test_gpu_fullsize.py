@@ -1,0 +1,79 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times: the 7B-shaped target's layer
+(4096 wide, 32 heads x 128, FFN 11008, vocabulary 32000; one layer, so that the fp64 oracle finishes in seconds) and
+the whole 12-layer 768-wide draft, at a 1024-token prefix, packed weights, verification over gamma+1 = 9 rows and
+draft steps of 2 and 1 rows (the fused few-row schedule)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.forward import forward
+from paper_2505_15141_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+PREFIX = 1024
+
+
+def bs():
+    from paper_2505_15141_amd import binding
+    return binding
+
+
+def build(c, seed):
+    Wd = synth.make_weights_device(c, seed, "cuda")
+    W = {k: v.float().cpu().numpy() for k, v in Wd.items()}          # exact upcast of the bf16 values
+    m = bs().Model(c, Wd).pack(release_originals=True)
+    return W, m
+
+
+def test_target_layer_shape_prefill_1024_then_verify_9_rows():
+    c = dict(synth.LLAMA7B_TARGET, n_layers=1)
+    W, m = build(c, 21)
+    kv = bs().KV(m, 1, PREFIX + 64)
+    toks = synth.make_prompts(1, PREFIX + 9, c["vocab"], seed=22)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    last = bs().prefill(m, kv, dt, PREFIX, want_logits=True)
+    kvl = torch.full((1,), PREFIX, dtype=torch.int32, device="cuda")
+    logits = bs().verify_forward(m, kv, dt[:, PREFIX:PREFIX + 9].contiguous(), kvl)
+    torch.cuda.synchronize()
+    ref = forward(c, W, toks[0], storage="bf16")
+    assert np.max(np.abs(last[0].cpu().numpy() - ref[PREFIX - 1])) < 2e-2
+    err = np.max(np.abs(logits[0].cpu().numpy() - ref[PREFIX:PREFIX + 9]))
+    assert err < 2e-2, err
+
+
+def test_draft_model_prefill_1024_then_steps_of_two_and_one_rows():
+    c = synth.LLAMA7B_DRAFT
+    W, m = build(c, 23)
+    kv = bs().KV(m, 1, PREFIX + 64)
+    toks = synth.make_prompts(1, PREFIX + 3, c["vocab"], seed=24)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    bs().prefill(m, kv, dt, PREFIX, want_logits=False)
+    kvl = torch.full((1,), PREFIX, dtype=torch.int32, device="cuda")
+    two = bs().verify_forward(m, kv, dt[:, PREFIX:PREFIX + 2].contiguous(), kvl)             # first draft step of a round
+    kvl += 2
+    one = bs().verify_forward(m, kv, dt[:, PREFIX + 2:PREFIX + 3].contiguous(), kvl)         # the following steps
+    torch.cuda.synchronize()
+    ref = forward(c, W, toks[0], storage="bf16")
+    e2 = np.max(np.abs(two[0].cpu().numpy() - ref[PREFIX:PREFIX + 2]))
+    e1 = np.max(np.abs(one[0].cpu().numpy() - ref[PREFIX + 2:PREFIX + 3]))
+    assert e2 < 2e-2 and e1 < 2e-2, (e2, e1)
+
+
+def test_attention_head_configuration_at_4096_cached_tokens():
+    """32 heads x 128 against 4096 cached keys per sequence (the long-context workloads' attention shape); the FFN and
+    the vocabulary are shrunk so that the fp64 full-recompute reference takes seconds."""
+    c = synth.cfg(1, 4096, 32, 128, 256, 512)
+    W, m = build(c, 25)
+    ctx, B = 4096, 1
+    kv = bs().KV(m, B, ctx + 32)
+    toks = synth.make_prompts(B, ctx + 9, c["vocab"], seed=26)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    bs().prefill(m, kv, dt, ctx, want_logits=False)
+    kvl = torch.full((B,), ctx, dtype=torch.int32, device="cuda")
+    logits = bs().verify_forward(m, kv, dt[:, ctx:ctx + 9].contiguous(), kvl)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = forward(c, W, toks[b], storage="bf16")
+        err = np.max(np.abs(logits[b].cpu().numpy() - ref[ctx:ctx + 9]))
+        assert err < 2e-2, (b, err)
