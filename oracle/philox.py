@@ -20,6 +20,7 @@ PURPOSE_DRAFT = 0      # slot i: draw of draft token i
 PURPOSE_ACCEPT = 1     # slot i: acceptance test of draft token i
 PURPOSE_FINAL = 2      # slot 0: residual or bonus draw
 PURPOSE_BANDIT = 3     # EXP3Spec arm draw (b = 0, slot 0)
+PURPOSE_NOISE = 4      # draft-logit perturbation: fourth counter word 4 + 8*g for the vocabulary ids 4g .. 4g+3
 
 
 def philox4x32_10(counter, key):
@@ -66,3 +67,35 @@ def final_uniform(seed, b, t):
 
 def bandit_uniform(seed, t):
     return u_closed_open(word(seed, 0, t, 0, PURPOSE_BANDIT))
+
+
+def philox4x32_10_vec(c0, c1, c2, c3, key):
+    """The same ten rounds on arrays of counters (numpy uint64 holding 32-bit values) -> four arrays of words."""
+    c = [np.asarray(x, dtype=np.uint64) & np.uint64(MASK) for x in np.broadcast_arrays(c0, c1, c2, c3)]
+    k0, k1 = int(key[0]) & MASK, int(key[1]) & MASK
+    for _ in range(10):
+        p0 = np.uint64(M0) * c[0]
+        p1 = np.uint64(M1) * c[2]
+        hi0, lo0 = p0 >> np.uint64(32), p0 & np.uint64(MASK)
+        hi1, lo1 = p1 >> np.uint64(32), p1 & np.uint64(MASK)
+        c = [hi1 ^ c[1] ^ np.uint64(k0), lo1, hi0 ^ c[3] ^ np.uint64(k1), lo0]
+        k0, k1 = (k0 + W0) & MASK, (k1 + W1) & MASK
+    return c
+
+
+def noise_normals(seed, b, t, i, V):
+    """V standard normals for the perturbation of draft row i of sequence b in round t (the non-stationary
+    workload's draft-logit noise; not in the paper).  One Philox call per four vocabulary ids; words (w0, w1) and
+    (w2, w3) each give a Box-Muller pair: radius sqrt(-2 ln u1) with u1 on (0, 1], angle 2 pi u2 with u2 on [0, 1);
+    cosine first, sine second."""
+    seed = int(seed)
+    g = np.arange((V + 3) // 4, dtype=np.uint64)
+    w = philox4x32_10_vec(b, t, i, np.uint64(PURPOSE_NOISE) + np.uint64(8) * g, (seed & MASK, (seed >> 32) & MASK))
+    z = np.empty(4 * len(g), dtype=np.float64)
+    for pair in (0, 1):
+        u1 = ((w[2 * pair] >> np.uint64(8)).astype(np.float64) + 1.0) * 2.0 ** -24
+        u2 = (w[2 * pair + 1] >> np.uint64(8)).astype(np.float64) * 2.0 ** -24
+        r = np.sqrt(-2.0 * np.log(u1))
+        z[2 * pair::4] = r * np.cos(2.0 * np.pi * u2)
+        z[2 * pair + 1::4] = r * np.sin(2.0 * np.pi * u2)
+    return z[:V]

@@ -20,13 +20,18 @@ from .forward import forward
 from .sampling import spec_sample, draw_from_logits
 
 
-def draft_propose(cfg, W, tokens, gamma, seed, b, t, temperature=1.0, storage="f32"):
+def draft_propose(cfg, W, tokens, gamma, seed, b, t, temperature=1.0, storage="f32", noise_sigma=0.0):
     """gamma autoregressive draws x~_i ~ Q(. | tokens, x~_{<i}).
+    noise_sigma > 0 (the non-stationary workload, not the paper): Q is the softmax of the draft's logits plus
+    noise_sigma * N(0, 1) noise; that perturbed row is what is drawn from AND what the acceptance ratio uses, so the
+    round stays exact for the target distribution (Prop. 3.1 holds for any Q).
     Returns (draft_tokens [gamma], draft_logits [gamma, V], uniforms [gamma], probs [gamma, V])."""
     toks = list(int(x) for x in tokens)
     out_tok, out_logits, us, probs = [], [], [], []
     for i in range(gamma):
         logits = forward(cfg, W, toks, storage)[-1]
+        if noise_sigma > 0.0:
+            logits = logits + noise_sigma * philox.noise_normals(seed, b, t, i, cfg["vocab"])
         u = philox.draft_uniform(seed, b, t, i)
         k, p = draw_from_logits(logits, u, temperature)
         out_tok.append(k); out_logits.append(logits); us.append(u); probs.append(p)
@@ -36,12 +41,12 @@ def draft_propose(cfg, W, tokens, gamma, seed, b, t, temperature=1.0, storage="f
             np.array(us), np.array(probs).reshape(gamma, V))
 
 
-def spec_round(target, draft, tokens, gamma, seed, b, t, temperature=1.0, storage="f32"):
+def spec_round(target, draft, tokens, gamma, seed, b, t, temperature=1.0, storage="f32", noise_sigma=0.0):
     """One round for one sequence.  target/draft = (cfg, W).  tokens: list of ints (prefix).
     Returns dict(emitted, y, tau, draft_tokens, draft_logits, target_logits, margins, ...)."""
     n = len(tokens)
     d_tok, d_logits, d_u, d_probs = draft_propose(draft[0], draft[1], tokens, gamma, seed, b, t,
-                                                  temperature, storage)
+                                                  temperature, storage, noise_sigma)
     full = list(int(x) for x in tokens) + [int(x) for x in d_tok]
     t_logits = forward(target[0], target[1], full, storage)[n - 1:n + gamma]    # gamma+1 rows
     u_acc = np.array([philox.accept_uniform(seed, b, t, i) for i in range(gamma)])
@@ -55,8 +60,19 @@ def spec_round(target, draft, tokens, gamma, seed, b, t, temperature=1.0, storag
                 residual_fallback=r["residual_fallback"])
 
 
+def noise_sigma_of(noise, generated):
+    """noise = None, or (sigma_a, sigma_b, period): sigma_a while floor(generated / period) is even, sigma_b while it
+    is odd (period 0: always sigma_a), `generated` = tokens the sequence has produced before this round."""
+    if noise is None:
+        return 0.0
+    sigma_a, sigma_b, period = noise
+    if period <= 0:
+        return float(sigma_a)
+    return float(sigma_a if (generated // period) % 2 == 0 else sigma_b)
+
+
 def banditspec(alg, target, drafts, gammas, prompts, n_generate, seed, temperature=1.0,
-               storage="f32", bandit_seed=None, on_round=None):
+               storage="f32", bandit_seed=None, on_round=None, noise=None):
     """Alg. 3 with a token budget in place of EOS (synthetic models have none).
 
     alg:      UCBSpec / EXP3Spec instance (oracle.bandit); one bandit for the whole batch.
@@ -76,7 +92,8 @@ def banditspec(alg, target, drafts, gammas, prompts, n_generate, seed, temperatu
         for b, s in enumerate(seqs):
             if len(s) >= goal[b]:
                 continue
-            r = spec_round(target, drafts[arm], s, gammas[arm], seed, b, t, temperature, storage)
+            sigma = noise_sigma_of(noise, len(s) - len(prompts[b]))
+            r = spec_round(target, drafts[arm], s, gammas[arm], seed, b, t, temperature, storage, sigma)
             if on_round is not None:
                 on_round(t, b, arm, r)
             s.extend(r["emitted"])

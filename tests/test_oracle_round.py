@@ -91,3 +91,30 @@ def test_exp3_loop_runs_and_uses_bandit_uniforms():
     assert len(res["tokens"][0]) == 13 and alg.t == res["rounds"]
     exp = EXP3Spec(2, 4)
     assert res["arms"][0] == exp.select(philox.bandit_uniform(4, 0))
+
+
+def test_draft_logit_noise_is_part_of_q_and_keeps_the_round_exact():
+    """The perturbed row is the draft distribution: drawn from and used in the acceptance ratio.  Exactness for the
+    target distribution (Prop. 3.1 holds for any Q): the first emitted token follows p_1 whatever the noise."""
+    target, draft = models()
+    prompt = [3, 1, 4, 1, 5]
+    clean = spec_round(target, draft, prompt, 2, 77, 0, 0)
+    noisy = spec_round(target, draft, prompt, 2, 77, 0, 0, noise_sigma=1.5)
+    # row 0 does not depend on earlier draws: it is the clean row plus sigma times the addressed normals
+    assert np.allclose(noisy["draft_logits"][0], clean["draft_logits"][0] + 1.5 * philox.noise_normals(77, 0, 0, 0, 11))
+    k, _ = draw_from_logits(noisy["draft_logits"][0], noisy["draft_uniforms"][0])
+    assert k == noisy["draft_tokens"][0]
+    p1 = np.exp(clean["target_logits"][0] - clean["target_logits"][0].max()); p1 /= p1.sum()
+    counts = np.zeros(11)
+    n = 4000
+    for t in range(n):
+        counts[spec_round(target, draft, prompt, 2, 5, 0, t, noise_sigma=1.5)["emitted"][0]] += 1
+    chi2 = float(np.sum((counts - n * p1) ** 2 / (n * p1)))
+    assert chi2 < 40.0, chi2           # 10 degrees of freedom: P(chi2 > 40) < 2e-5
+
+
+def test_noise_schedule_switches_with_the_tokens_a_sequence_has_generated():
+    from oracle.spec_round import noise_sigma_of
+    assert noise_sigma_of(None, 10) == 0.0
+    assert noise_sigma_of((0.2, 1.5, 0), 1000) == 0.2
+    assert [noise_sigma_of((0.2, 1.5, 64), g) for g in (0, 63, 64, 127, 128, 200)] == [0.2, 0.2, 1.5, 1.5, 0.2, 1.5]
