@@ -207,6 +207,17 @@ typedef struct {
     void* dev_workspace;               /* bs_round_workspace_bytes(...) bytes, 256-byte aligned */
     size_t workspace_bytes;
     int32_t use_graph;                 /* 1: capture each arm's round once into a HIP graph and replay it */
+    /* Draft-logit perturbation of the non-stationary workload (not in the paper; both 0 = none): every draft row
+     * gets sigma * N(0,1) noise before it is drawn from, and the perturbed row is also the Q of the acceptance
+     * test, so the round stays exact for the target distribution (Prop. 3.1 holds for any Q).  sigma =
+     * noise_sigma[0] while floor(generated / noise_period) is even, noise_sigma[1] while it is odd
+     * (noise_period 0: always noise_sigma[0]); generated = total_len[b] - prompt_len[b] at the start of the round.
+     * Normals: Philox counter (b, t, draft position i, 4 + 8*g) gives four words for vocabulary ids 4g..4g+3;
+     * (w0, w1) and (w2, w3) are Box-Muller pairs, radius from u1 = ((w>>8)+1) 2^-24, angle 2 pi (w>>8) 2^-24,
+     * cosine first. */
+    const int32_t* dev_prompt_len;     /* [B] int32 or NULL (= 0): tokens that were given rather than generated */
+    float noise_sigma[2];
+    int32_t noise_period;
 } bs_round_cfg;
 
 typedef struct bs_round bs_round;
@@ -214,9 +225,18 @@ size_t bs_round_workspace_bytes(const bs_model_cfg* target, const bs_model_cfg* 
                                 int B, int L, int max_len);
 int bs_round_create(const bs_round_cfg* cfg, bs_round** out);
 int bs_round_destroy(bs_round* r);
-/* Sets the device round counter t (enqueues a tiny kernel) and marks every draft cache as holding
- * total_len-2 valid positions or more (true right after prefill of the same prompts). */
+/* Sets the device round counter t (enqueues a tiny kernel) and records that every draft cache holds the keys and
+ * values of at least the first total_len-2 tokens of every sequence (true right after prefill of the same prompts).
+ * From then on the library tracks how far each draft cache is valid: a draft model that was not selected for some
+ * rounds never saw the tokens emitted meanwhile, and is brought up to date (passes of 16 tokens per sequence
+ * through the same forward kernels, cache fill only) before its next proposal. */
 int bs_round_reset(bs_round* r, uint32_t t0, void* stream);
+/* Draft proposal alone (App. A, the gamma draws x~_i ~ Q(. | pt, x~_{<i})) for arm `arm` from the current device
+ * state, without verification or commit: the round counter and the token state do not advance, and a following
+ * bs_spec_round of the same arm repeats exactly these draws.  dev_draft_tokens [B, gamma] int32 and dev_draft_logits
+ * [B, gamma, V] float32 (the rows of Q that were drawn from, after the perturbation if one is configured) may each
+ * be NULL.  Not captured into a graph. */
+int bs_draft_propose(bs_round* r, int arm, int32_t* dev_draft_tokens, float* dev_draft_logits, void* stream);
 /* Enqueues draft proposal -> verification -> accept/reject -> commit for arm `arm`.
  *  dev_emitted   [B, L+1] int32 out: accepted draft tokens then the residual/bonus token
  *  dev_n_emitted [B] int32 out: y = tau + 1 (the reward of Sec. 3; 0 for sequences already at goal)

@@ -45,7 +45,8 @@ class RoundCfg(C.Structure):
                 ("draft_kvs", C.POINTER(vp)), ("n_arms", i32), ("arm_draft", C.POINTER(i32)),
                 ("arm_gamma", C.POINTER(i32)), ("B", i32), ("max_len", i32), ("dev_tokens", vp),
                 ("dev_total_len", vp), ("dev_goal_len", vp), ("temperature", f32), ("seed", u64),
-                ("dev_workspace", vp), ("workspace_bytes", sz), ("use_graph", i32)]
+                ("dev_workspace", vp), ("workspace_bytes", sz), ("use_graph", i32),
+                ("dev_prompt_len", vp), ("noise_sigma", f32 * 2), ("noise_period", i32)]
 
 
 def _sig(name, restype, *argtypes):
@@ -81,6 +82,7 @@ _sig("bs_round_create", C.c_int, C.POINTER(RoundCfg), C.POINTER(vp))
 _sig("bs_round_destroy", C.c_int, vp)
 _sig("bs_round_reset", C.c_int, vp, u32, vp)
 _sig("bs_spec_round", C.c_int, vp, C.c_int, vp, vp, vp)
+_sig("bs_draft_propose", C.c_int, vp, C.c_int, vp, vp, vp)
 _sig("bs_profile_enable", C.c_int, C.c_int)
 _sig("bs_profile_collect", C.c_int, C.c_int, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_longlong))
 _sig("bs_round_debug_views", C.c_int, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp))
@@ -278,11 +280,13 @@ class Round:
     """bs_round_* : device state of the speculative rounds of one batch."""
 
     def __init__(self, target, target_kv, drafts, draft_kvs, arm_draft, arm_gamma, tokens, total_len, goal_len,
-                 temperature=1.0, seed=0, use_graph=False):
+                 temperature=1.0, seed=0, use_graph=False, prompt_len=None, noise=None):
+        """noise: None or (sigma_a, sigma_b, period) for the draft-logit perturbation; prompt_len: int32 [B] tensor."""
         self.B, self.max_len = tokens.shape
         self.L = max(arm_gamma)
         self.V = target.c["vocab"]
-        self.keep = (target, target_kv, drafts, draft_kvs, tokens, total_len, goal_len)
+        self.keep = (target, target_kv, drafts, draft_kvs, tokens, total_len, goal_len, prompt_len)
+        sa, sb, period = noise if noise is not None else (0.0, 0.0, 0)
         dcfgs = (C.POINTER(ModelCfg) * len(drafts))(*[C.pointer(d.cfg) for d in drafts])
         nbytes = lib.bs_round_workspace_bytes(C.byref(target.cfg), dcfgs, len(drafts), self.B, self.L, self.max_len)
         self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=tokens.device)
@@ -293,7 +297,8 @@ class Round:
         self.arm_gamma = list(arm_gamma)
         cfg = RoundCfg(target.h, target_kv.h, len(drafts), self._drafts, self._kvs, len(arm_gamma), self._arm_draft,
                        self._arm_gamma, self.B, self.max_len, tokens.data_ptr(), total_len.data_ptr(),
-                       goal_len.data_ptr(), temperature, seed, self.workspace.data_ptr(), nbytes, int(use_graph))
+                       goal_len.data_ptr(), temperature, seed, self.workspace.data_ptr(), nbytes, int(use_graph),
+                       None if prompt_len is None else prompt_len.data_ptr(), (f32 * 2)(sa, sb), int(period))
         self.h = vp()
         check(lib.bs_round_create(C.byref(cfg), C.byref(self.h)))
         self.emitted = torch.zeros(self.B, self.L + 1, dtype=torch.int32, device=tokens.device)
@@ -305,6 +310,14 @@ class Round:
     def spec_round(self, arm, stream=None):
         check(lib.bs_spec_round(self.h, arm, ptr(self.emitted), ptr(self.n_emitted), stream_ptr(stream)))
         return self.emitted, self.n_emitted
+
+    def draft_propose(self, arm, stream=None):
+        """bs_draft_propose: (draft_tokens [B,gamma] int32, draft_logits [B,gamma,V] float32) without verification or commit."""
+        gamma = self.arm_gamma[arm]
+        toks = torch.empty(self.B, gamma, dtype=torch.int32, device=self.workspace.device)
+        logits = torch.empty(self.B, gamma, self.V, dtype=torch.float32, device=self.workspace.device)
+        check(lib.bs_draft_propose(self.h, arm, ptr(toks), ptr(logits), stream_ptr(stream)))
+        return toks, logits
 
     def debug_views(self, gamma):
         """(target_logits [B,gamma+1,V], draft_logits [B,gamma,V], draft_tokens [B,gamma], margins [B,gamma]) as

@@ -34,10 +34,31 @@ void set_error(const char* fmt, ...);
     } while (0)
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), host and device -------------------------------------
-enum : uint32_t { PURPOSE_DRAFT = 0, PURPOSE_ACCEPT = 1, PURPOSE_FINAL = 2, PURPOSE_BANDIT = 3 };
+enum : uint32_t { PURPOSE_DRAFT = 0, PURPOSE_ACCEPT = 1, PURPOSE_FINAL = 2, PURPOSE_BANDIT = 3, PURPOSE_NOISE = 4 };
 
 __host__ __device__ inline uint32_t mulhi32(uint32_t a, uint32_t b) {
     return (uint32_t)(((uint64_t)a * (uint64_t)b) >> 32);
+}
+
+struct Philox4 { uint32_t w[4]; };
+
+// all four output words for counter (c0, c1, c2, c3)
+__host__ __device__ inline Philox4 philox4(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = mulhi32(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = mulhi32(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    Philox4 o;
+    o.w[0] = c0; o.w[1] = c1; o.w[2] = c2; o.w[3] = c3;
+    return o;
 }
 
 __host__ __device__ inline uint32_t philox_word(uint64_t seed, uint32_t b, uint32_t t, uint32_t slot,

@@ -364,8 +364,13 @@ struct RoundWs {
     uint32_t* round; int32_t* status;
     int32_t *q_draft2, *q_draft1, *q_target, *draft_tokens, *kvlen_draft, *kvlen_target, *flags, *cand, *active;
     float *draft_logits, *target_logits, *margins; void* stats;
+    float* sigma;            // [B] draft-logit noise scale of this round
+    int32_t* dlen;           // [n_drafts][B] tokens whose keys/values each draft cache holds
+    int32_t *q_catch, *kvlen_catch;     // inputs of a catch-up pass
     char* fwd; size_t fwd_bytes; size_t total;
 };
+
+constexpr int CATCH = 16;    // tokens per sequence one catch-up pass of an idle draft model processes
 
 static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* drafts, int n_drafts, int B, int L, int max_len, char* base) {
     RoundWs w;
@@ -384,11 +389,15 @@ static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* dra
     w.active = (int32_t*)take((size_t)B * 4);
     w.margins = (float*)take((size_t)B * L * 4);
     w.stats = take(spec_scratch_bytes(B, L));
+    w.sigma = (float*)take((size_t)B * 4);
+    w.dlen = (int32_t*)take((size_t)n_drafts * B * 4);
+    w.q_catch = (int32_t*)take((size_t)B * CATCH * 4);
+    w.kvlen_catch = (int32_t*)take((size_t)B * 4);
     w.draft_logits = (float*)take((size_t)B * L * t.vocab * 4);
     w.target_logits = (float*)take((size_t)B * (L + 1) * t.vocab * 4);
     size_t f = carve_max(t, B, L + 1, max_len);
     for (int i = 0; i < n_drafts; ++i) {
-        size_t fd = carve_max(*drafts[i], B, 2, max_len);
+        size_t fd = carve_max(*drafts[i], B, n_drafts > 1 ? CATCH : 2, max_len);
         if (fd > f) f = fd;
     }
     w.fwd = take(f); w.fwd_bytes = f;
@@ -415,13 +424,62 @@ struct bs_round {
     int L;
     RoundWs ws;
     std::vector<ArmGraph> graphs;
+    std::vector<int> lag_bound;      // per draft: upper bound of the tokens emitted since its cache was last brought up to date
     int last_gamma;
 };
 
 namespace bs {
 
-__global__ void set_round_kernel(uint32_t* round, int32_t* status, int32_t* fwd_status, uint32_t t0) {
-    if (threadIdx.x == 0) { *round = t0; *status = 0; *fwd_status = 0; }
+__global__ void set_round_kernel(uint32_t* round, int32_t* status, int32_t* fwd_status, uint32_t t0,
+                                 const int32_t* __restrict__ total_len, int B, int n_drafts, int32_t* __restrict__ dlen) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) { *round = t0; *status = 0; *fwd_status = 0; }
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * n_drafts) dlen[i] = total_len[i % B];       // caller's promise: caches are filled for the current tokens
+}
+
+// Inputs of one catch-up pass of a draft model whose cache lags: CATCH tokens per sequence from the first position
+// the cache does not hold yet (never past total-2: the round's first draft step feeds the last two tokens itself).
+__global__ void catchup_prepare_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ total_len, int B,
+                                       int max_len, int32_t* __restrict__ dlen, int32_t* __restrict__ q_catch,
+                                       int32_t* __restrict__ kvlen_catch) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int total = total_len[b];
+    if (total < 2 || total > max_len) { kvlen_catch[b] = max_len; return; }       // the forward skips this sequence
+    const int need = total - 2;
+    const int have = min(dlen[b], need);
+    const int start = max(min(have, max_len - CATCH), 0);                          // the pass must fit the cache
+    for (int j = 0; j < CATCH; ++j) {
+        const int pos = start + j;
+        q_catch[b * CATCH + j] = pos < total ? tokens[(size_t)b * max_len + pos] : 0;   // past the end: rows nobody reads
+    }
+    kvlen_catch[b] = start;
+    dlen[b] = max(have, min(start + CATCH, need));
+}
+
+// Draft-logit perturbation: row[v] += sigma[b] * z(b, t, i, v) with Box-Muller normals from Philox
+// (counter (b, t, i, 4 + 8g) -> four words for v = 4g..4g+3).  grid (ceil(V/4/256), B).
+__global__ void noise_kernel(float* __restrict__ rows, size_t row_stride, int V, const float* __restrict__ sigma,
+                             uint64_t seed, const uint32_t* __restrict__ round, uint32_t slot) {
+    const int b = blockIdx.y;
+    const float sg = sigma[b];
+    if (sg == 0.f) return;
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (4 * g >= V) return;
+    const Philox4 ph = philox4(seed, (uint32_t)b, *round, slot, PURPOSE_NOISE + 8u * (uint32_t)g);
+    float z[4];
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const float u1 = u_open_closed(ph.w[2 * pr]), u2 = u_closed_open(ph.w[2 * pr + 1]);
+        const float rad = sqrtf(-2.0f * logf(u1));
+        float sn, cs;
+        sincosf(6.28318530717958647692f * u2, &sn, &cs);
+        z[2 * pr] = rad * cs; z[2 * pr + 1] = rad * sn;
+    }
+    float* row = rows + (size_t)b * row_stride;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (4 * g + e < V) row[4 * g + e] += sg * z[e];
 }
 
 // Start of a round: gather the draft's first two inputs and the target's first query token.
@@ -429,10 +487,16 @@ __global__ void round_begin_kernel(const int32_t* __restrict__ tokens, const int
                                    const int32_t* __restrict__ goal_len, int B, int max_len, int tq_stride,
                                    int32_t* __restrict__ q_draft2, int32_t* __restrict__ q_target,
                                    int32_t* __restrict__ kvlen_draft, int32_t* __restrict__ kvlen_target,
-                                   int32_t* __restrict__ active, int32_t* __restrict__ status) {
+                                   int32_t* __restrict__ active, int32_t* __restrict__ status,
+                                   const int32_t* __restrict__ prompt_len, float sigma_a, float sigma_b, int period,
+                                   float* __restrict__ sigma) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     const int total = total_len[b];
+    {
+        const int generated = max(total - (prompt_len ? prompt_len[b] : 0), 0);
+        sigma[b] = (period > 0 && ((generated / period) & 1)) ? sigma_b : sigma_a;
+    }
     const bool ok = total >= 2 && total <= max_len;
     if (!ok) atomicOr(status, 4);
     const int t1 = ok ? tokens[(size_t)b * max_len + total - 1] : 0;
@@ -450,7 +514,7 @@ __global__ void round_commit_kernel(const int32_t* __restrict__ flags, const int
                                     const int32_t* __restrict__ goal_len, int B, int gamma, int L, int max_len,
                                     int32_t* __restrict__ tokens, int32_t* __restrict__ total_len,
                                     int32_t* __restrict__ emitted, int32_t* __restrict__ n_emitted,
-                                    uint32_t* __restrict__ round) {
+                                    uint32_t* __restrict__ round, int32_t* __restrict__ dlen_used) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b == 0) *round += 1u;      // every kernel of this round has already read the counter (stream order)
     if (b >= B) return;
@@ -458,6 +522,8 @@ __global__ void round_commit_kernel(const int32_t* __restrict__ flags, const int
     int tau = 0;
     while (tau < gamma && (flags[(size_t)b * (gamma + 1) + tau] & 1)) ++tau;
     const int total = total_len[b];
+    // the draft's steps consumed x~_1 .. x~_{gamma-1}: its cache is right up to the last accepted one of those
+    dlen_used[b] = total + min(tau, gamma - 1);
     const int goal = goal_len ? min(goal_len[b], max_len) : max_len;
     int len = total;
     for (int i = 0; i <= tau; ++i) {
@@ -479,6 +545,9 @@ extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_r
     BS_REQUIRE(cfg->dev_tokens && cfg->dev_total_len && cfg->dev_workspace, BS_EINVAL, "bs_round_create: NULL device pointer");
     BS_REQUIRE(cfg->n_drafts >= 1 && cfg->n_arms >= 1 && cfg->B >= 1 && cfg->max_len >= 2, BS_ESHAPE, "bs_round_create: bad counts");
     BS_REQUIRE(cfg->temperature > 0.f, BS_EINVAL, "bs_round_create: temperature must be > 0");
+    BS_REQUIRE(cfg->noise_sigma[0] >= 0.f && cfg->noise_sigma[1] >= 0.f && cfg->noise_period >= 0, BS_EINVAL,
+               "bs_round_create: noise scale and period must be >= 0");
+    BS_REQUIRE(cfg->n_drafts == 1 || cfg->max_len >= CATCH, BS_ESHAPE, "bs_round_create: several draft models need max_len >= %d", CATCH);
     int rc = check_fwd_args(cfg->target, cfg->target_kv, "bs_round_create(target)");
     if (rc != BS_OK) return rc;
     BS_REQUIRE(cfg->target_kv->B == cfg->B && cfg->target_kv->max_len == cfg->max_len, BS_ESHAPE,
@@ -511,6 +580,7 @@ extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_r
     r->L = L;
     r->ws = carve_round(cfg->target->cfg, dcfg.data(), cfg->n_drafts, cfg->B, L, cfg->max_len, reinterpret_cast<char*>(cfg->dev_workspace));
     r->graphs.resize(cfg->n_arms);
+    r->lag_bound.assign(cfg->n_drafts, 0);
     r->last_gamma = 0;
     *out = r;
     return BS_OK;
@@ -527,23 +597,44 @@ extern "C" __attribute__((visibility("default"))) int bs_round_destroy(bs_round*
 
 extern "C" __attribute__((visibility("default"))) int bs_round_reset(bs_round* r, uint32_t t0, void* stream) {
     BS_REQUIRE(r, BS_EINVAL, "bs_round_reset: NULL handle");
-    hipLaunchKernelGGL(bs::set_round_kernel, dim3(1), dim3(64), 0, reinterpret_cast<hipStream_t>(stream), r->ws.round, r->ws.status, reinterpret_cast<int32_t*>(r->ws.fwd), t0);
+    const int n = r->cfg.B * r->cfg.n_drafts;
+    hipLaunchKernelGGL(bs::set_round_kernel, dim3((n + 127) / 128), dim3(128), 0, reinterpret_cast<hipStream_t>(stream), r->ws.round,
+                       r->ws.status, reinterpret_cast<int32_t*>(r->ws.fwd), t0, r->cfg.dev_total_len, r->cfg.B, r->cfg.n_drafts, r->ws.dlen);
     BS_LAUNCH_CHECK();
+    r->lag_bound.assign(r->cfg.n_drafts, 0);
     return BS_OK;
 }
 
-static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emitted, hipStream_t s) {
+// Brings the cache of the arm's draft model up to total_len-2 if it was idle (eager launches, outside any graph).
+static int catch_up(bs_round* r, int arm, hipStream_t s) {
+    const bs_round_cfg& c = r->cfg;
+    const int d = r->arm_draft[arm], B = c.B;
+    RoundWs& w = r->ws;
+    const int passes = (r->lag_bound[d] + CATCH - 1) / CATCH;
+    for (int p = 0; p < passes; ++p) {
+        hipLaunchKernelGGL(bs::catchup_prepare_kernel, dim3((B + 127) / 128), dim3(128), 0, s, c.dev_tokens, c.dev_total_len, B,
+                           c.max_len, w.dlen + (size_t)d * B, w.q_catch, w.kvlen_catch);
+        BS_LAUNCH_CHECK();
+        const int rc = forward(r->drafts[d], r->draft_kvs[d], w.q_catch, CATCH, w.kvlen_catch, 0, CATCH, 0, nullptr, 0, w.fwd, w.fwd_bytes, s);
+        if (rc != BS_OK) return rc;
+    }
+    r->lag_bound[d] = 0;
+    return BS_OK;
+}
+
+// round_begin + the gamma draft steps of the arm (App. A, generation of x~_1..x~_gamma)
+static int enqueue_draft(bs_round* r, int arm, hipStream_t s) {
     const bs_round_cfg& c = r->cfg;
     const int gamma = r->arm_gamma[arm], B = c.B, V = c.target->cfg.vocab;
     const bs_model* draft = r->drafts[r->arm_draft[arm]];
     const bs_kv* dkv = r->draft_kvs[r->arm_draft[arm]];
     RoundWs& w = r->ws;
+    const bool noisy = c.noise_sigma[0] > 0.f || c.noise_sigma[1] > 0.f;
     int rc;
     hipLaunchKernelGGL(bs::round_begin_kernel, dim3((B + 127) / 128), dim3(128), 0, s, c.dev_tokens, c.dev_total_len,
                        c.dev_goal_len, B, c.max_len, gamma + 1, w.q_draft2, w.q_target, w.kvlen_draft, w.kvlen_target,
-                       w.active, w.status);
+                       w.active, w.status, c.dev_prompt_len, c.noise_sigma[0], c.noise_sigma[1], c.noise_period, w.sigma);
     BS_LAUNCH_CHECK();
-    // ---- draft proposal: gamma sequential steps (App. A, generation of x~_1..x~_gamma) ----
     for (int i = 0; i < gamma; ++i) {
         float* row = w.draft_logits + (size_t)i * V;                  // [B, gamma, V], row i of every sequence
         if (i == 0)
@@ -551,6 +642,11 @@ static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emit
         else
             rc = forward(draft, dkv, w.q_draft1, 1, w.kvlen_draft, i + 1, 1, 1, row, (size_t)gamma * V, w.fwd, w.fwd_bytes, s);
         if (rc != BS_OK) return rc;
+        if (noisy) {
+            hipLaunchKernelGGL(bs::noise_kernel, dim3(((V + 3) / 4 + 255) / 256, B), dim3(256), 0, s, row, (size_t)gamma * V, V,
+                               w.sigma, c.seed, w.round, (uint32_t)i);
+            BS_LAUNCH_CHECK();
+        }
         DrawParams d;
         d.logits = row; d.row_stride = gamma * V; d.V = V; d.inv_temp = 1.0f / c.temperature; d.seed = c.seed;
         d.round_ptr = w.round; d.round = 0; d.slot = (uint32_t)i;
@@ -560,6 +656,15 @@ static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emit
         rc = launch_draw(d, B, s);
         if (rc != BS_OK) return rc;
     }
+    return BS_OK;
+}
+
+static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emitted, hipStream_t s) {
+    const bs_round_cfg& c = r->cfg;
+    const int gamma = r->arm_gamma[arm], B = c.B, V = c.target->cfg.vocab;
+    RoundWs& w = r->ws;
+    int rc = enqueue_draft(r, arm, s);
+    if (rc != BS_OK) return rc;
     // ---- verification: one target pass over gamma+1 positions ----
     rc = forward(c.target, c.target_kv, w.q_target, gamma + 1, w.kvlen_target, 0, gamma + 1, gamma + 1, w.target_logits,
                  (size_t)(gamma + 1) * V, w.fwd, w.fwd_bytes, s);
@@ -571,7 +676,7 @@ static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emit
     // ---- commit ----
     hipLaunchKernelGGL(bs::round_commit_kernel, dim3((B + 127) / 128), dim3(128), 0, s, w.flags, w.cand, w.draft_tokens,
                        w.active, c.dev_goal_len, B, gamma, r->L, c.max_len, c.dev_tokens, c.dev_total_len, emitted,
-                       n_emitted, w.round);
+                       n_emitted, w.round, w.dlen + (size_t)r->arm_draft[arm] * B);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
@@ -582,6 +687,12 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r,
     BS_REQUIRE(dev_emitted && dev_n_emitted, BS_EINVAL, "bs_spec_round: NULL output pointer");
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     r->last_gamma = r->arm_gamma[arm];
+    {
+        const int rc = catch_up(r, arm, s);
+        if (rc != BS_OK) return rc;
+        for (size_t d = 0; d < r->lag_bound.size(); ++d)          // the other drafts fall behind by what this round emits
+            if ((int)d != r->arm_draft[arm]) r->lag_bound[d] += r->arm_gamma[arm] + 1;
+    }
     if (!r->cfg.use_graph) return enqueue_round(r, arm, dev_emitted, dev_n_emitted, s);
     BS_REQUIRE(s != nullptr, BS_EINVAL, "bs_spec_round: graph mode needs a non-null stream");
     ArmGraph& g = r->graphs[arm];
@@ -602,6 +713,20 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r,
         g.emitted = dev_emitted; g.n_emitted = dev_n_emitted;
     }
     BS_HIP(hipGraphLaunch(g.exec, s));
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_draft_propose(bs_round* r, int arm, int32_t* dev_draft_tokens, float* dev_draft_logits, void* stream) {
+    BS_REQUIRE(r, BS_EINVAL, "bs_draft_propose: NULL handle");
+    BS_REQUIRE(arm >= 0 && arm < (int)r->arm_gamma.size(), BS_EINVAL, "bs_draft_propose: arm %d not in [0,%zu)", arm, r->arm_gamma.size());
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    int rc = catch_up(r, arm, s);
+    if (rc != BS_OK) return rc;
+    rc = enqueue_draft(r, arm, s);
+    if (rc != BS_OK) return rc;
+    const int gamma = r->arm_gamma[arm], B = r->cfg.B, V = r->cfg.target->cfg.vocab;
+    if (dev_draft_tokens) BS_HIP(hipMemcpyAsync(dev_draft_tokens, r->ws.draft_tokens, (size_t)B * gamma * 4, hipMemcpyDeviceToDevice, s));
+    if (dev_draft_logits) BS_HIP(hipMemcpyAsync(dev_draft_logits, r->ws.draft_logits, (size_t)B * gamma * V * 4, hipMemcpyDeviceToDevice, s));
     return BS_OK;
 }
 

@@ -6,7 +6,7 @@ import torch
 from oracle import philox
 from oracle.bandit import UCBSpec, EXP3Spec
 from oracle.sampling import draw_is_valid
-from oracle.spec_round import spec_round
+from oracle.spec_round import spec_round, noise_sigma_of
 from paper_2505_15141_amd import synth
 from helpers import MARGIN, BIN_TOL
 
@@ -21,7 +21,7 @@ def bs():
 class Harness:
     """Device state of one batch plus re-synchronisation to a given token history."""
 
-    def __init__(self, tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph=False):
+    def __init__(self, tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph=False, noise=None):
         b = bs()
         self.B, self.P = prompts.shape
         self.max_len = self.P + n_generate + max(arm_gamma) + 2
@@ -35,8 +35,9 @@ class Harness:
         self.tokens = torch.zeros(self.B, self.max_len, dtype=torch.int32, device="cuda")
         self.total = torch.zeros(self.B, dtype=torch.int32, device="cuda")
         self.goal = torch.full((self.B,), self.P + n_generate, dtype=torch.int32, device="cuda")
+        self.prompt_len = torch.full((self.B,), self.P, dtype=torch.int32, device="cuda")
         self.round = b.Round(self.target, self.tkv, self.drafts, self.dkvs, arm_draft, arm_gamma, self.tokens, self.total,
-                             self.goal, 1.0, seed, use_graph)
+                             self.goal, 1.0, seed, use_graph, prompt_len=self.prompt_len, noise=noise)
         self.sync_to([list(p) for p in prompts], 0)
 
     def sync_to(self, seqs, t):
@@ -59,11 +60,11 @@ class Harness:
 
 
 def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed, storage, logit_tol, use_graph=False,
-             max_rounds=10 ** 9, wseed=1):
+             max_rounds=10 ** 9, wseed=1, noise=None):
     Wt = synth.make_weights(tc, wseed)
     Wds = [synth.make_weights(c, wseed + 1 + i) for i, c in enumerate(dcs)]
     prompts = synth.make_prompts(B, P, tc["vocab"], seed + 17)
-    h = Harness(tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph)
+    h = Harness(tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph, noise)
     seqs = [list(int(x) for x in p) for p in prompts]
     goal = P + n_generate
     L = max(arm_gamma)
@@ -83,7 +84,8 @@ def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed
             if len(seqs[b]) >= goal:
                 assert n_emitted[b] == 0
                 continue
-            r = spec_round((tc, Wt), (dcs[arm_draft[arm_o]], Wds[arm_draft[arm_o]]), seqs[b], gamma, seed, b, t, 1.0, storage)
+            r = spec_round((tc, Wt), (dcs[arm_draft[arm_o]], Wds[arm_draft[arm_o]]), seqs[b], gamma, seed, b, t, 1.0, storage,
+                           noise_sigma_of(noise, len(seqs[b]) - P))
             ys.append(r["y"])
             # draft draws: identical, or inside the widened CDF bin of the oracle's distribution
             same_drafts = True
@@ -161,12 +163,65 @@ def test_bf16_mid_size_models_lockstep():
     assert stats["decisions"] >= 8 and stats["max_logit_err"] < 2e-2
 
 
-def test_two_draft_models_as_arms():
+class Scripted:
+    """Arm selection from a fixed list (both sides of the lock-step run use one): lets a test make a draft model idle
+    for as long as it wants."""
+
+    def __init__(self, arms):
+        self.arms, self.t = list(arms), 0
+
+    def select(self, u=None):
+        return self.arms[self.t % len(self.arms)]
+
+    def update(self, arm, y):
+        self.t += 1
+
+
+def test_draft_models_as_arms_ucbspec():
+    # arms = draft models (the multi-draft workload's bandit): an idle draft's cache lags and is caught up before use
     b = bs()
     d2 = synth.cfg(1, 128, 2, 64, 352, 4096, dtype="bf16")
-    # arms alternate strictly by round-robin/UCB; an idle draft's cache lags, so only consecutive use of one draft
-    # is in scope here: K=1 per draft, run twice with different drafts
-    for arm_draft in ([0], [1]):
-        stats, _ = lockstep(MID_T, [MID_D, d2], arm_draft, [5], UCBSpec(1, 5), b.Bandit(b.BS_UCBSPEC, 1, 5),
-                            1, 20, 20, seed=3, storage="bf16", logit_tol=2e-2)
-        assert stats["rounds"] >= 4
+    stats, seqs = lockstep(MID_T, [MID_D, d2], [0, 1], [5, 5], UCBSpec(2, 5), b.Bandit(b.BS_UCBSPEC, 2, 5),
+                           2, 20, 40, seed=3, storage="bf16", logit_tol=2e-2)
+    assert stats["rounds"] >= 7 and stats["decisions"] >= 8
+
+
+def test_idle_draft_model_catches_up_over_several_passes():
+    # draft 1 sits out long enough to lag by more than one 16-token pass, also with a third, never-used draft around
+    b = bs()
+    d2 = synth.cfg(1, 128, 2, 64, 352, 4096, dtype="bf16")
+    script = [0] * 7 + [1, 1] + [0] * 5 + [1]
+    stats, seqs = lockstep(MID_T, [MID_D, d2, d2], [0, 1, 2], [4, 3, 2], Scripted(script), Scripted(script),
+                           2, 9, 60, seed=5, storage="bf16", logit_tol=2e-2, max_rounds=len(script))
+    assert stats["rounds"] == len(script) and stats["decisions"] >= 10
+
+
+def test_draft_logit_perturbation_switches_with_generated_tokens():
+    # sigma 0.2 for the first 8 generated tokens of a sequence, 1.5 for the next 8, and so on; fp32 plumbing models.
+    # Tolerance: the Box-Muller transform is evaluated in fp32 on the device (argument of sin/cos rounded to 4e-7,
+    # radius up to 5.8, sigma 1.5), on top of the 1e-5 of the logits themselves.
+    b = bs()
+    stats, seqs = lockstep(synth.TINY_TARGET, [synth.TINY_DRAFT], [0, 0, 0], [2, 3, 4], EXP3Spec(3, 4),
+                           b.Bandit(b.BS_EXP3SPEC, 3, 4, seed=77), 2, 16, 40, seed=77, storage="f32", logit_tol=2e-5,
+                           noise=(0.2, 1.5, 8))
+    assert all(len(s) == 56 for s in seqs) and stats["decisions"] > 10
+
+
+def test_draft_propose_alone_matches_the_round_that_follows():
+    b = bs()
+    Wt, Wd = synth.make_weights(synth.TINY_TARGET, 1), synth.make_weights(synth.TINY_DRAFT, 2)
+    prompts = synth.make_prompts(2, 12, 512, 9)
+    h = Harness(synth.TINY_TARGET, [synth.TINY_DRAFT], Wt, [Wd], [0], [4], prompts, 20, 123, noise=(0.5, 0.5, 0))
+    toks, logits = h.round.draft_propose(0)
+    total_before = h.total.clone()
+    emitted, n = h.round.spec_round(0)
+    torch.cuda.synchronize()
+    _, dl, dt, _ = h.round.debug_views(4)
+    assert torch.equal(total_before + n, h.total)                 # the proposal alone committed nothing
+    assert torch.equal(toks, dt) and torch.equal(logits, dl)
+    for i in range(2):
+        r = spec_round((synth.TINY_TARGET, Wt), (synth.TINY_DRAFT, Wd), list(prompts[i]), 4, 123, i, 0, 1.0, "f32", 0.5)
+        for j in range(4):                                         # rows after a diverging draw see another prefix
+            assert np.max(np.abs(logits[i, j].cpu().numpy() - r["draft_logits"][j])) < 2e-5
+            if int(toks[i, j]) != int(r["draft_tokens"][j]):
+                break
