@@ -23,7 +23,16 @@ import numpy as np
 
 
 def softmax_t(logits, temperature=1.0):
-    """softmax(logits / temperature) along the last axis, fp64, max-subtracted."""
+    """softmax(logits / temperature) along the last axis, fp64, max-subtracted.
+    temperature == 0 is the limit T -> 0 (greedy decoding, Sec. 2): all mass on the largest logit, on the lowest
+    token id among equal largest logits.  With that limit distribution for P and Q the accept/reject rule below needs
+    no special case: a draft token is accepted iff it is the target's argmax, and the residual [P - Q]_+ is the
+    one-hot of the target's argmax."""
+    if float(temperature) == 0.0:
+        z = np.asarray(logits, dtype=np.float64)
+        out = np.zeros_like(z)
+        np.put_along_axis(out, np.argmax(z, axis=-1)[..., None], 1.0, axis=-1)      # argmax returns the first maximum
+        return out
     z = np.asarray(logits, dtype=np.float64) / float(temperature)
     z = z - z.max(axis=-1, keepdims=True)
     e = np.exp(z)

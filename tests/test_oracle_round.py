@@ -118,3 +118,24 @@ def test_noise_schedule_switches_with_the_tokens_a_sequence_has_generated():
     assert noise_sigma_of(None, 10) == 0.0
     assert noise_sigma_of((0.2, 1.5, 0), 1000) == 0.2
     assert [noise_sigma_of((0.2, 1.5, 64), g) for g in (0, 63, 64, 127, 128, 200)] == [0.2, 0.2, 1.5, 1.5, 0.2, 1.5]
+
+
+def test_greedy_speculative_decoding_equals_greedy_canonical_decoding_token_for_token():
+    """T -> 0: whatever the draft model and the speculation length, the emitted stream is the target's greedy stream."""
+    target, draft = models()
+    prompt = [2, 7, 1, 8]
+    canon = canonical_decode(target[0], target[1], prompt, 15, np.zeros(15), temperature=0.0)
+    for gamma in (1, 3, 5):
+        res = banditspec(UCBSpec(1, gamma), target, [draft], [gamma], [prompt], 15, seed=4, temperature=0.0)
+        assert res["tokens"][0] == canon
+    res0 = banditspec(UCBSpec(1, 1), target, [draft], [0], [prompt], 15, seed=4, temperature=0.0)     # gamma = 0: Alg. 1 itself
+    assert res0["tokens"][0] == canon and res0["rounds"] == 15
+
+
+def test_speculation_length_zero_is_canonical_decoding_with_the_final_uniforms():
+    target, draft = models()
+    prompt = [2, 7, 1, 8]
+    res = banditspec(UCBSpec(1, 1), target, [draft], [0], [prompt], 10, seed=6)
+    us = [philox.final_uniform(6, 0, t) for t in range(10)]
+    assert res["tokens"][0] == canonical_decode(target[0], target[1], prompt, 10, us)
+    assert all(y == [1] for y in res["ys"])

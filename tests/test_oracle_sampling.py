@@ -158,3 +158,27 @@ def test_inverse_cdf_order_zero_weights_and_widened_bin():
     assert [inverse_cdf(w, u)[0] for u in (0.0, 0.49, 0.5, 0.74, 0.75, 0.999)] == [1, 1, 3, 3, 4, 4]
     assert draw_is_valid(w, 0.5, 3, 1e-6) and draw_is_valid(w, 0.5, 1, 1e-6)      # on the edge: both fine
     assert not draw_is_valid(w, 0.6, 1, 1e-6) and not draw_is_valid(w, 0.6, 4, 1e-6)
+
+
+def test_temperature_zero_is_the_limit_distribution_with_lowest_id_on_ties():
+    from oracle.sampling import softmax_t
+    z = np.array([[0.3, 2.0, -1.0, 2.0], [5.0, 1.0, 1.0, 0.0]])
+    assert np.array_equal(softmax_t(z, 0.0), [[0, 1, 0, 0], [1, 0, 0, 0]])
+    z2 = np.array([0.3, 2.0, -1.0, 1.5])
+    assert np.allclose(softmax_t(z2, 1e-3), softmax_t(z2, 0.0), atol=1e-200)       # T -> 0 converges to it
+
+
+def test_greedy_accepts_exactly_the_targets_argmax_prefix():
+    from oracle.sampling import spec_sample
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        V, gamma = 7, 4
+        p = rng.normal(size=(gamma + 1, V)); q = rng.normal(size=(gamma, V))
+        q[:, :] += 3.0 * (rng.uniform(size=(gamma, 1)) < 0.6) * np.eye(V)[p[:gamma].argmax(axis=1)]    # often agree with the target
+        d = q.argmax(axis=1)                      # greedy draft tokens: the draws from the limit distribution of Q
+        r = spec_sample(p, q, d, rng.uniform(1e-6, 1.0, gamma), rng.uniform(), temperature=0.0)
+        am = p.argmax(axis=1)
+        tau = 0
+        while tau < gamma and d[tau] == am[tau]:
+            tau += 1
+        assert r["tau"] == tau and r["token"] == am[tau]
