@@ -68,7 +68,11 @@ uint32_t bs_philox_word(uint64_t seed, uint32_t b, uint32_t t, uint32_t slot, ui
  *  dev_margins       [B, gamma] float32 out or NULL: min(1,p/q) - u for every position (all tested)
  *  dev_workspace     bs_spec_sample_workspace_bytes(B, gamma) bytes, 16-byte aligned, contents ignored
  *                    (per-row softmax statistics)
- * 0 <= gamma <= 512, B >= 0 (B == 0 is a no-op), 1 <= V <= 2^20, temperature > 0.
+ * 0 <= gamma <= 512, B >= 0 (B == 0 is a no-op), 1 <= V <= 2^20, temperature >= 0.
+ * temperature == 0 is greedy decoding, the limit T -> 0 of Sec. 2: p_i and q_i put all mass on their largest logit
+ * (lowest token id among equal ones), so a draft token is accepted iff it is the target's argmax at its position and
+ * next_token is the target's argmax at the deciding position; no uniform is used, dev_draft_logits may be NULL (the
+ * draft tokens are taken to be the draft's argmax), margins are +1 / -1.
  * ---------------------------------------------------------------------------------------------- */
 size_t bs_spec_sample_workspace_bytes(int B, int gamma);
 int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
@@ -197,12 +201,13 @@ typedef struct {
     const bs_kv* const* draft_kvs;     /* host array [n_drafts], each bound with the same B, max_len */
     int32_t n_arms;
     const int32_t* arm_draft;          /* host array [n_arms]: index into drafts */
-    const int32_t* arm_gamma;          /* host array [n_arms]: speculation length, >= 1 */
+    const int32_t* arm_gamma;          /* host array [n_arms]: speculation length, >= 0; 0 = no draft tokens: the round is
+                                          one step of canonical decoding (Alg. 1), y = 1 */
     int32_t B, max_len;
     int32_t* dev_tokens;
     int32_t* dev_total_len;
     const int32_t* dev_goal_len;
-    float temperature;
+    float temperature;                 /* > 0, or 0 for greedy decoding (see bs_spec_sample) */
     uint64_t seed;
     void* dev_workspace;               /* bs_round_workspace_bytes(...) bytes, 256-byte aligned */
     size_t workspace_bytes;

@@ -397,7 +397,7 @@ static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* dra
     w.target_logits = (float*)take((size_t)B * (L + 1) * t.vocab * 4);
     size_t f = carve_max(t, B, L + 1, max_len);
     for (int i = 0; i < n_drafts; ++i) {
-        size_t fd = carve_max(*drafts[i], B, n_drafts > 1 ? CATCH : 2, max_len);
+        size_t fd = carve_max(*drafts[i], B, max_len >= CATCH ? CATCH : 2, max_len);      // draft steps (1-2 rows) and catch-up passes
         if (fd > f) f = fd;
     }
     w.fwd = take(f); w.fwd_bytes = f;
@@ -407,7 +407,7 @@ static RoundWs carve_round(const bs_model_cfg& t, const bs_model_cfg* const* dra
 
 extern "C" __attribute__((visibility("default"))) size_t bs_round_workspace_bytes(const bs_model_cfg* target, const bs_model_cfg* const* drafts, int n_drafts,
                                                    int B, int L, int max_len) {
-    if (!target || !drafts || n_drafts < 1 || B < 1 || L < 1 || max_len < 1) return 0;
+    if (!target || !drafts || n_drafts < 1 || B < 1 || L < 0 || max_len < 1) return 0;
     return carve_round(*target, drafts, n_drafts, B, L, max_len, nullptr).total;
 }
 
@@ -523,7 +523,7 @@ __global__ void round_commit_kernel(const int32_t* __restrict__ flags, const int
     while (tau < gamma && (flags[(size_t)b * (gamma + 1) + tau] & 1)) ++tau;
     const int total = total_len[b];
     // the draft's steps consumed x~_1 .. x~_{gamma-1}: its cache is right up to the last accepted one of those
-    dlen_used[b] = total + min(tau, gamma - 1);
+    if (dlen_used) dlen_used[b] = total + min(tau, gamma - 1);
     const int goal = goal_len ? min(goal_len[b], max_len) : max_len;
     int len = total;
     for (int i = 0; i <= tau; ++i) {
@@ -544,10 +544,15 @@ extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_r
                "bs_round_create: NULL handle array");
     BS_REQUIRE(cfg->dev_tokens && cfg->dev_total_len && cfg->dev_workspace, BS_EINVAL, "bs_round_create: NULL device pointer");
     BS_REQUIRE(cfg->n_drafts >= 1 && cfg->n_arms >= 1 && cfg->B >= 1 && cfg->max_len >= 2, BS_ESHAPE, "bs_round_create: bad counts");
-    BS_REQUIRE(cfg->temperature > 0.f, BS_EINVAL, "bs_round_create: temperature must be > 0");
+    BS_REQUIRE(cfg->temperature >= 0.f, BS_EINVAL, "bs_round_create: temperature must be >= 0");
     BS_REQUIRE(cfg->noise_sigma[0] >= 0.f && cfg->noise_sigma[1] >= 0.f && cfg->noise_period >= 0, BS_EINVAL,
                "bs_round_create: noise scale and period must be >= 0");
-    BS_REQUIRE(cfg->n_drafts == 1 || cfg->max_len >= CATCH, BS_ESHAPE, "bs_round_create: several draft models need max_len >= %d", CATCH);
+    {
+        bool idle_possible = cfg->n_drafts > 1;                   // a draft model can miss rounds: other drafts, or gamma = 0 arms
+        for (int a = 0; a < cfg->n_arms; ++a) idle_possible = idle_possible || cfg->arm_gamma[a] == 0;
+        BS_REQUIRE(!idle_possible || cfg->max_len >= CATCH, BS_ESHAPE,
+                   "bs_round_create: several draft models or gamma = 0 arms need max_len >= %d", CATCH);
+    }
     int rc = check_fwd_args(cfg->target, cfg->target_kv, "bs_round_create(target)");
     if (rc != BS_OK) return rc;
     BS_REQUIRE(cfg->target_kv->B == cfg->B && cfg->target_kv->max_len == cfg->max_len, BS_ESHAPE,
@@ -564,7 +569,7 @@ extern "C" __attribute__((visibility("default"))) int bs_round_create(const bs_r
     int L = 0;
     for (int a = 0; a < cfg->n_arms; ++a) {
         BS_REQUIRE(cfg->arm_draft[a] >= 0 && cfg->arm_draft[a] < cfg->n_drafts, BS_EINVAL, "bs_round_create: arm %d names draft %d", a, cfg->arm_draft[a]);
-        BS_REQUIRE(cfg->arm_gamma[a] >= 1 && cfg->arm_gamma[a] <= 64, BS_EINVAL, "bs_round_create: arm %d gamma %d outside [1,64]", a, cfg->arm_gamma[a]);
+        BS_REQUIRE(cfg->arm_gamma[a] >= 0 && cfg->arm_gamma[a] <= 64, BS_EINVAL, "bs_round_create: arm %d gamma %d outside [0,64]", a, cfg->arm_gamma[a]);
         if (cfg->arm_gamma[a] > L) L = cfg->arm_gamma[a];
     }
     const size_t need = carve_round(cfg->target->cfg, dcfg.data(), cfg->n_drafts, cfg->B, L, cfg->max_len, nullptr).total;
@@ -648,7 +653,9 @@ static int enqueue_draft(bs_round* r, int arm, hipStream_t s) {
             BS_LAUNCH_CHECK();
         }
         DrawParams d;
-        d.logits = row; d.row_stride = gamma * V; d.V = V; d.inv_temp = 1.0f / c.temperature; d.seed = c.seed;
+        d.logits = row; d.row_stride = gamma * V; d.V = V; d.seed = c.seed;
+        d.greedy = c.temperature == 0.f ? 1 : 0;
+        d.inv_temp = d.greedy ? 1.0f : 1.0f / c.temperature;
         d.round_ptr = w.round; d.round = 0; d.slot = (uint32_t)i;
         d.out0 = w.draft_tokens; d.stride0 = gamma; d.off0 = i;
         d.out1 = w.q_target; d.stride1 = gamma + 1; d.off1 = i + 1;
@@ -676,7 +683,7 @@ static int enqueue_round(bs_round* r, int arm, int32_t* emitted, int32_t* n_emit
     // ---- commit ----
     hipLaunchKernelGGL(bs::round_commit_kernel, dim3((B + 127) / 128), dim3(128), 0, s, w.flags, w.cand, w.draft_tokens,
                        w.active, c.dev_goal_len, B, gamma, r->L, c.max_len, c.dev_tokens, c.dev_total_len, emitted,
-                       n_emitted, w.round, w.dlen + (size_t)r->arm_draft[arm] * B);
+                       n_emitted, w.round, gamma > 0 ? w.dlen + (size_t)r->arm_draft[arm] * B : nullptr);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
@@ -688,10 +695,13 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_round(bs_round* r,
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     r->last_gamma = r->arm_gamma[arm];
     {
-        const int rc = catch_up(r, arm, s);
-        if (rc != BS_OK) return rc;
-        for (size_t d = 0; d < r->lag_bound.size(); ++d)          // the other drafts fall behind by what this round emits
-            if ((int)d != r->arm_draft[arm]) r->lag_bound[d] += r->arm_gamma[arm] + 1;
+        const bool drafts_used = r->arm_gamma[arm] > 0;
+        if (drafts_used) {
+            const int rc = catch_up(r, arm, s);
+            if (rc != BS_OK) return rc;
+        }
+        for (size_t d = 0; d < r->lag_bound.size(); ++d)          // the drafts not used fall behind by what this round emits
+            if (!drafts_used || (int)d != r->arm_draft[arm]) r->lag_bound[d] += r->arm_gamma[arm] + 1;
     }
     if (!r->cfg.use_graph) return enqueue_round(r, arm, dev_emitted, dev_n_emitted, s);
     BS_REQUIRE(s != nullptr, BS_EINVAL, "bs_spec_round: graph mode needs a non-null stream");

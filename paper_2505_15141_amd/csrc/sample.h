@@ -8,6 +8,7 @@ struct DrawParams {
     const float* logits;     // [B, row_stride] float32, first V entries of each row are used
     int row_stride, V;
     float inv_temp;
+    int greedy;              // 1: token = argmax of the row (temperature 0), no uniform used
     uint64_t seed;
     const uint32_t* round_ptr;   // device round counter (overrides `round` when non-null)
     uint32_t round, slot;

@@ -529,11 +529,84 @@ __global__ __launch_bounds__(ST) void spec_decide_kernel(DecideParams a) {
     }
 }
 
+// ---- greedy mode (temperature 0, Sec. 2: all mass on the largest logit) ---------------------------------
+// Index of the largest logit of a row, lowest token id among equal ones.  Every lane walks its groups in
+// increasing id and keeps the first strict maximum; lanes are then combined by (value desc, id asc).
+struct ArgBest { float v; int i; };
+__device__ __forceinline__ ArgBest better(ArgBest a, ArgBest b) {
+    return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+template <typename T, int NT>
+__device__ __forceinline__ int block_argmax(const T* __restrict__ row, int V, ArgBest* red /* NT / 64 entries of LDS */) {
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int ngroups = (V + GE - 1) / GE;
+    const bool vec = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
+    ArgBest best = {-INFINITY, 0x7FFFFFFF};
+    for (int g = tid; g < ngroups; g += NT) {
+        float v[GE];
+        expand(load_raw(row, g, V, vec), 1.0f, v);
+#pragma unroll
+        for (int e = 0; e < GE; ++e)
+            if (v[e] > best.v) { best.v = v[e]; best.i = g * GE + e; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        ArgBest other;
+        other.v = __shfl_xor(best.v, o, 64);
+        other.i = __shfl_xor(best.i, o, 64);
+        best = better(best, other);
+    }
+    if (lane == 0) red[wid] = best;
+    __syncthreads();
+    ArgBest tot = red[0];
+    for (int w = 1; w < NT / 64; ++w) tot = better(tot, red[w]);
+    __syncthreads();
+    return tot.i < V ? tot.i : 0;                 // a row without any finite logit: token 0
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void row_argmax_kernel(const T* __restrict__ rows, int V, int32_t* __restrict__ out) {
+    __shared__ ArgBest red[4];
+    const int k = block_argmax<T, 256>(rows + (size_t)blockIdx.x * V, V, red);
+    if (threadIdx.x == 0) out[blockIdx.x] = k;
+}
+
+// one lane per sequence: tau = leading draft tokens equal to the target's argmax; the emitted token is the
+// target's argmax at the first mismatch, or at the bonus position
+__global__ void greedy_decide_kernel(const int32_t* __restrict__ amax, const int32_t* __restrict__ draft_tokens, int B, int gamma,
+                                     int32_t* __restrict__ flags, int32_t* __restrict__ cand, int32_t* __restrict__ accept_len,
+                                     int32_t* __restrict__ next_token, float* __restrict__ margins) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int tau = gamma;
+    for (int i = gamma - 1; i >= 0; --i) {
+        const int acc = draft_tokens[(size_t)b * gamma + i] == amax[(size_t)b * (gamma + 1) + i];
+        if (!acc) tau = i;
+        if (flags) flags[(size_t)b * (gamma + 1) + i] = acc;
+        if (margins) margins[(size_t)b * gamma + i] = acc ? 1.f : -1.f;
+    }
+    const int token = amax[(size_t)b * (gamma + 1) + tau];
+    if (flags) flags[(size_t)b * (gamma + 1) + tau] = 0;
+    if (cand) cand[(size_t)b * (gamma + 1) + tau] = token;
+    if (accept_len) accept_len[b] = tau;
+    if (next_token) next_token[b] = token;
+}
+
 // Draft-step draw: x~ ~ softmax(logits[b] / T) with the Philox uniform (b, t, slot, DRAFT).
 __global__ __launch_bounds__(ST) void draw_kernel(DrawParams a) {
     __shared__ RowShared sh;
     const int b = blockIdx.x;
     const float* p = a.logits + (size_t)b * a.row_stride;
+    if (a.greedy) {                                  // temperature 0: the draft's argmax
+        __shared__ ArgBest red[SW];
+        const int k = block_argmax<float, ST>(p, a.V, red);
+        if (threadIdx.x == 0) {
+            if (a.out0) a.out0[(size_t)b * a.stride0 + a.off0] = k;
+            if (a.out1) a.out1[(size_t)b * a.stride1 + a.off1] = k;
+            if (a.out2) a.out2[(size_t)b * a.stride2 + a.off2] = k;
+        }
+        return;
+    }
     const uint32_t t = a.round_ptr ? *a.round_ptr : a.round;
     const float u = u_closed_open(philox_word(a.seed, (uint32_t)b, t, a.slot, PURPOSE_DRAFT));
     RowResult r;
@@ -565,6 +638,16 @@ int launch_spec_sample(const void* p_logits, const void* q_logits, const int32_t
                        int32_t* next_token, float* margins, hipStream_t stream) {
     if (B <= 0) return BS_OK;
     const int n_p = B * (gamma + 1), n_rows = n_p + B * gamma;
+    if (temperature == 0.f) {                        // greedy: only the target rows' argmax is needed
+        int32_t* amax = reinterpret_cast<int32_t*>(stats_scratch);
+        if (dtype == BS_BF16) hipLaunchKernelGGL((row_argmax_kernel<uint16_t>), dim3(n_p), dim3(256), 0, stream, (const uint16_t*)p_logits, V, amax);
+        else hipLaunchKernelGGL((row_argmax_kernel<float>), dim3(n_p), dim3(256), 0, stream, (const float*)p_logits, V, amax);
+        BS_LAUNCH_CHECK();
+        hipLaunchKernelGGL(greedy_decide_kernel, dim3((B + 127) / 128), dim3(128), 0, stream, amax, draft_tokens, B, gamma, flags, cand,
+                           accept_len, next_token, margins);
+        BS_LAUNCH_CHECK();
+        return BS_OK;
+    }
     float2* stats = reinterpret_cast<float2*>(stats_scratch);
     const float inv_temp = 1.0f / temperature;
     if (dtype == BS_BF16)
@@ -610,11 +693,11 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void*
     BS_REQUIRE(gamma <= 512, BS_ESHAPE, "bs_spec_sample: gamma=%d > 512", gamma);
     BS_REQUIRE((long long)B * (gamma + 1) < (1LL << 31), BS_ESHAPE, "bs_spec_sample: B*(gamma+1) overflows");
     BS_REQUIRE(dtype == BS_F32 || dtype == BS_BF16, BS_EDTYPE, "bs_spec_sample: dtype %d", dtype);
-    BS_REQUIRE(temperature > 0.f && isfinite(temperature), BS_EINVAL, "bs_spec_sample: temperature %g", (double)temperature);
+    BS_REQUIRE(temperature >= 0.f && isfinite(temperature), BS_EINVAL, "bs_spec_sample: temperature %g", (double)temperature);
     if (B == 0) return BS_OK;
     BS_REQUIRE(dev_target_logits && dev_accept_len && dev_next_token && dev_workspace, BS_EINVAL,
                "bs_spec_sample: NULL pointer");
-    BS_REQUIRE(gamma == 0 || (dev_draft_logits && dev_draft_tokens), BS_EINVAL, "bs_spec_sample: NULL draft input");
+    BS_REQUIRE(gamma == 0 || (dev_draft_tokens && (dev_draft_logits || temperature == 0.f)), BS_EINVAL, "bs_spec_sample: NULL draft input");
     BS_REQUIRE(workspace_bytes >= bs_spec_sample_workspace_bytes(B, gamma), BS_EWORKSPACE,
                "bs_spec_sample: workspace %zu < %zu bytes", workspace_bytes, bs_spec_sample_workspace_bytes(B, gamma));
     BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 15) == 0, BS_EWORKSPACE, "bs_spec_sample: workspace misaligned");

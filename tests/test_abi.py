@@ -84,7 +84,8 @@ def test_host_side_argument_checks_launch_nothing():
     assert bs.lib.bs_spec_sample(None, None, None, -1, 2, 10, 0, 1.0, None, 0, 0, None, None, None, None, 0, None) == -1
     assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 0, 0, 1.0, None, 0, 0, None, None, None, None, 0, None) == -2
     assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 10, 5, 1.0, None, 0, 0, None, None, None, None, 0, None) == -3
-    assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 10, 0, 0.0, None, 0, 0, None, None, None, None, 0, None) == -1
+    assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 10, 0, -1.0, None, 0, 0, None, None, None, None, 0, None) == -1
+    assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 10, 0, 0.0, None, 0, 0, None, None, None, None, 0, None) == -1   # greedy: NULL pointers
     assert bs.lib.bs_spec_sample(None, None, None, 1, 2, 10, 0, 1.0, None, 0, 0, None, None, None, None, 0, None) == -1
     assert bs.lib.bs_spec_sample(None, None, None, 0, 2, 10, 0, 1.0, None, 0, 0, None, None, None, None, 0, None) == 0
     assert bs.spec_sample_workspace_bytes(64, 8) >= 2 * 64 * 9 * 4

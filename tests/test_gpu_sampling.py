@@ -147,3 +147,24 @@ def test_output_law_on_device_matches_target_distribution():
     assert chi2 < 45.0                                             # chi^2_11 at ~1e-5
     alpha = float(np.minimum(pp, pq).sum())
     assert abs((acc + 1).mean() - (1 - alpha ** (gamma + 1)) / (1 - alpha)) < 0.05
+
+
+@pytest.mark.parametrize("B,gamma,V,dtype", [(64, 8, 32000, "bf16"), (5, 3, 1001, "f32"), (3, 0, 77, "f32"), (2, 5, 128256, "bf16")])
+def test_greedy_mode_is_bit_exact(B, gamma, V, dtype):
+    """Temperature 0: integer decisions only (argmax with the lowest id on ties), no tolerance anywhere.  bf16 logits
+    have many exactly equal values, so ties at the maximum do occur in these inputs."""
+    tl, dl = synth.make_sampling_logits(B, gamma, V, seed=31, dtype=dtype)
+    tl, dl = np.round(tl * 4) / 4, np.round(dl * 4) / 4          # coarse grid: ties at the maximum in most rows
+    rng = np.random.default_rng(32)
+    for b in range(B):                                           # let the draft agree with the target at 70% of the positions
+        for i in range(gamma):
+            if rng.uniform() < 0.7:
+                dl[b, i, tl[b, i].argmax()] = dl[b, i].max() + 1.0
+    dt = dl.argmax(axis=-1).astype(np.int32).reshape(B, gamma)   # greedy draft tokens (numpy argmax = first maximum)
+    u = np.full((B, gamma + 1), 0.5)
+    acc, tok, _ = spec_sample_batch(tl, dl, dt, u, temperature=0.0)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    a, t, _ = bs().spec_sample(torch.from_numpy(tl).to(td).cuda(), None, torch.from_numpy(dt).cuda(), temperature=0.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(a.cpu().numpy(), acc) and np.array_equal(t.cpu().numpy(), tok)
+    assert len(set(acc.tolist())) > 1 or gamma == 0             # the case mixes accepted lengths
