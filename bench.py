@@ -152,6 +152,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--profile-rounds", type=int, default=8)
+    ap.add_argument("--reward", choices=["accepted", "throughput"], default="accepted",
+                    help="accepted: reward = accepted length y (the headline configuration); throughput: arms gamma in "
+                         "{0,2,4,6,8} with the measured tokens/s of the round as the reward (bs_throughput_reward)")
+    ap.add_argument("--canonical-rounds", type=int, default=32, help="rounds of gamma = 0 (canonical decoding) timed as the baseline")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for `rocprofv3 --pmc` runs: only the eager, event-timed rounds are executed, so the 16-row GEMM "
                          "dispatches of the counter file are exactly the launches whose algorithmic bytes are printed")
@@ -169,9 +173,12 @@ def main():
 
     torch.cuda.set_device(0)
     tc, dc = synth.LLAMA7B_TARGET, synth.LLAMA7B_DRAFT
-    gammas = [2, 4, 6, 8]
+    by_throughput = args.reward == "throughput"
+    gammas = [0, 2, 4, 6, 8] if by_throughput else [2, 4, 6, 8]     # the bandit's arms
+    round_gammas = gammas if by_throughput else gammas + [0]         # the device also knows the canonical step (gamma = 0)
+    canon_arm = round_gammas.index(0)
     L, B, prefix = max(gammas), 1, 1024
-    total_rounds = args.warmup + args.steps + args.profile_rounds + 4
+    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12
     max_len = prefix + (L + 1) * total_rounds + L + 2
     seed = 2025
 
@@ -190,19 +197,27 @@ def main():
         bs.prefill(draft, dkv, tokens, prefix - 1)
         stream.synchronize()
         prefill_s = time.perf_counter() - t0
-        rnd = bs.Round(target, tkv, [draft], [dkv], [0] * len(gammas), gammas, tokens, total, goal, 1.0, seed,
+        rnd = bs.Round(target, tkv, [draft], [dkv], [0] * len(round_gammas), round_gammas, tokens, total, goal, 1.0, seed,
                        use_graph=not args.no_graph)
         rnd.reset(0)
         bandit = bs.Bandit(bs.BS_UCBSPEC, len(gammas), L, 0.5)
         host_y = torch.zeros(B, dtype=torch.int32).pin_memory()
 
-        def one_round():
-            arm = bandit.select()
+        def timed_round(arm):
+            t_start = time.perf_counter()
             _, n_emitted = rnd.spec_round(arm)
             host_y.copy_(n_emitted, non_blocking=True)
             stream.synchronize()                      # the next arm choice depends on y (Alg. 3)
-            y = float(host_y.float().mean())
-            bandit.update(arm, y)
+            return float(host_y.float().mean()), time.perf_counter() - t_start
+
+        canon_s = None
+        if by_throughput and not args.pmc_mode:       # duration of one target pass: the reference of the throughput reward
+            canon_s = float(np.median([timed_round(canon_arm)[1] for _ in range(5)][1:]))
+
+        def one_round():
+            arm = bandit.select()
+            y, seconds = timed_round(arm)
+            bandit.update(arm, bs.throughput_reward(y, seconds, canon_s, L) if by_throughput else y)
             return arm, y
 
         for _ in range(args.warmup):
@@ -217,10 +232,22 @@ def main():
         elapsed = time.perf_counter() - t0
         gen_tokens = float(np.sum(ys)) * B
 
+        # ---- canonical decoding (Alg. 1) on the same kernels: gamma = 0 rounds, one token per target pass ----
+        canonical = None
+        if args.canonical_rounds > 0 and not args.pmc_mode:
+            for _ in range(2):
+                timed_round(canon_arm)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.canonical_rounds):
+                timed_round(canon_arm)
+            torch.cuda.synchronize()
+            canonical = args.canonical_rounds * B / (time.perf_counter() - t0)
+
         # ---- verify-step latency (eager, HIP events on this stream), per gamma ----
         verify_ms = {}
         kvl = (total - 1).to(torch.int32)       # current cache length; rows written here are overwritten by later rounds
-        for g in ([] if args.pmc_mode else gammas):
+        for g in ([] if args.pmc_mode else [2, 4, 6, 8]):
             q = tokens[:, prefix - 1:prefix + g].contiguous()
             ws = torch.empty(target.forward_workspace_bytes(B, g + 1, max_len), dtype=torch.uint8, device="cuda")
             lg = torch.empty(B, g + 1, tc["vocab"], dtype=torch.float32, device="cuda")
@@ -235,13 +262,13 @@ def main():
             verify_ms[str(g)] = round(float(np.median(ts[1:])), 4)
 
         # ---- roofline of the dominant kernel: eager rounds with HIP events around every GEMM launch ----
-        rnd_eager = bs.Round(target, tkv, [draft], [dkv], [0] * len(gammas), gammas, tokens, total, goal, 1.0, seed,
-                             use_graph=False)
+        eager_gammas = [2, 4, 6, 8]
+        rnd_eager = bs.Round(target, tkv, [draft], [dkv], [0] * 4, eager_gammas, tokens, total, goal, 1.0, seed, use_graph=False)
         rnd_eager.reset(total_rounds)
         stream.synchronize()
         bs.profile_enable(True)
         for i in range(args.profile_rounds):
-            rnd_eager.spec_round(i % len(gammas))
+            rnd_eager.spec_round(i % 4)
             stream.synchronize()
         ms1, by1, n1 = bs.profile_collect(1)
         bs.profile_enable(False)
@@ -290,12 +317,16 @@ def main():
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / max(args.steps, 1) * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "Llama-7B-shaped verification (32x4096, 32 heads x128, FFN 11008, vocab 32000) with a 12-layer "
-                                  "d=768 draft, batch 1, prefix 1024, UCBSpec over gamma in {2,4,6,8}, random-init bf16 weights",
-                      "batch": B, "prefix": prefix, "arms_gamma": gammas, "bandit": "UCBSpec", "graph": not args.no_graph},
+                                  "d=768 draft, batch 1, prefix 1024, UCBSpec over gamma in {%s}, random-init bf16 weights"
+                                  % ",".join(str(g) for g in gammas),
+                      "batch": B, "prefix": prefix, "arms_gamma": gammas, "bandit": "UCBSpec", "reward": args.reward,
+                      "graph": not args.no_graph},
            "mean_accepted_tokens": round(mean_y, 4), "generated_tokens": int(gen_tokens),
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
+           "canonical_decoding_tokens_per_s": round(canonical, 2) if canonical else None,
+           "speedup_vs_canonical": round(gen_tokens / elapsed / canonical, 3) if canonical and args.steps else None,
            "prefill_s": round(prefill_s, 3), "stages": stages, "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(tc, dc, prefix, 4, mean_y)

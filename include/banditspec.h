@@ -99,6 +99,14 @@ int bs_bandit_update(bs_bandit* b, int arm, double y); /* arm must be the last s
 int bs_bandit_probs(bs_bandit* b, double* host_out_K);
 /* pulls n_i, and per arm sum of y (UCBSpec) or cumulative estimated loss (EXP3Spec); rounds so far */
 int bs_bandit_stats(bs_bandit* b, double* host_n_K, double* host_sum_K, int64_t* rounds_out);
+/* Throughput as the reward (Sec. 6, second experiment: arms gamma in {0..L} incl. canonical decoding, "the current
+ * throughput as the reward"; the paper prints no formula, this normalisation is this library's and has no parity pin):
+ *   y = 1 + L * min(1, (tokens / seconds) / ((L + 1) / canonical_seconds))
+ * tokens = mean tokens the round emitted per sequence, seconds = its duration, canonical_seconds = duration of a
+ * gamma = 0 round (one target pass).  The reference rate (L+1 tokens per target pass) bounds any arm, so y lies in
+ * [1, L+1], the range bs_bandit_update and the confidence radius of Alg. 4 expect.
+ * Errors: BS_EINVAL (NULL, non-positive times, negative tokens, L < 1). */
+int bs_throughput_reward(double tokens, double seconds, double canonical_seconds, int L, double* y_out);
 
 /* ------------------------------------------------------------------------------------------------
  * Models (Sec. 2: a model is the conditional distribution softmax(logits/T); the network itself is

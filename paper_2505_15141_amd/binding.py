@@ -67,6 +67,7 @@ _sig("bs_bandit_select", C.c_int, vp, C.POINTER(C.c_int))
 _sig("bs_bandit_update", C.c_int, vp, C.c_int, f64)
 _sig("bs_bandit_probs", C.c_int, vp, C.POINTER(f64))
 _sig("bs_bandit_stats", C.c_int, vp, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_int64))
+_sig("bs_throughput_reward", C.c_int, f64, f64, f64, C.c_int, C.POINTER(f64))
 _sig("bs_model_create", C.c_int, C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(vp))
 _sig("bs_model_destroy", C.c_int, vp)
 _sig("bs_model_packed_bytes", sz, C.POINTER(ModelCfg))
@@ -141,6 +142,12 @@ def spec_sample(target_logits, draft_logits, draft_tokens, temperature=1.0, unif
 
 
 # ------------------------------------------------------------------------------------------ bandit
+def throughput_reward(tokens, seconds, canonical_seconds, L):
+    y = f64()
+    check(lib.bs_throughput_reward(tokens, seconds, canonical_seconds, L, C.byref(y)))
+    return y.value
+
+
 class Bandit:
     def __init__(self, kind, K, L, delta=0.5, seed=0):
         self.K = K

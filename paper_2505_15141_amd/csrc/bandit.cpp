@@ -124,3 +124,13 @@ extern "C" __attribute__((visibility("default"))) int bs_bandit_stats(bs_bandit*
     if (rounds) *rounds = b->t;
     return BS_OK;
 }
+
+extern "C" __attribute__((visibility("default"))) int bs_throughput_reward(double tokens, double seconds, double canonical_seconds, int L, double* y_out) {
+    BS_REQUIRE(y_out, BS_EINVAL, "bs_throughput_reward: NULL output");
+    BS_REQUIRE(L >= 1 && tokens >= 0.0 && seconds > 0.0 && canonical_seconds > 0.0, BS_EINVAL,
+               "bs_throughput_reward: tokens=%g seconds=%g canonical_seconds=%g L=%d", tokens, seconds, canonical_seconds, L);
+    const double rate = tokens / seconds, ref = (double)(L + 1) / canonical_seconds;
+    const double frac = rate / ref < 1.0 ? rate / ref : 1.0;
+    *y_out = 1.0 + (double)L * frac;
+    return BS_OK;
+}
