@@ -77,3 +77,51 @@ def test_attention_head_configuration_at_4096_cached_tokens():
         ref = forward(c, W, toks[b], storage="bf16")
         err = np.max(np.abs(logits[b].cpu().numpy() - ref[ctx:ctx + 9]))
         assert err < 2e-2, (b, err)
+
+
+def test_llama3_8b_layer_shapes_one_round_gqa_and_128k_vocabulary():
+    """The multi-draft workload's shapes at full width: grouped-query attention 32 / 8 heads x 128, FFN 14336, vocabulary
+    128256 (LM head 1 GB, sampling rows of 128256 logits that do not fit the register-resident path), draft d = 1024.
+    One layer each and one round at gamma = 5, checked against the oracle like the lock-step runs."""
+    from oracle.sampling import draw_is_valid
+    from oracle.spec_round import spec_round
+    from helpers import MARGIN, BIN_TOL
+    tc = dict(synth.LLAMA3_8B_TARGET, n_layers=1)
+    dc = synth.LLAMA3_DRAFTS[0]
+    Wt, mt = build(tc, 31)
+    Wd, md = build(dc, 32)
+    B, P, gamma, seed = 2, 40, 5, 99
+    max_len = P + gamma + 8
+    b = bs()
+    tkv, dkv = b.KV(mt, B, max_len), b.KV(md, B, max_len)
+    prompts = synth.make_prompts(B, P, tc["vocab"], seed=33)
+    tokens = torch.zeros(B, max_len, dtype=torch.int32, device="cuda")
+    tokens[:, :P] = torch.from_numpy(prompts.astype(np.int32)).cuda()
+    total = torch.full((B,), P, dtype=torch.int32, device="cuda")
+    goal = torch.full((B,), max_len, dtype=torch.int32, device="cuda")
+    b.prefill(mt, tkv, tokens, P)
+    b.prefill(md, dkv, tokens, P)
+    rnd = b.Round(mt, tkv, [md], [dkv], [0], [gamma], tokens, total, goal, 1.0, seed)
+    rnd.reset(0)
+    emitted, n_emitted = rnd.spec_round(0)
+    torch.cuda.synchronize()
+    tl, dl, dt, _ = (x.cpu().numpy() for x in rnd.debug_views(gamma))
+    emitted, n_emitted = emitted.cpu().numpy(), n_emitted.cpu().numpy()
+    for i in range(B):
+        r = spec_round((tc, Wt), (dc, Wd), list(prompts[i]), gamma, seed, i, 0, 1.0, "bf16")
+        same = True
+        for j in range(gamma):
+            assert np.max(np.abs(dl[i, j] - r["draft_logits"][j])) < 2e-2
+            if int(dt[i, j]) != int(r["draft_tokens"][j]):
+                assert draw_is_valid(r["draft_probs"][j], r["draft_uniforms"][j], int(dt[i, j]), BIN_TOL)
+                same = False
+                break
+        if not same:
+            continue                                         # a draw on a bin edge: later rows see another prefix
+        assert np.max(np.abs(tl[i] - r["target_logits"])) < 2e-2
+        tested = r["margins"][~np.isnan(r["margins"])]
+        if tested.size and np.min(np.abs(tested)) < MARGIN:
+            continue
+        assert int(n_emitted[i]) == r["y"] and list(emitted[i, :r["tau"]]) == r["emitted"][:r["tau"]]
+        if int(emitted[i, r["tau"]]) != r["token"]:
+            assert draw_is_valid(r["final_weights"], r["u_final"], int(emitted[i, r["tau"]]), BIN_TOL)
