@@ -93,31 +93,32 @@ def stage_probes(bs, synth, torch, np, stream):
     of one 7B-shaped layer at batch 16 with 4096 cached tokens per sequence."""
     out = {}
     with torch.cuda.stream(stream):
-        # ---- accept/reject + residual sampling ----
-        B, gamma, V, copies = 64, 8, 32000, 5                     # 5 x 70 MB of logits: more than the 256 MB last-level cache
+        # ---- accept/reject + residual sampling: the stand-alone workload (B = 64) and the same rows at B = 1024 ----
+        gamma, V = 8, 32000
         g = torch.Generator(device="cuda"); g.manual_seed(7)
-        T = [(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 2).to(torch.bfloat16) for _ in range(copies)]
-        Q = [(t[:, :gamma].float() + 0.5 * torch.randn(B, gamma, V, generator=g, device="cuda")).to(torch.bfloat16) for t in T]
-        toks = [torch.multinomial(torch.softmax(q.float().view(-1, V), -1), 1).view(B, gamma).to(torch.int32) for q in Q]
-        u = torch.rand(B, gamma + 1, generator=g, device="cuda").clamp_(1e-6, 1 - 1e-6)
-        ws = torch.empty(bs.spec_sample_workspace_bytes(B, gamma), dtype=torch.uint8, device="cuda")
-        res = (torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
-        for i in range(3):
-            bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps, alg = 20, 0.0
-        e0.record(stream)
-        for i in range(reps):
-            bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
-        e1.record(stream); e1.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        acc = res[0].cpu().numpy()
-        alg = float(np.sum((acc + 1) + np.minimum(acc + 1, gamma))) * V * 2      # rows up to the deciding one
-        touched = B * (2 * gamma + 1) * V * 2
-        out["sampling"] = {"workload": "B=64 gamma=8 V=32000 bf16 logits", "us": round(us, 2),
-                           "touched_GBps": round(touched / us / 1e3, 1), "algorithmic_GBps": round(alg / us / 1e3, 1),
-                           "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4)}
-        del T, Q, toks
+        for B, copies, key in ((64, 5, "sampling"), (1024, 2, "sampling_b1024")):    # 5 x 70 MB: more than the 256 MB last-level cache
+            T = [(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 2).to(torch.bfloat16) for _ in range(copies)]
+            Q = [(t[:, :gamma].float() + 0.5 * torch.randn(B, gamma, V, generator=g, device="cuda")).to(torch.bfloat16) for t in T]
+            toks = [torch.multinomial(torch.softmax(q.float().view(-1, V), -1), 1).view(B, gamma).to(torch.int32) for q in Q]
+            u = torch.rand(B, gamma + 1, generator=g, device="cuda").clamp_(1e-6, 1 - 1e-6)
+            ws = torch.empty(bs.spec_sample_workspace_bytes(B, gamma), dtype=torch.uint8, device="cuda")
+            res = (torch.empty(B, dtype=torch.int32, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda"))
+            for i in range(3):
+                bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 20
+            e0.record(stream)
+            for i in range(reps):
+                bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
+            e1.record(stream); e1.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            acc = res[0].cpu().numpy()
+            alg = float(np.sum((acc + 1) + np.minimum(acc + 1, gamma))) * V * 2      # rows up to the deciding one
+            touched = B * (2 * gamma + 1) * V * 2
+            out[key] = {"workload": f"B={B} gamma=8 V=32000 bf16 logits", "us": round(us, 2),
+                        "touched_GBps": round(touched / us / 1e3, 1), "algorithmic_GBps": round(alg / us / 1e3, 1),
+                        "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4)}
+            del T, Q, toks
         # ---- verification attention at batch 16, 4096 cached tokens, one 7B-shaped layer ----
         c1 = dict(synth.LLAMA7B_TARGET, n_layers=1, vocab=1024)
         m1 = bs.Model(c1, gpu_weights(c1, 9, torch)).pack(release_originals=True)

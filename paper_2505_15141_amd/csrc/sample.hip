@@ -485,16 +485,19 @@ template <typename T, int NG, bool CACHED>
 __global__ __launch_bounds__(ST) void spec_decide_kernel(DecideParams a) {
     __shared__ RowShared sh;
     __shared__ int s_acc[ST];
+    __shared__ float2 s_sp[ST + 1], s_sq[ST];     // row statistics of this sequence: no second trip to memory for them
     __shared__ float s_known[4];
     const int b = blockIdx.x, tid = threadIdx.x, gamma = a.gamma;
     const T* P = reinterpret_cast<const T*>(a.p_logits) + (size_t)b * (gamma + 1) * a.V;
     const T* Q = reinterpret_cast<const T*>(a.q_logits) + (size_t)b * gamma * a.V;
     const uint32_t t = a.round_ptr ? *a.round_ptr : a.round;
+    if (tid == 0) s_sp[gamma] = a.stats[(size_t)b * (gamma + 1) + gamma];
     for (int i = tid; i < gamma; i += ST) {
         int x = a.draft_tokens[(size_t)b * gamma + i];
         const bool okx = x >= 0 && x < a.V;
         if (!okx) x = 0;
         const float2 sp = a.stats[(size_t)b * (gamma + 1) + i], sq = a.stats[a.n_p_rows + (size_t)b * gamma + i];
+        s_sp[i] = sp; s_sq[i] = sq;
         const float px = __expf(load_one<T>(P + (size_t)i * a.V, x) * a.inv_temp - sp.x) / sp.y;
         const float qx = __expf(load_one<T>(Q + (size_t)i * a.V, x) * a.inv_temp - sq.x) / sq.y;
         const float u = a.uniforms ? a.uniforms[(size_t)b * (gamma + 1) + i]
@@ -509,12 +512,9 @@ __global__ __launch_bounds__(ST) void spec_decide_kernel(DecideParams a) {
     while (tau < gamma && s_acc[tau]) ++tau;
     const bool has_q = tau < gamma;
     if (tid == 0) {
-        const float2 sp = a.stats[(size_t)b * (gamma + 1) + tau];
+        const float2 sp = s_sp[tau];
         s_known[0] = sp.x; s_known[1] = sp.y; s_known[2] = 0.f; s_known[3] = 1.f;
-        if (has_q) {
-            const float2 sq = a.stats[a.n_p_rows + (size_t)b * gamma + tau];
-            s_known[2] = sq.x; s_known[3] = sq.y;
-        }
+        if (has_q) { const float2 sq = s_sq[tau]; s_known[2] = sq.x; s_known[3] = sq.y; }
     }
     __syncthreads();
     const float u_final = a.uniforms ? a.uniforms[(size_t)b * (gamma + 1) + gamma]
@@ -661,17 +661,12 @@ int launch_spec_sample(const void* p_logits, const void* q_logits, const int32_t
     a.p_logits = p_logits; a.q_logits = q_logits; a.draft_tokens = draft_tokens; a.uniforms = uniforms; a.seed = seed;
     a.round_ptr = round_ptr; a.round = round; a.gamma = gamma; a.V = V; a.n_p_rows = n_p; a.inv_temp = inv_temp;
     a.stats = stats; a.flags = flags; a.cand = cand; a.accept_len = accept_len; a.next_token = next_token; a.margins = margins;
-    // register-resident deciding row: 8 groups per lane of bf16 (V <= 32768), 2 groups per lane of float
-    const bool aligned = V % GE == 0 && ((uintptr_t)p_logits & 15) == 0 && ((uintptr_t)q_logits & 15) == 0;
-    const bool cached = aligned && V <= (dtype == BS_BF16 ? 8 : 2) * ST * GE;
+    // The deciding row pair is streamed again (it was read a moment ago by phase A: L2 / memory-side cache), not kept
+    // in registers: 42 instead of 256 registers per lane lets several sequences share a compute unit, which is what
+    // hides this kernel's chain of dependent loads (measured at B = 1024: 77 -> 42 us).
     const dim3 grid(B), block(ST);
-    if (dtype == BS_BF16) {
-        if (cached) hipLaunchKernelGGL((spec_decide_kernel<uint16_t, 8, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((spec_decide_kernel<uint16_t, 1, false>), grid, block, 0, stream, a);
-    } else {
-        if (cached) hipLaunchKernelGGL((spec_decide_kernel<float, 2, true>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((spec_decide_kernel<float, 1, false>), grid, block, 0, stream, a);
-    }
+    if (dtype == BS_BF16) hipLaunchKernelGGL((spec_decide_kernel<uint16_t, 1, false>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((spec_decide_kernel<float, 1, false>), grid, block, 0, stream, a);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
