@@ -7,6 +7,8 @@
 //   gemm        y = x W^T: bf16 weights streamed once from HBM through MFMA 16x16x32 tiles (the
 //               contraction is skinny: M = B*(gamma+1) rows, so it is bound by weight bandwidth),
 //               split-K partials out; fp32 variant for the fp32 plumbing configuration
+//   gemm_dec    the same contraction for one or two rows (draft steps) with the layer's small kernels
+//               folded into its epilogues (residual, RoPE + cache write, SwiGLU; RMSNorm by linearity)
 //   swiglu      sums gate/up partials, applies silu(g)*u
 //   rope_kv     sums q/k/v partials, rotates q and k, writes k/v into the cache
 //   attention   q_len causal query rows per head against the contiguous KV cache, split along the
