@@ -179,7 +179,7 @@ def main():
     round_gammas = gammas if by_throughput else gammas + [0]         # the device also knows the canonical step (gamma = 0)
     canon_arm = round_gammas.index(0)
     L, B, prefix = max(gammas), 1, 1024
-    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12
+    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12 + 14 * 4
     max_len = prefix + (L + 1) * total_rounds + L + 2
     seed = 2025
 
@@ -244,6 +244,16 @@ def main():
                 timed_round(canon_arm)
             torch.cuda.synchronize()
             canonical = args.canonical_rounds * B / (time.perf_counter() - t0)
+
+        # ---- round duration per arm (graph replay, host clock around launch + D2H of y), and the draft step it implies ----
+        round_ms = {}
+        if not args.pmc_mode:
+            for arm, g in enumerate(round_gammas):
+                if g == 0:
+                    continue
+                for _ in range(2):
+                    timed_round(arm)
+                round_ms[str(g)] = round(float(np.median([timed_round(arm)[1] for _ in range(12)])) * 1e3, 4)
 
         # ---- verify-step latency (eager, HIP events on this stream), per gamma ----
         verify_ms = {}
@@ -324,6 +334,9 @@ def main():
                       "graph": not args.no_graph},
            "mean_accepted_tokens": round(mean_y, 4), "generated_tokens": int(gen_tokens),
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
+           "round_ms_by_gamma": round_ms,
+           "draft_step_us": (round((round_ms["8"] - round_ms["2"] - (verify_ms["8"] - verify_ms["2"])) / 6.0 * 1e3, 1)
+                             if "8" in round_ms and "2" in round_ms and verify_ms else None),
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
            "canonical_decoding_tokens_per_s": round(canonical, 2) if canonical else None,

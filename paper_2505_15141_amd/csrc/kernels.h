@@ -28,6 +28,7 @@ struct DecArgs {
     float* x; const float* gain_next; uint16_t* out_planes; size_t out_plane; float* ssq_out;   // RESID; out_planes also SWIGLU
     const int32_t* pos; const float2* rope; int q_len, H, KVH, hd, cache_len;                    // QKV
     float* q_out; uint16_t* k_cache; uint16_t* v_cache;
+    const float* att_part; int att_splits;    // RESID with the attention's per-split partials as input instead of planes (uses H, hd)
 };
 bool gemm_dec_fits(int M, int K);
 int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s);
@@ -52,6 +53,7 @@ int launch_swiglu(int dtype, const float* part, int ks, size_t ks_stride, int M,
 int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const int32_t* pos, const float2* rope, int M,
                    int q_len, int H, int KVH, int hd, int max_len, float* q_out, void* k_cache, void* v_cache,
                    hipStream_t s);
+// out == nullptr: the splits are left un-merged in `part` (the consumer combines them)
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
                      int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,
                      hipStream_t s);

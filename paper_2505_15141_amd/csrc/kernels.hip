@@ -458,7 +458,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_m16_kernel(GemmArgs a, int kper
 // the weight bytes in L1 traffic at 16 rows, which is why this path is for a handful of rows only.
 // Weights are in the tiled layout.
 
-template <int EPI, int DEPTH>
+template <int EPI, int DEPTH, bool MERGE>
 __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
     __shared__ __attribute__((aligned(16))) float red[8][256];
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];     // [2 planes][M][K + 8]
@@ -523,11 +523,13 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
     const int kc8 = a.K / 8;                                      // 16-byte chunks per row
     const int kc0 = threadIdx.x < (unsigned)kc8 ? (int)threadIdx.x : 0;       // lanes past the row re-read chunk 0 (not stored)
     uint4 xv0[2 * DEC_MAX_ROWS];
+    if (!MERGE) {
 #pragma unroll
-    for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr) {               // pr = plane * M + row, clamped to the last valid pair
-        const int q = min(pr, 2 * a.M - 1);
-        const int plane = q >= a.M ? 1 : 0, m = q - plane * a.M;
-        xv0[pr] = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc0 * 8);
+        for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr) {           // pr = plane * M + row, clamped to the last valid pair
+            const int q = min(pr, 2 * a.M - 1);
+            const int plane = q >= a.M ? 1 : 0, m = q - plane * a.M;
+            xv0[pr] = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc0 * 8);
+        }
     }
     const int steps = a.K / 32;
     const int ws_shift = __ffs(WS) - 1;                           // WS is 4 or 8
@@ -545,13 +547,69 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) rw[u] = ldg16((const uint16_t*)(wb + w0 + min(u, nn) * 4096));   // clamped to the last step
     }
+    if (!MERGE) {
 #pragma unroll
-    for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr)
-        if (pr < 2 * a.M && threadIdx.x < (unsigned)kc8) *reinterpret_cast<uint4*>(&xs[pr * row_e + threadIdx.x * 8]) = xv0[pr];
-    for (int pr = 0; pr < 2 * a.M; ++pr) {                        // rows longer than the workgroup (8 columns per lane): the rest
-        const int plane = pr >= a.M ? 1 : 0, m = pr - plane * a.M;
-        for (int kc = threadIdx.x + blockDim.x; kc < kc8; kc += blockDim.x)
-            *reinterpret_cast<uint4*>(&xs[pr * row_e + kc * 8]) = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc * 8);
+        for (int pr = 0; pr < 2 * DEC_MAX_ROWS; ++pr)
+            if (pr < 2 * a.M && threadIdx.x < (unsigned)kc8) *reinterpret_cast<uint4*>(&xs[pr * row_e + threadIdx.x * 8]) = xv0[pr];
+        for (int pr = 0; pr < 2 * a.M; ++pr) {                    // rows longer than the workgroup (8 columns per lane): the rest
+            const int plane = pr >= a.M ? 1 : 0, m = pr - plane * a.M;
+            for (int kc = threadIdx.x + blockDim.x; kc < kc8; kc += blockDim.x)
+                *reinterpret_cast<uint4*>(&xs[pr * row_e + kc * 8]) = ldg16(a.xh + (size_t)plane * a.x_plane + (size_t)m * a.K + kc * 8);
+        }
+    } else {
+        // The activations are the attention output, still as per-split partials (o[hd], max, sum): each lane combines
+        // the splits of eight head-dim elements (online over groups of 8 splits, all loads of a group in flight) and
+        // writes both planes.  Every workgroup redoes this for the whole row: a few KB from L2, one kernel fewer.
+        const size_t pstride = (size_t)a.hd + 4;
+        const int hd_shift = __ffs(a.hd) - 1;
+        for (int m = 0; m < a.M; ++m)
+            for (int kc = threadIdx.x; kc < kc8; kc += blockDim.x) {
+                const int col = kc * 8, h = col >> hd_shift, d0 = col & (a.hd - 1);
+                const float* base = a.att_part + ((size_t)m * a.H + h) * a.att_splits * pstride;
+                float mm = -INFINITY, lsum = 0.f, o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = 0.f;
+                for (int s0 = 0; s0 < a.att_splits; s0 += 8) {
+                    float4 oa[8], ob[8];
+                    float2 ml[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const float* ps = base + (size_t)min(s0 + u, a.att_splits - 1) * pstride;
+                        oa[u] = *reinterpret_cast<const float4*>(ps + d0);
+                        ob[u] = *reinterpret_cast<const float4*>(ps + d0 + 4);
+                        ml[u] = *reinterpret_cast<const float2*>(ps + a.hd);
+                        if (s0 + u >= a.att_splits) ml[u] = make_float2(-INFINITY, 0.f);
+                    }
+                    float gm = mm;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) gm = fmaxf(gm, ml[u].x);
+                    if (gm == -INFINITY) continue;
+                    const float keep = __expf(mm - gm);                  // 0 when nothing was accumulated yet
+                    lsum *= keep;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] *= keep;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const float f = (ml[u].x == -INFINITY) ? 0.f : __expf(ml[u].x - gm);
+                        if (f == 0.f) continue;                          // an empty split's o[] was never written
+                        lsum += ml[u].y * f;
+                        o[0] += oa[u].x * f; o[1] += oa[u].y * f; o[2] += oa[u].z * f; o[3] += oa[u].w * f;
+                        o[4] += ob[u].x * f; o[5] += ob[u].y * f; o[6] += ob[u].z * f; o[7] += ob[u].w * f;
+                    }
+                    mm = gm;
+                }
+                const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+                uint32_t hw[4], lw[4];
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float v0 = o[e] * inv, v1 = o[e + 1] * inv;
+                    const uint16_t h0 = from_f<uint16_t>(v0), h1 = from_f<uint16_t>(v1);
+                    hw[e / 2] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+                    lw[e / 2] = (uint32_t)from_f<uint16_t>(v0 - to_f(h0)) | ((uint32_t)from_f<uint16_t>(v1 - to_f(h1)) << 16);
+                }
+                *reinterpret_cast<uint4*>(&xs[(size_t)m * row_e + col]) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+                *reinterpret_cast<uint4*>(&xs[(size_t)(a.M + m) * row_e + col]) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+            }
     }
     __syncthreads();                                              // activations are in LDS
     if (n > 0) {
@@ -903,11 +961,11 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
     const int kvh = h / (H / KVH);
     const int m_first = b * q_len;
     const int pos0 = pos[m_first];
-    const size_t pstride = (size_t)hd + 2;
+    const size_t pstride = (size_t)hd + 4;       // o[hd], max, sum, 2 pad: rows stay 16-byte aligned
     if (pos0 < 0) {                                // sequence skipped: empty partials
         for (int idx = threadIdx.x; idx < q_len; idx += 256) {
             float* dst = part + ((((size_t)(m_first + idx)) * H + h) * n_splits + split) * pstride;
-            dst[0] = -INFINITY; dst[1] = 0.f;
+            dst[hd] = -INFINITY; dst[hd + 1] = 0.f;
         }
         return;
     }
@@ -1006,8 +1064,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
                 l += wl[w][r] * f;
             }
             float* dst = part + ((((size_t)(m_first + r0 + r)) * H + h) * n_splits + split) * pstride;
-            dst[2 + d] = o;
-            if (d == 0) { dst[0] = mm; dst[1] = l; }
+            dst[d] = o;
+            if (d == 0) { dst[hd] = mm; dst[hd + 1] = l; }
         }
     }
 }
@@ -1046,12 +1104,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
     const int G = H / KVH, R = G * q_len;
     const int m_first = b * q_len;
     const int pos0 = pos[m_first];
-    const size_t pstride = (size_t)HD + 2;
+    const size_t pstride = (size_t)HD + 4;       // o[HD], max, sum, 2 pad: rows stay 16-byte aligned
     if (pos0 < 0) {                                  // sequence skipped: empty partials
         for (int r = threadIdx.x; r < R; r += 256) {
             const int g = r / q_len, qi = r % q_len;
             float* dst = part + ((((size_t)(m_first + qi)) * H + kvh * G + g) * n_splits + split) * pstride;
-            dst[0] = -INFINITY; dst[1] = 0.f;
+            dst[HD] = -INFINITY; dst[HD + 1] = 0.f;
         }
         return;
     }
@@ -1183,8 +1241,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
             }
             const int gg = (r0 + r) / q_len, qq = (r0 + r) % q_len;
             float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
-            dst[2 + d] = ov;
-            if (d == 0) { dst[0] = mm; dst[1] = lv; }
+            dst[d] = ov;
+            if (d == 0) { dst[HD] = mm; dst[HD + 1] = lv; }
         }
     }
 }
@@ -1194,14 +1252,14 @@ template <typename T>
 __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, size_t plane, void* __restrict__ out) {
     const size_t mh = blockIdx.x;
     const int d = threadIdx.x;
-    const size_t pstride = (size_t)hd + 2;
+    const size_t pstride = (size_t)hd + 4;       // o[hd], max, sum, 2 pad: rows stay 16-byte aligned
     const float* base = part + mh * n_splits * pstride;
     // loads of up to 8 splits are issued together (they are independent), then combined
     float mm = -INFINITY;
     for (int s0 = 0; s0 < n_splits; s0 += 8) {
         float mv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = (s0 + u < n_splits) ? base[(s0 + u) * pstride] : -INFINITY;
+        for (int u = 0; u < 8; ++u) mv[u] = (s0 + u < n_splits) ? base[(s0 + u) * pstride + hd] : -INFINITY;
 #pragma unroll
         for (int u = 0; u < 8; ++u) mm = fmaxf(mm, mv[u]);
     }
@@ -1211,13 +1269,14 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const bool ok = s0 + u < n_splits;
-            mv[u] = ok ? base[(s0 + u) * pstride] : -INFINITY;
-            lv[u] = ok ? base[(s0 + u) * pstride + 1] : 0.f;
-            ov[u] = ok ? base[(s0 + u) * pstride + 2 + d] : 0.f;
+            mv[u] = ok ? base[(s0 + u) * pstride + hd] : -INFINITY;
+            lv[u] = ok ? base[(s0 + u) * pstride + hd + 1] : 0.f;
+            ov[u] = ok ? base[(s0 + u) * pstride + d] : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const float f = (mv[u] == -INFINITY) ? 0.f : __expf(mv[u] - mm);
+            if (f == 0.f) continue;                      // an empty split's o[] was never written
             l += lv[u] * f;
             o += ov[u] * f;
         }
@@ -1252,6 +1311,8 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
     BS_REQUIRE(a.M >= 1 && a.M <= 16 && a.K % 32 == 0 && a.N % 16 == 0 && a.K >= 32, BS_ESHAPE, "gemm_dec: M=%d N=%d K=%d", a.M, a.N, a.K);
     BS_REQUIRE((double)a.N * a.K * 2.0 < 4294967296.0 && (double)a.M * a.K * 2.0 < 4294967296.0, BS_ESHAPE,
                "gemm_dec: a matrix of %d x %d exceeds the 32-bit byte offsets of this kernel", a.N, a.K);
+    BS_REQUIRE(!a.att_part || (epi == EPI_RESID && a.att_splits >= 1 && (a.hd == 64 || a.hd == 128) && a.K == a.H * a.hd), BS_ESHAPE,
+               "gemm_dec: attention partials as input need the O projection's shape (K = %d, H = %d, hd = %d)", a.K, a.H, a.hd);
     BS_REQUIRE(epi != EPI_QKV || (a.hd % 16 == 0 && a.seg_rows[0] % 16 == 0 && a.seg_rows[1] % 16 == 0), BS_ESHAPE, "gemm_dec: head_dim %d", a.hd);
     const int steps = a.K / 32;
     // wavefronts per 16-column tile: about six k steps each, 4 or 8 of them; the gate/up pair takes 4 + 4
@@ -1265,11 +1326,12 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
         BS_HIP(hipEventRecord(e0, s));
     }
     const size_t lds = dec_lds_bytes(a.M, a.K);
-#define BS_DEC(E) do { if (deep) hipLaunchKernelGGL((gemm_dec_kernel<E, 8>), grid, block, lds, s, a); \
-                       else hipLaunchKernelGGL((gemm_dec_kernel<E, 4>), grid, block, lds, s, a); } while (0)
-    if (epi == EPI_RESID) BS_DEC(EPI_RESID);
-    else if (epi == EPI_QKV) BS_DEC(EPI_QKV);
-    else BS_DEC(EPI_SWIGLU);
+#define BS_DEC(E, MG) do { if (deep) hipLaunchKernelGGL((gemm_dec_kernel<E, 8, MG>), grid, block, lds, s, a); \
+                           else hipLaunchKernelGGL((gemm_dec_kernel<E, 4, MG>), grid, block, lds, s, a); } while (0)
+    if (epi == EPI_RESID && a.att_part) BS_DEC(EPI_RESID, true);
+    else if (epi == EPI_RESID) BS_DEC(EPI_RESID, false);
+    else if (epi == EPI_QKV) BS_DEC(EPI_QKV, false);
+    else BS_DEC(EPI_SWIGLU, false);
 #undef BS_DEC
     BS_LAUNCH_CHECK();
     if (g_prof.on) {                                       // class 50: fused few-row projections
@@ -1354,7 +1416,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
             g_prof.bytes.push_back(0.0);
             g_prof.mt.push_back(100);
         }
-        hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
+        if (out) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
                            (const float*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);

@@ -177,7 +177,7 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.part_o = (float*)take(M * c.d_model * 4 * w.ks_o);
     w.part_gu = (float*)take(M * 2 * c.d_ff * 4 * w.ks_gu);
     w.part_d = (float*)take(M * c.d_model * 4 * w.ks_d);
-    w.part_attn = (float*)take(M * c.n_heads * attn_splits(B, c.n_heads, max_len) * (size_t)(c.head_dim + 2) * 4);
+    w.part_attn = (float*)take(M * c.n_heads * attn_splits(B, c.n_heads, max_len) * (size_t)(c.head_dim + 4) * 4);
     w.total = off;
     return w;
 }
@@ -237,8 +237,9 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
             a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
             BS_TRY(launch_gemm_dec(EPI_QKV, a, s));
             BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
-                                    (size_t)M * nq, w.att, s));
+                                    (size_t)M * nq, nullptr, s));          // splits are merged by the O projection
             a = DecArgs{};
+            a.att_part = w.part_attn; a.att_splits = splits; a.H = H; a.hd = hd;
             a.xh = reinterpret_cast<const uint16_t*>(w.att); a.x_plane = (size_t)M * nq; a.w[0] = L.wo; a.M = M; a.N = d; a.K = nq;
             a.x = w.x; a.gain_next = L.ffn_norm; a.out_planes = hp; a.out_plane = pd; a.ssq_out = w.ssq;
             BS_TRY(launch_gemm_dec(EPI_RESID, a, s));
