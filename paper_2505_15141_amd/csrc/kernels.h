@@ -48,11 +48,16 @@ int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, in
 int launch_embed(int dtype, const int32_t* tok, const void* embed, int M, int d, float* x, hipStream_t s);
 int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d,
                    float eps, int n_seq, int rows_in, int rows_out, size_t plane, void* out, hipStream_t s);
+// bf16 models: residual completion + planes of gain .* x + per-chunk sums of squares [rows][norm_chunks(d)]; the
+// consumers below apply the rows' RMS scale when given those sums (ssq != nullptr)
+int norm_chunks(int d);
+int launch_resid_sum(float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d, int rows,
+                     size_t plane, void* out, float* ssq, hipStream_t s);
 int launch_swiglu(int dtype, const float* part, int ks, size_t ks_stride, int M, int ff, size_t plane, void* out,
-                  hipStream_t s);
+                  const float* ssq, int d, float eps, hipStream_t s);
 int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const int32_t* pos, const float2* rope, int M,
                    int q_len, int H, int KVH, int hd, int max_len, float* q_out, void* k_cache, void* v_cache,
-                   hipStream_t s);
+                   const float* ssq, int d, float eps, hipStream_t s);
 // out == nullptr: the splits are left un-merged in `part` (the consumer combines them)
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
                      int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,

@@ -194,10 +194,58 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(float* __restrict__ x, co
     }
 }
 
+// ---- residual completion for bf16 models (the 16-row and many-row schedules) ---------------------------
+// RMSNorm commutes with the projection that follows it (norm(x) W^T = r * ((gain .* x) W^T), r per row), so the
+// row-wide reduction does not have to finish before the projection starts: this kernel only completes the residual
+// (x += sum of the pending split-K partials), writes the planes of gain .* x and ONE partial sum of squares per
+// 1024-column chunk; the projection's consumer (rope_kv, swiglu) multiplies by r.  grid (rows, ceil(d/1024)):
+// every row is spread over several compute units instead of one.
+__global__ __launch_bounds__(256) void resid_sum_kernel(float* __restrict__ x, const float* __restrict__ pend, int pend_ks,
+                                                        size_t pend_stride, const float* __restrict__ gain, int d, size_t plane,
+                                                        uint16_t* __restrict__ out, float* __restrict__ ssq) {
+    __shared__ float red[4];
+    const int r = blockIdx.x, chunk = blockIdx.y, nchunks = gridDim.y;
+    const int i = chunk * 1024 + threadIdx.x * 4;                 // d % 8 == 0 (host check): whole float4 granules
+    float ss = 0.f;
+    if (i < d) {
+        float* row = x + (size_t)r * d + i;
+        float4 v = *reinterpret_cast<const float4*>(row);
+        if (pend) {
+            const float* prow = pend + (size_t)r * d + i;
+            for (int s0 = 0; s0 < pend_ks; s0 += 8) {
+                float4 p[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    p[u] = *reinterpret_cast<const float4*>(prow + (size_t)min(s0 + u, pend_ks - 1) * pend_stride);
+                    if (s0 + u >= pend_ks) p[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
+            }
+            *reinterpret_cast<float4*>(row) = v;
+        }
+        ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        const float4 g = *reinterpret_cast<const float4*>(gain + i);
+        store_planes4(out, plane, (size_t)r * d + i, v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w);
+    }
+    ss = wsum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq[(size_t)r * nchunks + chunk] = red[0] + red[1] + red[2] + red[3];
+}
+
+// r = rsqrt(mean square + eps) of row m from its per-chunk sums of squares (null: no scaling)
+__device__ __forceinline__ float row_rscale(const float* __restrict__ ssq, int nchunks, int m, float inv_d, float eps) {
+    if (!ssq) return 1.f;
+    float tot = 0.f;
+    for (int c = 0; c < nchunks; ++c) tot += ssq[(size_t)m * nchunks + c];
+    return 1.0f / sqrtf(tot * inv_d + eps);
+}
+
 // ---- SwiGLU over split-K partials: act = silu(sum_s g) * sum_s u, columns [0,ff) gate, [ff,2ff) up ------
 template <typename T>
 __global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_stride, int M, int ff, size_t plane,
-                              void* __restrict__ out) {
+                              void* __restrict__ out, const float* __restrict__ ssq, int nchunks, float inv_d, float eps) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)M * ff) return;
     const size_t m = idx / ff, j = idx % ff;
@@ -206,6 +254,8 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_
         g += part[(size_t)s * ks_stride + m * 2 * ff + j];
         u += part[(size_t)s * ks_stride + m * 2 * ff + ff + j];
     }
+    const float rs = row_rscale(ssq, nchunks, (int)m, inv_d, eps);     // the input rows' RMS scale, if it was deferred
+    g *= rs; u *= rs;
     Act<T>::store(out, plane, idx, g / (1.0f + __expf(-g)) * u);
 }
 
@@ -896,7 +946,8 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int ks, size_t ks_stride, const int32_t* __restrict__ pos,
                                const float2* __restrict__ rope, int q_len, int H, int KVH, int hd, int max_len,
-                               float* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache) {
+                               float* __restrict__ q_out, T* __restrict__ k_cache, T* __restrict__ v_cache,
+                               const float* __restrict__ ssq, int nchunks, float inv_d, float eps) {
     const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;       // i < hd/2
     const int p = pos[m];
     const int b = m / q_len;
@@ -906,6 +957,10 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int ks, size_t ks
     for (int s = 0; s < ks; ++s) {
         const float2 v = *reinterpret_cast<const float2*>(src + (size_t)s * ks_stride + 2 * i);
         x0 += v.x; x1 += v.y;
+    }
+    {
+        const float rs = row_rscale(ssq, nchunks, m, inv_d, eps);      // the input rows' RMS scale, if it was deferred
+        x0 *= rs; x1 *= rs;
     }
     if (head < H + KVH) {
         const float2 cs = rope[(size_t)m * (hd / 2) + i];
@@ -1343,6 +1398,8 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
     return BS_OK;
 }
 
+int norm_chunks(int d) { return (d + 1023) / 1024; }
+
 int launch_embed(int dtype, const int32_t* tok, const void* embed, int M, int d, float* x, hipStream_t s) {
     if (dtype == BS_BF16)
         hipLaunchKernelGGL((embed_kernel<uint16_t>), dim3(M), dim3(256), 0, s, tok, (const uint16_t*)embed, d, x);
@@ -1364,26 +1421,39 @@ int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t p
     return BS_OK;
 }
 
+int launch_resid_sum(float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d, int rows,
+                     size_t plane, void* out, float* ssq, hipStream_t s) {
+    if (rows <= 0) return BS_OK;
+    hipLaunchKernelGGL(resid_sum_kernel, dim3(rows, norm_chunks(d)), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, plane,
+                       (uint16_t*)out, ssq);
+    BS_LAUNCH_CHECK();
+    return BS_OK;
+}
+
 int launch_swiglu(int dtype, const float* part, int ks, size_t ks_stride, int M, int ff, size_t plane, void* out,
-                  hipStream_t s) {
+                  const float* ssq, int d, float eps, hipStream_t s) {
     const size_t n = (size_t)M * ff;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
-    if (dtype == BS_BF16) hipLaunchKernelGGL((swiglu_kernel<uint16_t>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out);
-    else hipLaunchKernelGGL((swiglu_kernel<float>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out);
+    const int nch = norm_chunks(d);
+    const float inv_d = 1.0f / (float)d;
+    if (dtype == BS_BF16) hipLaunchKernelGGL((swiglu_kernel<uint16_t>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out, ssq, nch, inv_d, eps);
+    else hipLaunchKernelGGL((swiglu_kernel<float>), grid, block, 0, s, part, ks, ks_stride, M, ff, plane, out, ssq, nch, inv_d, eps);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
 
 int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const int32_t* pos, const float2* rope, int M,
                    int q_len, int H, int KVH, int hd, int max_len, float* q_out, void* k_cache, void* v_cache,
-                   hipStream_t s) {
+                   const float* ssq, int d, float eps, hipStream_t s) {
     const dim3 grid(M, H + 2 * KVH), block(hd / 2);
+    const int nch = norm_chunks(d);
+    const float inv_d = 1.0f / (float)d;
     if (dtype == BS_BF16)
         hipLaunchKernelGGL((rope_kv_kernel<uint16_t>), grid, block, 0, s, part, ks, ks_stride, pos, rope, q_len, H, KVH, hd,
-                           max_len, q_out, (uint16_t*)k_cache, (uint16_t*)v_cache);
+                           max_len, q_out, (uint16_t*)k_cache, (uint16_t*)v_cache, ssq, nch, inv_d, eps);
     else
         hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, part, ks, ks_stride, pos, rope, q_len, H, KVH, hd,
-                           max_len, q_out, (float*)k_cache, (float*)v_cache);
+                           max_len, q_out, (float*)k_cache, (float*)v_cache, ssq, nch, inv_d, eps);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }

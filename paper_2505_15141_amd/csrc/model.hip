@@ -262,26 +262,34 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         const bs_layer_weights& L = m->layers[l];
         char* kc = kv->buf + (size_t)l * kv_layer;
         char* vc = kc + kv_layer / 2;
-        BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, c.norm_eps, B, q_len, q_len,
-                              (size_t)M * d, w.h, s));
+        const bool defer = dt == BS_BF16;        // bf16: RMS scale applied behind the projection (see resid_sum_kernel)
+        const float* ssq = defer ? w.ssq : nullptr;
+        if (defer)
+            BS_TRY(launch_resid_sum(w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, M, (size_t)M * d, w.h, w.ssq, s));
+        else
+            BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, c.norm_eps, B, q_len, q_len,
+                                  (size_t)M * d, w.h, s));
         GemmArgs g;
         g.tiled = m->packed ? 1 : 0;
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
         g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
         BS_TRY(launch_gemm(dt, g, s));
         BS_TRY(launch_rope_kv(dt, w.part_qkv, w.ks_qkv, (size_t)M * nqkv, w.pos, w.rope, M, q_len, H, KVH, hd, crow,
-                              w.q, kc, vc, s));
+                              w.q, kc, vc, ssq, d, c.norm_eps, s));
         BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
                                 (size_t)M * nq, w.att, s));
         g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_o; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = nq; g.ldo = d; g.KS = w.ks_o;
         BS_TRY(launch_gemm(dt, g, s));
-        BS_TRY(launch_rmsnorm(dt, w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, c.norm_eps, B, q_len, q_len,
-                              (size_t)M * d, w.h, s));
+        if (defer)
+            BS_TRY(launch_resid_sum(w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, M, (size_t)M * d, w.h, w.ssq, s));
+        else
+            BS_TRY(launch_rmsnorm(dt, w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, c.norm_eps, B, q_len, q_len,
+                                  (size_t)M * d, w.h, s));
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = ff; g.seg_rows[1] = ff;
         g.out = w.part_gu; g.ks_stride = (size_t)M * 2 * ff; g.M = M; g.N = 2 * ff; g.K = d; g.ldo = 2 * ff; g.KS = w.ks_gu;
         BS_TRY(launch_gemm(dt, g, s));
-        BS_TRY(launch_swiglu(dt, w.part_gu, w.ks_gu, (size_t)M * 2 * ff, M, ff, (size_t)M * ff, w.act, s));
+        BS_TRY(launch_swiglu(dt, w.part_gu, w.ks_gu, (size_t)M * 2 * ff, M, ff, (size_t)M * ff, w.act, ssq, d, c.norm_eps, s));
         g.x = w.act; g.x_plane = (size_t)M * ff; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_d; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = ff; g.ldo = d; g.KS = w.ks_d;
         BS_TRY(launch_gemm(dt, g, s));
