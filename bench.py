@@ -193,9 +193,11 @@ def main():
     goal = torch.full((B,), max_len, dtype=torch.int32, device="cuda")
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        t0 = time.perf_counter()
-        bs.prefill(target, tkv, tokens, prefix - 1)
+        bs.prefill(target, tkv, tokens, prefix - 1)          # first pass also loads the code objects
         bs.prefill(draft, dkv, tokens, prefix - 1)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        bs.prefill(target, tkv, tokens, prefix - 1)          # same tokens again: the timed prompt pass of the target
         stream.synchronize()
         prefill_s = time.perf_counter() - t0
         rnd = bs.Round(target, tkv, [draft], [dkv], [0] * len(round_gammas), round_gammas, tokens, total, goal, 1.0, seed,
@@ -341,7 +343,11 @@ def main():
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
            "canonical_decoding_tokens_per_s": round(canonical, 2) if canonical else None,
            "speedup_vs_canonical": round(gen_tokens / elapsed / canonical, 3) if canonical and args.steps else None,
-           "prefill_s": round(prefill_s, 3), "stages": stages, "roofline": roofline}
+           "prefill": {"tokens": prefix - 1, "seconds": round(prefill_s, 4), "tokens_per_s": round((prefix - 1) / prefill_s, 1),
+                       # projections only: 2 flops per weight and token; both activation planes go through the matrix cores
+                       "useful_TFLOPs": round(weights_bytes * (prefix - 1) / prefill_s / 1e12, 1),
+                       "mfma_issue_frac_of_peak": round(2 * weights_bytes * (prefix - 1) / prefill_s / 2.5e15, 4)},
+           "stages": stages, "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(tc, dc, prefix, 4, mean_y)
     print(json.dumps(out))

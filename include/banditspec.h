@@ -266,7 +266,7 @@ int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const flo
  * GEMM and of the bf16 attention kernel made OUTSIDE a graph capture is bracketed by HIP events on its
  * own stream.  bs_profile_collect synchronises on those events and returns, for launches of the asked
  * class, the summed kernel time in ms, the summed algorithmic bytes and the launch count.  Classes:
- * 1, 2, 4, 6 = GEMM launches with that many tiles of 16 activation rows (bytes: each weight element
+ * 1, 2, 4, 6, 8, 16 = GEMM launches with up to that many tiles of 16 activation rows (bytes: each weight element
  * once, N*K*2); 50 = the fused few-row projections of draft steps (same bytes); 100 = attention (bytes
  * reported as 0: the cache lengths live on the device, the caller knows them); 0 = everything.  Enabling clears earlier records.  Do not enable while a graph is being
  * captured.

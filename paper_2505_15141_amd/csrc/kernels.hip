@@ -299,21 +299,22 @@ __global__ void pack_weights_kernel(const uint16_t* __restrict__ src, uint16_t* 
     *reinterpret_cast<uint4*>(dst + c * 8) = v;
 }
 
-template <int MT, int KC, bool TILED>
+template <int MT, int NT, int KC, bool TILED>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
     constexpr int ROW = KC + 8;                       // padded LDS row (bf16 elements)
     constexpr int NSL = KC / 32;                      // k slices per stage
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][MT * 16][ROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
-    const int n0 = blockIdx.x * 64 + wave * 16;
-    const uint16_t* wrow;
-    {
-        int n = n0 + li;
+    const int n0 = blockIdx.x * (64 * NT) + wave * (16 * NT);    // this wavefront: NT tiles of 16 weight rows
+    const uint16_t* wrow[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        int n = n0 + u * 16 + li;
         if (n >= a.N) n = a.N - 1;
         int seg = 0, local = n;
         if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
-        wrow = wlane_ptr<TILED>(reinterpret_cast<const uint16_t*>(a.w[seg]), local, a.K, lq);
+        wrow[u] = wlane_ptr<TILED>(reinterpret_cast<const uint16_t*>(a.w[seg]), local, a.K, lq);
     }
     const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
     const uint16_t* xl = xh + a.x_plane;
@@ -322,63 +323,221 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
     const int ks = blockIdx.y, KS = gridDim.y;
     const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
 
-    f32x4 acc[MT];
+    f32x4 acc[NT][MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int u = 0; u < NT; ++u)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 wcur[NSL], wnext[NSL];
-    auto load_stage = [&](int st, uint4 (&dst)[NSL]) {
+    uint4 wcur[NT][NSL], wnext[NT][NSL];
+    auto load_stage = [&](int st, uint4 (&dst)[NT][NSL]) {
         const int kb = st * KC;                       // wrow already points at this lane's k-slot
 #pragma unroll
-        for (int j = 0; j < NSL; ++j) {
-            const int k = kb + j * 32;
-            dst[j] = (st < st_end && k + lq * 8 < a.K) ? ldg16(wrow + (size_t)k * (WSTEP<TILED>::v / 32)) : make_uint4(0, 0, 0, 0);
-        }
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int j = 0; j < NSL; ++j) {
+                const int k = kb + j * 32;
+                dst[u][j] = (st < st_end && k + lq * 8 < a.K) ? ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32)) : make_uint4(0, 0, 0, 0);
+            }
     };
-    load_stage(st_begin, wcur);
-    for (int st = st_begin; st < st_end; ++st) {
-        load_stage(st + 1, wnext);                    // prefetch (all zero past the end)
-        __syncthreads();                              // previous stage's LDS reads are done
-        // stage the activation slice: 16-byte chunks, rows >= M and columns >= K are zero
-        constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
-        for (int c = threadIdx.x; c < CHUNKS; c += 256) {
+    // Activation slice of a stage: 16-byte chunks, rows >= M and columns >= K are zero.  It is requested into registers
+    // one stage ahead (behind the weight prefetch) and written to LDS after the MFMAs of the current stage, so the trip
+    // to memory hides behind them.
+    constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
+    constexpr int XPT = (CHUNKS + 255) / 256;         // chunks per lane
+    uint4 xr[XPT];
+    auto load_x = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int c = threadIdx.x + i * 256;
             const int plane = c / (MT * 16 * (KC / 8));
             const int rem = c % (MT * 16 * (KC / 8));
             const int m = rem / (KC / 8), kc = (rem % (KC / 8)) * 8;
             const int k = st * KC + kc;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m < a.M && k < a.K) v = ldg16((plane ? xl : xh) + (size_t)m * a.K + k);
-            *reinterpret_cast<uint4*>(&xs[plane][m][kc]) = v;
+            const bool ok = c < CHUNKS && st < st_end && m < a.M && k < a.K;
+            const uint4 v = ldg16((plane ? xl : xh) + (ok ? (size_t)m * a.K + k : 0));       // always a valid address
+            xr[i] = ok ? v : make_uint4(0, 0, 0, 0);
         }
-        __syncthreads();
+    };
+    auto store_x = [&]() {
 #pragma unroll
-        for (int j = 0; j < NSL; ++j) {
-            const bf16x8 A = __builtin_bit_cast(bf16x8, wcur[j]);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const uint4 bh = *reinterpret_cast<const uint4*>(&xs[0][t * 16 + li][j * 32 + lq * 8]);
-                const uint4 bl = *reinterpret_cast<const uint4*>(&xs[1][t * 16 + li][j * 32 + lq * 8]);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bh), acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, bl), acc[t], 0, 0, 0);
+        for (int i = 0; i < XPT; ++i) {
+            const int c = threadIdx.x + i * 256;
+            if (c < CHUNKS) {
+                const int plane = c / (MT * 16 * (KC / 8));
+                const int rem = c % (MT * 16 * (KC / 8));
+                *reinterpret_cast<uint4*>(&xs[plane][rem / (KC / 8)][(rem % (KC / 8)) * 8]) = xr[i];
             }
         }
+    };
+    load_stage(st_begin, wcur);
+    load_x(st_begin);
+    store_x();
+    __syncthreads();
+    for (int st = st_begin; st < st_end; ++st) {
+        load_stage(st + 1, wnext);                    // prefetch (all zero past the end)
+        load_x(st + 1);
 #pragma unroll
-        for (int j = 0; j < NSL; ++j) wcur[j] = wnext[j];
+        for (int j = 0; j < NSL; ++j) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {            // one pair of activation operands serves the NT weight tiles
+                const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[0][t * 16 + li][j * 32 + lq * 8]));
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[1][t * 16 + li][j * 32 + lq * 8]));
+#pragma unroll
+                for (int u = 0; u < NT; ++u) {
+                    const bf16x8 A = __builtin_bit_cast(bf16x8, wcur[u][j]);
+                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bh, acc[u][t], 0, 0, 0);
+                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bl, acc[u][t], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();                              // every wavefront is done reading this stage's slice
+        store_x();
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int j = 0; j < NSL; ++j) wcur[u][j] = wnext[u][j];
     }
-    // D[n = n0 + 4*lq + e][m = 16t + li]: four consecutive n per lane -> one 16-byte store
+    // D[n = n0 + 16u + 4*lq + e][m = 16t + li]: four consecutive n per lane -> one 16-byte store
     float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride;
-    const int nb = n0 + 4 * lq;
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const int m = t * 16 + li;
-        if (m >= a.M) continue;
-        float* o = out + (size_t)m * a.ldo + nb;
-        if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
-            *reinterpret_cast<float4*>(o) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
-        } else {
+    for (int u = 0; u < NT; ++u) {
+        const int nb = n0 + u * 16 + 4 * lq;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (nb + e < a.N) o[e] = acc[t][e];
+        for (int t = 0; t < MT; ++t) {
+            const int m = t * 16 + li;
+            if (m >= a.M) continue;
+            float* o = out + (size_t)m * a.ldo + nb;
+            if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
+                *reinterpret_cast<float4*>(o) = make_float4(acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (nb + e < a.N) o[e] = acc[u][t][e];
+            }
+        }
+    }
+}
+
+// ---- GEMM for 129..256 activation rows (prompt processing of one sequence) ----------------------------
+// From about 150 rows on the projections are bound by the matrix cores, not by the weight stream (two MFMAs per
+// weight tile and activation tile because of the two planes).  Same operand mapping as above with everything sized
+// for that regime: 8 wavefronts x 2 weight tiles = 256 weight rows per workgroup, 256 activation rows = 16 tiles,
+// stages of 64 columns, and the activation slice DOUBLE-buffered in LDS (2 x 72 KiB of the 160 KiB a compute unit
+// has): the next slice travels memory -> registers during the MFMAs of the current one and is written to the other
+// buffer, so a stage costs one barrier and no exposed memory latency.
+constexpr int BIG_MT = 16, BIG_NT = 2, BIG_KC = 64, BIG_WAVES = 8;
+
+template <bool TILED>
+__global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs a) {
+    constexpr int MT = BIG_MT, NT = BIG_NT, KC = BIG_KC, NTHR = 64 * BIG_WAVES;
+    constexpr int ROW = KC + 8, NSL = KC / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][2][MT * 16][ROW];      // [buffer][plane][row][column]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const int n0 = blockIdx.x * (16 * NT * BIG_WAVES) + wave * (16 * NT);
+    const uint16_t* wrow[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        int n = n0 + u * 16 + li;
+        if (n >= a.N) n = a.N - 1;
+        int seg = 0, local = n;
+        if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+        wrow[u] = wlane_ptr<TILED>(reinterpret_cast<const uint16_t*>(a.w[seg]), local, a.K, lq);
+    }
+    const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
+    const uint16_t* xl = xh + a.x_plane;
+    const int nstages = (a.K + KC - 1) / KC;
+    const int ks = blockIdx.y, KS = gridDim.y;
+    const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
+
+    f32x4 acc[NT][MT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 wcur[NT][NSL], wnext[NT][NSL];
+    auto load_stage = [&](int st, uint4 (&dst)[NT][NSL]) {
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int j = 0; j < NSL; ++j) {
+                const int k = st * KC + j * 32;
+                dst[u][j] = (st < st_end && k + lq * 8 < a.K) ? ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32)) : make_uint4(0, 0, 0, 0);
+            }
+    };
+    constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
+    constexpr int XPT = CHUNKS / NTHR;                // 8 chunks of 16 bytes per lane
+    static_assert(CHUNKS % NTHR == 0, "slice chunks divide evenly over the lanes");
+    uint4 xr[XPT];
+    auto load_x = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int c = threadIdx.x + i * NTHR;
+            const int plane = c / (MT * 16 * (KC / 8));
+            const int rem = c % (MT * 16 * (KC / 8));
+            const int m = rem / (KC / 8), k = st * KC + (rem % (KC / 8)) * 8;
+            const bool ok = st < st_end && m < a.M && k < a.K;
+            const uint4 v = ldg16((plane ? xl : xh) + (ok ? (size_t)m * a.K + k : 0));       // always a valid address
+            xr[i] = ok ? v : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int c = threadIdx.x + i * NTHR;
+            const int plane = c / (MT * 16 * (KC / 8));
+            const int rem = c % (MT * 16 * (KC / 8));
+            *reinterpret_cast<uint4*>(&xs[buf][plane][rem / (KC / 8)][(rem % (KC / 8)) * 8]) = xr[i];
+        }
+    };
+    load_stage(st_begin, wcur);
+    load_x(st_begin);
+    store_x(0);
+    __syncthreads();
+    for (int st = st_begin; st < st_end; ++st) {
+        const int buf = (st - st_begin) & 1;
+        load_stage(st + 1, wnext);
+        load_x(st + 1);
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[buf][0][t * 16 + li][j * 32 + lq * 8]));
+                const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[buf][1][t * 16 + li][j * 32 + lq * 8]));
+#pragma unroll
+                for (int u = 0; u < NT; ++u) {
+                    const bf16x8 A = __builtin_bit_cast(bf16x8, wcur[u][j]);
+                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bh, acc[u][t], 0, 0, 0);
+                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bl, acc[u][t], 0, 0, 0);
+                }
+            }
+        }
+        store_x(buf ^ 1);                             // nobody reads that buffer: its readers passed the last barrier
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+#pragma unroll
+            for (int j = 0; j < NSL; ++j) wcur[u][j] = wnext[u][j];
+    }
+    float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        const int nb = n0 + u * 16 + 4 * lq;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int m = t * 16 + li;
+            if (m >= a.M) continue;
+            float* o = out + (size_t)m * a.ldo + nb;
+            if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
+                *reinterpret_cast<float4*>(o) = make_float4(acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (nb + e < a.N) o[e] = acc[u][t][e];
+            }
         }
     }
 }
@@ -833,11 +992,16 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
     }
 }
 
+// Weight tiles per wavefront of the many-row kernel: two from 97 rows on (halves the LDS reads per weight byte,
+// which is what bounds the kernel there).
+int gemm_row_tiles_nt(int rows) { return rows > 96 ? 2 : 1; }
+
 // Split-K factor: enough workgroups to cover the chip a few times, at least two stages per split.
 int gemm_splits(int dtype, int N, int K, int M) {
     if (dtype != BS_BF16) return 1;
     if (M <= 16) return m16_splits(N, K);
-    const int tiles = (N + 63) / 64;
+    const int nt = gemm_row_tiles_nt(M > GEMM_MAX_ROWS ? GEMM_MAX_ROWS : M);
+    const int tiles = M > 128 ? (N + 255) / 256 : (N + 64 * nt - 1) / (64 * nt);     // more than 128 rows: 256 weight rows per workgroup
     const int stages = (K + 255) / 256;
     int ks = (768 + tiles - 1) / tiles;
     if (ks > stages / 2) ks = stages / 2;
@@ -905,8 +1069,9 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         c.M = (a.M - m0 < GEMM_MAX_ROWS) ? a.M - m0 : GEMM_MAX_ROWS;
         c.x = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m0 * a.K;
         c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
-        const dim3 grid((a.N + 63) / 64, a.KS), block(256);
         const int mt = (c.M + 15) / 16;
+        const int nt = gemm_row_tiles_nt(c.M);                  // weight tiles of 16 rows per wavefront
+        const dim3 grid((a.N + 64 * nt - 1) / (64 * nt), a.KS), block(256);
         const int kper = ((a.K + a.KS - 1) / a.KS + 31) / 32 * 32;      // columns per split, whole k slices
         const bool m16 = a.M <= 16;
         hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -916,25 +1081,22 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
             BS_HIP(hipEventRecord(e0, s));
         }
         // one 16-row weight tile per wavefront measured faster than two (3.7 vs 3.2 TB/s over the 7B layer shapes)
-        if (a.tiled) {
-            if (m16) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, true>), grid, block, 0, s, c, kper);
-            else if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256, true>), grid, block, 0, s, c);
-            else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 256, true>), grid, block, 0, s, c);
-            else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 128, true>), grid, block, 0, s, c);
-            else hipLaunchKernelGGL((gemm_bf16_kernel<6, 128, true>), grid, block, 0, s, c);
-        } else {
-            if (m16) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, false>), grid, block, 0, s, c, kper);
-            else if (mt <= 1) hipLaunchKernelGGL((gemm_bf16_kernel<1, 256, false>), grid, block, 0, s, c);
-            else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 256, false>), grid, block, 0, s, c);
-            else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 128, false>), grid, block, 0, s, c);
-            else hipLaunchKernelGGL((gemm_bf16_kernel<6, 128, false>), grid, block, 0, s, c);
-        }
+#define BS_ROWS(TL) do { \
+            if (m16) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, TL>), grid, block, 0, s, c, kper); \
+            else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, TL>), grid, block, 0, s, c); \
+            else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 1, 128, TL>), grid, block, 0, s, c); \
+            else if (mt <= 6) hipLaunchKernelGGL((gemm_bf16_kernel<6, 1, 128, TL>), grid, block, 0, s, c); \
+            else if (mt <= 8) hipLaunchKernelGGL((gemm_bf16_kernel<8, 2, 64, TL>), grid, block, 0, s, c); \
+            else hipLaunchKernelGGL((gemm_bf16_big_kernel<TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); } while (0)
+        if (a.tiled) BS_ROWS(true);
+        else BS_ROWS(false);
+#undef BS_ROWS
         BS_LAUNCH_CHECK();
         if (g_prof.on) {
             BS_HIP(hipEventRecord(e1, s));
             g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
             g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
-            g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : 6);
+            g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
         }
     }
     return BS_OK;
@@ -1343,7 +1505,7 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
 int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, int kv_base, int B, int q_len,
                 int max_len, int V, int hd, float rope_base, int32_t* pos, int32_t* tok, float2* rope,
                 int32_t* status, hipStream_t s) {
-    hipLaunchKernelGGL(prep_kernel, dim3(B), dim3(128), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
+    hipLaunchKernelGGL(prep_kernel, dim3(B), dim3(q_len > 16 ? 1024 : 128), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
                        hd / 2, rope_base, pos, tok, rope, status);
     BS_LAUNCH_CHECK();
     return BS_OK;

@@ -41,9 +41,11 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     (ODD_BF16, 1, 40, 7, False), (ODD_BF16, 2, 150, 3, True),
     # at most four rows on packed weights: the fused few-row schedule of the draft steps
     (MID, 1, 70, 2, True), (MID_GQA, 2, 130, 1, True), (WIDE, 1, 200, 4, True), (ODD_BF16, 2, 150, 2, True),
-    (MID, 4, 33, 1, True), (WIDE, 1, 1, 1, True)])
+    (MID, 4, 33, 1, True), (WIDE, 1, 1, 1, True),
+    # prompt chunks of 97..128 rows (two weight tiles per wavefront) and of 129..256 rows (double-buffered kernel)
+    (MID, 1, 120, 3, True), (MID_GQA, 3, 40, 2, False), (MID, 1, 250, 3, True), (ODD_BF16, 1, 290, 2, False)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
-    W, m, kv = setup(c, B, 300, seed=3, packed=packed)
+    W, m, kv = setup(c, B, 320, seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
     dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
     last = bs().prefill(m, kv, dtoks, n_prefix, want_logits=True)
