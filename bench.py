@@ -311,6 +311,31 @@ def main():
 
     if not args.pmc_mode:
         stages.update(stage_probes(bs, synth, torch, np, stream))
+        # ---- the whole verification pass at batch 16 with 4096 cached tokens per sequence (the batch workload's shape):
+        #      144 rows per projection, 34 GB of keys and values; cache contents are random bf16 patterns ----
+        with torch.cuda.stream(stream):
+            Bb, ctx, q_len = 16, 4096, 9
+            kvb = bs.KV(target, Bb, ctx + 64)
+            kvb.buf.view(torch.int16).random_(-3000, 3000)
+            qtok = torch.randint(0, tc["vocab"], (Bb, q_len), dtype=torch.int32, device="cuda")
+            kvlb = torch.full((Bb,), ctx, dtype=torch.int32, device="cuda")
+            wsb = torch.empty(target.forward_workspace_bytes(Bb, q_len, ctx + 64), dtype=torch.uint8, device="cuda")
+            lgb = torch.empty(Bb, q_len, tc["vocab"], dtype=torch.float32, device="cuda")
+            ts = []
+            for _ in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                bs.verify_forward(target, kvb, qtok, kvlb, workspace=wsb, logits=lgb)
+                e1.record(stream); e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            ms_b = float(np.median(ts[1:]))
+            kv_bytes_b = 2 * (ctx + q_len) * tc["n_kv_heads"] * tc["head_dim"] * 2 * Bb * tc["n_layers"]
+            nq_b = tc["n_heads"] * tc["head_dim"]
+            wb_b = 2 * (tc["n_layers"] * (tc["d_model"] * 3 * nq_b + nq_b * tc["d_model"] + 3 * tc["d_model"] * tc["d_ff"]) + tc["vocab"] * tc["d_model"])
+            stages["verify_b16_ctx4096"] = {"ms": round(ms_b, 3), "rows": Bb * q_len, "weight_plus_kv_GBps": round((wb_b + kv_bytes_b) / ms_b / 1e6, 1),
+                                            "frac_hbm": round((wb_b + kv_bytes_b) / ms_b / 1e6 / HBM_PEAK_GBS, 4),
+                                            "mfma_issue_frac_of_peak": round(2 * wb_b * Bb * q_len / (ms_b * 1e-3) / 2.5e15, 4)}
+            del kvb, wsb, lgb
     # a plain device copy of known size: the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a --pmc run
     cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
     cal_dst = torch.empty_like(cal_src)

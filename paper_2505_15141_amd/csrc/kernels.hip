@@ -283,6 +283,14 @@ __device__ __forceinline__ const uint16_t* wlane_ptr(const uint16_t* w, int loca
     return w + (size_t)local * K + lq * 8;
 }
 
+// Column offset of a k slice that starts at k, clamped into the row for the lane whose pointer already sits at k-slot lq
+// (tiled: K % 32 == 0, whole slices; row-major: K % 8 == 0, the lane's 8-column chunk must end inside the row).
+template <bool TILED>
+__device__ __forceinline__ int wclamp(int k, int K, int lq) {
+    if (TILED) return min(k, K - 32);
+    return max(min(k, K - 8 - lq * 8), -lq * 8);
+}
+
 // dst (tiled, rows padded to a multiple of 64 with zeros) <- src (row-major [N][K]); one 16-byte chunk per lane.
 __global__ void pack_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int N, int K) {
     const size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -336,8 +344,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
         for (int u = 0; u < NT; ++u)
 #pragma unroll
             for (int j = 0; j < NSL; ++j) {
-                const int k = kb + j * 32;
-                dst[u][j] = (st < st_end && k + lq * 8 < a.K) ? ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32)) : make_uint4(0, 0, 0, 0);
+                // unconditional and clamped (a select on the loaded value would make the wavefront wait for it right here):
+                // columns past K re-read the row's last chunk and meet zero activations, stages past the end are never used
+                const int k = wclamp<TILED>(kb + j * 32, a.K, lq);
+                dst[u][j] = ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32));
             }
     };
     // Activation slice of a stage: 16-byte chunks, rows >= M and columns >= K are zero.  It is requested into registers
@@ -464,58 +474,68 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
         for (int u = 0; u < NT; ++u)
 #pragma unroll
             for (int j = 0; j < NSL; ++j) {
-                const int k = st * KC + j * 32;
-                dst[u][j] = (st < st_end && k + lq * 8 < a.K) ? ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32)) : make_uint4(0, 0, 0, 0);
+                const int k = wclamp<TILED>(st * KC + j * 32, a.K, lq);       // unconditional, clamped: see gemm_bf16_kernel
+                dst[u][j] = ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32));
             }
     };
     constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
     constexpr int XPT = CHUNKS / NTHR;                // 8 chunks of 16 bytes per lane
     static_assert(CHUNKS % NTHR == 0, "slice chunks divide evenly over the lanes");
     uint4 xr[XPT];
-    auto load_x = [&](int st) {
+    auto x_ok = [&](int st, int i, int& plane, int& m, int& kc) {
+        const int c = threadIdx.x + i * NTHR;
+        plane = c / (MT * 16 * (KC / 8));
+        const int rem = c % (MT * 16 * (KC / 8));
+        m = rem / (KC / 8); kc = (rem % (KC / 8)) * 8;
+        return st < st_end && m < a.M && st * KC + kc < a.K;
+    };
+    auto load_x = [&](int st) {                       // raw loads only: nothing here waits for them
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int c = threadIdx.x + i * NTHR;
-            const int plane = c / (MT * 16 * (KC / 8));
-            const int rem = c % (MT * 16 * (KC / 8));
-            const int m = rem / (KC / 8), k = st * KC + (rem % (KC / 8)) * 8;
-            const bool ok = st < st_end && m < a.M && k < a.K;
-            const uint4 v = ldg16((plane ? xl : xh) + (ok ? (size_t)m * a.K + k : 0));       // always a valid address
-            xr[i] = ok ? v : make_uint4(0, 0, 0, 0);
+            int plane, m, kc;
+            const bool ok = x_ok(st, i, plane, m, kc);
+            xr[i] = ldg16((plane ? xl : xh) + (ok ? (size_t)m * a.K + st * KC + kc : 0));    // always a valid address
         }
     };
-    auto store_x = [&](int buf) {
+    auto store_x = [&](int st, int buf) {             // rows >= M, columns >= K and stages past the end become zeros
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
-            const int c = threadIdx.x + i * NTHR;
-            const int plane = c / (MT * 16 * (KC / 8));
-            const int rem = c % (MT * 16 * (KC / 8));
-            *reinterpret_cast<uint4*>(&xs[buf][plane][rem / (KC / 8)][(rem % (KC / 8)) * 8]) = xr[i];
+            int plane, m, kc;
+            const bool ok = x_ok(st, i, plane, m, kc);
+            *reinterpret_cast<uint4*>(&xs[buf][plane][m][kc]) = ok ? xr[i] : make_uint4(0, 0, 0, 0);
         }
     };
     load_stage(st_begin, wcur);
     load_x(st_begin);
-    store_x(0);
+    store_x(st_begin, 0);
     __syncthreads();
     for (int st = st_begin; st < st_end; ++st) {
         const int buf = (st - st_begin) & 1;
         load_stage(st + 1, wnext);
         load_x(st + 1);
+        // B operands (activation tiles) are read from LDS one tile ahead of the MFMAs that use them
+        uint4 bq[2][2];
+        auto lds_b = [&](int idx, int slot) {
+            const int j = idx / MT, t = idx % MT;
+            bq[slot][0] = *reinterpret_cast<const uint4*>(&xs[buf][0][t * 16 + li][j * 32 + lq * 8]);
+            bq[slot][1] = *reinterpret_cast<const uint4*>(&xs[buf][1][t * 16 + li][j * 32 + lq * 8]);
+        };
+        lds_b(0, 0);
 #pragma unroll
-        for (int j = 0; j < NSL; ++j) {
+        for (int idx = 0; idx < NSL * MT; ++idx) {
+            const int j = idx / MT, t = idx % MT, slot = idx & 1;
+            if (idx + 1 < NSL * MT) lds_b(idx + 1, slot ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8 bh = __builtin_bit_cast(bf16x8, bq[slot][0]), bl = __builtin_bit_cast(bf16x8, bq[slot][1]);
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[buf][0][t * 16 + li][j * 32 + lq * 8]));
-                const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&xs[buf][1][t * 16 + li][j * 32 + lq * 8]));
+            for (int u = 0; u < NT; ++u)              // the two MFMAs on one accumulator are kept apart
+                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[u][j]), bh, acc[u][t], 0, 0, 0);
 #pragma unroll
-                for (int u = 0; u < NT; ++u) {
-                    const bf16x8 A = __builtin_bit_cast(bf16x8, wcur[u][j]);
-                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bh, acc[u][t], 0, 0, 0);
-                    acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bl, acc[u][t], 0, 0, 0);
-                }
-            }
+            for (int u = 0; u < NT; ++u)
+                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[u][j]), bl, acc[u][t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        store_x(buf ^ 1);                             // nobody reads that buffer: its readers passed the last barrier
+        store_x(st + 1, buf ^ 1);                     // nobody reads that buffer: its readers passed the last barrier
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < NT; ++u)
