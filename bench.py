@@ -29,8 +29,8 @@ def gpu_weights(c, seed, torch, std=0.02):
 
 
 def cpu_baseline(tc, dc, prefix, gamma, mean_y):
-    """Oracle (fp64 numpy, full recompute) timed on a bounded sample of one round of the same workload: the target's
-    embedding + LM head and a 2-layer slice of it, the whole draft model once, one accept/reject call; the target's
+    """Oracle (fp64 numpy, full recompute) timed on a bounded sample of one round of the same workload: 
+    embedding + LM head and a 12-layer slice of it, the whole draft model once, one accept/reject call; 
     remaining layers are extrapolated linearly in depth (every layer does identical work)."""
     import numpy as np
     from oracle.forward import forward
@@ -43,7 +43,7 @@ def cpu_baseline(tc, dc, prefix, gamma, mean_y):
         cores = os.cpu_count() or 1
     rng = np.random.default_rng(0)
     toks = rng.integers(0, tc["vocab"], prefix + gamma)
-    slice_layers = 2
+    slice_layers = 12
 
     block = synth.to_bf16_grid((rng.standard_normal(1 << 22, dtype=np.float32) * 0.02))
 
