@@ -6,8 +6,8 @@
 // statistics (max, sum of exp): this is the HBM-bound part, about 2 exponentials per logit.  Phase B runs
 // one workgroup per sequence: the gamma acceptance tests u * q(x~) <= p(x~) need only those statistics and
 // two logits each; the first failure fixes the deciding position, and only that row pair is read again
-// (from cache, it was just streamed), kept in registers when the vocabulary fits (V <= 32768), and sampled:
-// from [p - q]_+ if a draft token was rejected, from p at the bonus position otherwise.  The sequential
+// (from cache, it was just streamed) and sampled: from [p - q]_+ if a draft token was rejected, from p at the
+// bonus position otherwise.  (The draft draw of a single short row keeps the row in registers instead.)  The sequential
 // accept chain of the algorithm costs gamma scalar tests; the vocabulary-wide work is parallel.
 //
 // Reductions: per-lane online softmax (max, sum) -> wavefront shuffles -> LDS across 8 wavefronts.
