@@ -437,11 +437,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
 // stages of 64 columns, and the activation slice DOUBLE-buffered in LDS (2 x 72 KiB of the 160 KiB a compute unit
 // has): the next slice travels memory -> registers during the MFMAs of the current one and is written to the other
 // buffer, so a stage costs one barrier and no exposed memory latency.
-constexpr int BIG_MT = 16, BIG_NT = 2, BIG_KC = 64, BIG_WAVES = 8;
+// MT (even, 10..16) is the number of 16-row activation tiles: 144 rows (a batch of 16 sequences being verified)
+// take 10 tiles, not 16, so the matrix cores do not multiply zero rows.
+constexpr int BIG_NT = 2, BIG_KC = 64, BIG_WAVES = 8;
 
-template <bool TILED>
+template <int MT, bool TILED>
 __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs a) {
-    constexpr int MT = BIG_MT, NT = BIG_NT, KC = BIG_KC, NTHR = 64 * BIG_WAVES;
+    constexpr int NT = BIG_NT, KC = BIG_KC, NTHR = 64 * BIG_WAVES;
     constexpr int ROW = KC + 8, NSL = KC / 32;
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][2][MT * 16][ROW];      // [buffer][plane][row][column]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1027,6 +1029,7 @@ int gemm_splits(int dtype, int N, int K, int M) {
     if (ks > stages / 2) ks = stages / 2;
     if (ks > 16) ks = 16;
     if (ks < 1) ks = 1;
+    if (M > 128 && tiles * ks < 256 && 2 * ks <= stages && 2 * ks <= 16) ks *= 2;   // fewer workgroups than compute units
     return ks;
 }
 
@@ -1107,7 +1110,10 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
             else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 1, 128, TL>), grid, block, 0, s, c); \
             else if (mt <= 6) hipLaunchKernelGGL((gemm_bf16_kernel<6, 1, 128, TL>), grid, block, 0, s, c); \
             else if (mt <= 8) hipLaunchKernelGGL((gemm_bf16_kernel<8, 2, 64, TL>), grid, block, 0, s, c); \
-            else hipLaunchKernelGGL((gemm_bf16_big_kernel<TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); } while (0)
+            else if (mt <= 10) hipLaunchKernelGGL((gemm_bf16_big_kernel<10, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
+            else if (mt <= 12) hipLaunchKernelGGL((gemm_bf16_big_kernel<12, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
+            else if (mt <= 14) hipLaunchKernelGGL((gemm_bf16_big_kernel<14, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
+            else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); } while (0)
         if (a.tiled) BS_ROWS(true);
         else BS_ROWS(false);
 #undef BS_ROWS
@@ -1331,11 +1337,14 @@ template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict__ q, const uint16_t* __restrict__ k_cache,
                                                         const uint16_t* __restrict__ v_cache,
                                                         const int32_t* __restrict__ pos, int q_len, int H, int KVH,
-                                                        int cache_len, float scale, float* __restrict__ part) {
+                                                        int cache_len, float scale, float* __restrict__ part, int n_splits) {
     constexpr int DS = HD / 32, DT = HD / 16;
     __shared__ float wm[4][16], wl[4][16];
     __shared__ float wo[4][16][HD + 1];
-    const int split = blockIdx.x, n_splits = gridDim.x, kvh = blockIdx.y, b = blockIdx.z;
+    // blockIdx.x = (group of row tiles, split of the keys): with many query rows (a prompt chunk) the tiles of 16
+    // rows are spread over workgroups and the keys over few splits; with one tile all of gridDim.x are key splits
+    const int split = blockIdx.x % n_splits, rt = blockIdx.x / n_splits, n_rt = gridDim.x / n_splits;
+    const int kvh = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
     const int G = H / KVH, R = G * q_len;
@@ -1351,13 +1360,16 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
         return;
     }
     const int n_keys = pos0 + q_len;
-    const int nblk = (n_keys + 31) / 32;
-    const int per = (nblk + n_splits - 1) / n_splits;
-    const int b_begin = split * per, b_end = min(nblk, b_begin + per);
     const uint16_t* kb = k_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
     const uint16_t* vb = v_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
 
-    for (int r0 = 0; r0 < R; r0 += 16) {
+    for (int r0 = rt * 16; r0 < R; r0 += 16 * n_rt) {
+        // keys any row of this tile may see (causal): up to the tile's latest query position
+        const int r_last = min(r0 + 15, R - 1);
+        const int qi_max = (r0 / q_len == r_last / q_len) ? r_last % q_len : q_len - 1;
+        const int nblk = (pos0 + qi_max + 1 + 31) / 32;
+        const int per = (nblk + n_splits - 1) / n_splits;
+        const int b_begin = split * per, b_end = min(nblk, b_begin + per);
         const int row = r0 + li;
         const bool rvalid = row < R;
         const int g = rvalid ? row / q_len : 0, qi = rvalid ? row % q_len : 0;
@@ -1646,7 +1658,14 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
     const float scale = 1.0f / sqrtf((float)hd);
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
-        const dim3 mgrid(n_splits, KVH, B);
+        // Many query rows per head group (prompt chunks): one workgroup per tile of 16 rows and only as many key splits
+        // as it takes to reach about a thousand workgroups; a single tile keeps all the splits.
+        const int n_rt = (H / KVH * q_len + 15) / 16;
+        if (out && n_rt > 1) {
+            const int want = (1024 + B * KVH * n_rt - 1) / (B * KVH * n_rt);
+            n_splits = want < n_splits ? want : n_splits;
+        }
+        const dim3 mgrid(n_splits * (out ? n_rt : 1), KVH, B);
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (g_prof.on) {
             BS_HIP(hipEventCreate(&e0));
@@ -1655,10 +1674,10 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         }
         if (hd == 128)
             hipLaunchKernelGGL((attn_mfma_kernel<128>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part);
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits);
         else if (hd == 64)
             hipLaunchKernelGGL((attn_mfma_kernel<64>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part);
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits);
         else
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
         BS_LAUNCH_CHECK();
