@@ -430,28 +430,55 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
     }
 }
 
-// ---- GEMM for 129..256 activation rows (prompt processing of one sequence) ----------------------------
+// ---- GEMM for 129..256 activation rows (prompt processing of one sequence, verification of a batch) ----
 // From about 150 rows on the projections are bound by the matrix cores, not by the weight stream (two MFMAs per
-// weight tile and activation tile because of the two planes).  Same operand mapping as above with everything sized
-// for that regime: 8 wavefronts x 2 weight tiles = 256 weight rows per workgroup, 256 activation rows = 16 tiles,
-// stages of 64 columns, and the activation slice DOUBLE-buffered in LDS (2 x 72 KiB of the 160 KiB a compute unit
-// has): the next slice travels memory -> registers during the MFMAs of the current one and is written to the other
-// buffer, so a stage costs one barrier and no exposed memory latency.
-// MT (even, 10..16) is the number of 16-row activation tiles: 144 rows (a batch of 16 sequences being verified)
-// take 10 tiles, not 16, so the matrix cores do not multiply zero rows.
-constexpr int BIG_NT = 2, BIG_KC = 64, BIG_WAVES = 8;
+// weight tile and activation tile because of the two planes), and what then limits a workgroup is how many
+// operand bytes it pulls out of LDS per MFMA and how far ahead its operands are requested.  Sized for that:
+//   * 8 wavefronts as 4 (weight rows) x 2 (activation rows): a wavefront multiplies 64 weight rows (4 tiles, in
+//     registers) with half of the activation tiles, so an activation tile read from LDS feeds 8 MFMAs;
+//   * stages of 32 columns; the activation slice of a stage goes memory -> LDS directly (16 bytes per lane, the
+//     lanes of a wavefront fill one contiguous KB = one 16-row tile of one plane, in the lane order of the MFMA
+//     B operand, so reading it back is one conflict-free 16-byte read per lane) into a ring of 4 buffers, three stages ahead;
+//   * the weight tiles of a stage sit in a register ring of 3 stages.
+// Every load of a stage is issued unconditionally and in the same order by every wavefront, so the wait before a
+// stage is a count: all but the loads of the two stages behind it.  Rows past M re-read row M-1 (their results
+// are not stored), stages past the end re-read the last stage into a buffer nobody reads.
+// MT (even) is the number of 16-row activation tiles: 144 rows (a batch of 16 sequences being verified) take 10
+// tiles, not 16, so the matrix cores do not multiply rows that do not exist.
+constexpr int BIG_WAVES = 8, BIG_STAGES = 4;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// two 16-byte LDS reads at addr + OA and addr + OB (bytes, below 64 KiB); the data is there after lds_wait
+template <int OA, int OB>
+__device__ __forceinline__ void lds_read_pair(u32x4& a, u32x4& b, uint32_t addr) {
+    static_assert(OA >= 0 && OA < 65536 && OB >= 0 && OB < 65536, "16-bit instruction offset");
+    asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4" : "=&v"(a), "=&v"(b) : "v"(addr), "n"(OA), "n"(OB) : "memory");
+}
+__device__ __forceinline__ void lds_wait(u32x4& a, u32x4& b) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b)); }
+
+// s_waitcnt immediate for "at most n vector-memory operations outstanding" (the other counters unconstrained)
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 template <int MT, bool TILED>
 __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs a) {
-    constexpr int NT = BIG_NT, KC = BIG_KC, NTHR = 64 * BIG_WAVES;
-    constexpr int ROW = KC + 8, NSL = KC / 32;
-    __shared__ __attribute__((aligned(16))) uint16_t xs[2][2][MT * 16][ROW];      // [buffer][plane][row][column]
+    static_assert(MT % 2 == 0 && MT >= 2 && MT <= 16, "row tiles split evenly over the two wavefront rows");
+    constexpr int MTW = MT / 2;                       // activation tiles per wavefront
+    constexpr int NF = (2 * MT + BIG_WAVES - 1) / BIG_WAVES;      // 1 KB pieces of a stage each wavefront fetches
+    constexpr int SLOT = NF + 4;                      // vector-memory operations per stage and wavefront
+    static_assert(2 * SLOT < 64, "the wait count has six bits");
+    __shared__ __attribute__((aligned(16))) uint16_t xs[BIG_STAGES][2 * MT][512];     // [buffer][plane * MT + tile][16 rows x 32 columns]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
-    const int n0 = blockIdx.x * (16 * NT * BIG_WAVES) + wave * (16 * NT);
-    const uint16_t* wrow[NT];
+    const int wn = wave & 3, wm = wave >> 2;
+    const int n0 = blockIdx.x * 256 + wn * 64;
+    const uint16_t* wrow[4];
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
+    for (int u = 0; u < 4; ++u) {
         int n = n0 + u * 16 + li;
         if (n >= a.N) n = a.N - 1;
         int seg = 0, local = n;
@@ -459,98 +486,93 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
         wrow[u] = wlane_ptr<TILED>(reinterpret_cast<const uint16_t*>(a.w[seg]), local, a.K, lq);
     }
     const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
-    const uint16_t* xl = xh + a.x_plane;
-    const int nstages = (a.K + KC - 1) / KC;
+    const int nstages = a.K / 32;                     // K % 32 == 0 (host check)
     const int ks = blockIdx.y, KS = gridDim.y;
     const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
-
-    f32x4 acc[NT][MT];
+    const int st_last = max(st_end - 1, st_begin);
+    // this wavefront's pieces of a stage: piece p = plane * MT + tile; lane (row l % 16, k-slot l / 16) fetches the 16
+    // bytes it will later read back as MFMA B operand, and the transfer puts lane l's bytes at offset 16 l of the piece
+    const uint16_t* fsrc[NF];
+    int fpiece[NF];
 #pragma unroll
-    for (int u = 0; u < NT; ++u)
-#pragma unroll
-        for (int t = 0; t < MT; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    uint4 wcur[NT][NSL], wnext[NT][NSL];
-    auto load_stage = [&](int st, uint4 (&dst)[NT][NSL]) {
-#pragma unroll
-        for (int u = 0; u < NT; ++u)
-#pragma unroll
-            for (int j = 0; j < NSL; ++j) {
-                const int k = wclamp<TILED>(st * KC + j * 32, a.K, lq);       // unconditional, clamped: see gemm_bf16_kernel
-                dst[u][j] = ldg16(wrow[u] + (size_t)k * (WSTEP<TILED>::v / 32));
-            }
-    };
-    constexpr int CHUNKS = 2 * MT * 16 * (KC / 8);
-    constexpr int XPT = CHUNKS / NTHR;                // 8 chunks of 16 bytes per lane
-    static_assert(CHUNKS % NTHR == 0, "slice chunks divide evenly over the lanes");
-    uint4 xr[XPT];
-    auto x_ok = [&](int st, int i, int& plane, int& m, int& kc) {
-        const int c = threadIdx.x + i * NTHR;
-        plane = c / (MT * 16 * (KC / 8));
-        const int rem = c % (MT * 16 * (KC / 8));
-        m = rem / (KC / 8); kc = (rem % (KC / 8)) * 8;
-        return st < st_end && m < a.M && st * KC + kc < a.K;
-    };
-    auto load_x = [&](int st) {                       // raw loads only: nothing here waits for them
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            int plane, m, kc;
-            const bool ok = x_ok(st, i, plane, m, kc);
-            xr[i] = ldg16((plane ? xl : xh) + (ok ? (size_t)m * a.K + st * KC + kc : 0));    // always a valid address
-        }
-    };
-    auto store_x = [&](int st, int buf) {             // rows >= M, columns >= K and stages past the end become zeros
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            int plane, m, kc;
-            const bool ok = x_ok(st, i, plane, m, kc);
-            *reinterpret_cast<uint4*>(&xs[buf][plane][m][kc]) = ok ? xr[i] : make_uint4(0, 0, 0, 0);
-        }
-    };
-    load_stage(st_begin, wcur);
-    load_x(st_begin);
-    store_x(st_begin, 0);
-    __syncthreads();
-    for (int st = st_begin; st < st_end; ++st) {
-        const int buf = (st - st_begin) & 1;
-        load_stage(st + 1, wnext);
-        load_x(st + 1);
-        // B operands (activation tiles) are read from LDS one tile ahead of the MFMAs that use them
-        uint4 bq[2][2];
-        auto lds_b = [&](int idx, int slot) {
-            const int j = idx / MT, t = idx % MT;
-            bq[slot][0] = *reinterpret_cast<const uint4*>(&xs[buf][0][t * 16 + li][j * 32 + lq * 8]);
-            bq[slot][1] = *reinterpret_cast<const uint4*>(&xs[buf][1][t * 16 + li][j * 32 + lq * 8]);
-        };
-        lds_b(0, 0);
-#pragma unroll
-        for (int idx = 0; idx < NSL * MT; ++idx) {
-            const int j = idx / MT, t = idx % MT, slot = idx & 1;
-            if (idx + 1 < NSL * MT) lds_b(idx + 1, slot ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-            const bf16x8 bh = __builtin_bit_cast(bf16x8, bq[slot][0]), bl = __builtin_bit_cast(bf16x8, bq[slot][1]);
-#pragma unroll
-            for (int u = 0; u < NT; ++u)              // the two MFMAs on one accumulator are kept apart
-                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[u][j]), bh, acc[u][t], 0, 0, 0);
-#pragma unroll
-            for (int u = 0; u < NT; ++u)
-                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wcur[u][j]), bl, acc[u][t], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        store_x(st + 1, buf ^ 1);                     // nobody reads that buffer: its readers passed the last barrier
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < NT; ++u)
-#pragma unroll
-            for (int j = 0; j < NSL; ++j) wcur[u][j] = wnext[u][j];
+    for (int f = 0; f < NF; ++f) {
+        const int p = min(wave + BIG_WAVES * f, 2 * MT - 1);      // a surplus fetch repeats the last piece (same bytes)
+        const int plane = p / MT, tile = p - plane * MT;
+        fpiece[f] = p;
+        fsrc[f] = xh + (size_t)plane * a.x_plane + (size_t)min(tile * 16 + li, a.M - 1) * a.K + lq * 8;
     }
+    auto fill = [&](int st, int buf) {
+        const int s = min(st, st_last);
+#pragma unroll
+        for (int f = 0; f < NF; ++f)
+            __builtin_amdgcn_global_load_lds((global_void_ptr)(fsrc[f] + (size_t)s * 32), (lds_void_ptr)&xs[buf][fpiece[f]][0], 16, 0, 0);
+    };
+    auto wload = [&](int st, uint4 (&dst)[4]) {
+        const int s = min(st, st_last);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dst[u] = ldg16(wrow[u] + (size_t)s * WSTEP<TILED>::v);
+    };
+    f32x4 acc[4][MTW];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) acc[u][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 w0[4], w1[4], w2[4];
+    fill(st_begin, 0);     wload(st_begin, w0);
+    fill(st_begin + 1, 1); wload(st_begin + 1, w1);
+    fill(st_begin + 2, 2); wload(st_begin + 2, w2);
+    auto step = [&](int st, uint4 (&w)[4], bool prefetch) {
+        // This stage's pieces and weights have landed; then a bare barrier (everybody's have, and everybody has read
+        // stage st-1: its LDS reads were waited for before its MFMAs).  __syncthreads() would add a release fence,
+        // which has to wait for ALL transfers into LDS, the prefetched stages included.
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * SLOT));
+        __builtin_amdgcn_s_barrier();
+        const int buf = (st - st_begin) & (BIG_STAGES - 1);
+        if (prefetch) fill(st + 3, (buf + 3) & (BIG_STAGES - 1));  // into the buffer of stage st-1
+        // The activation tiles are read with explicit LDS instructions and explicit waits: an LDS load the compiler
+        // knows about would be made to wait for EVERY transfer into LDS still in flight (it cannot tell the buffers
+        // apart), which is the prefetch of the next three stages.
+        const uint32_t bh = lds_addr(&xs[buf][wm * MTW][lane * 8]);      // plane 0; plane 1 is MT KB further
+        u32x4 bq[2][2];
+        lds_read_pair<0, MT * 1024>(bq[0][0], bq[0][1], bh);
+#pragma unroll
+        for (int t = 0; t < MTW; ++t) {
+            const int slot = t & 1;
+            lds_wait(bq[slot][0], bq[slot][1]);
+            if (t + 1 < MTW)                                       // the next tile is read while this one multiplies
+                lds_read_pair<0, MT * 1024>(bq[slot ^ 1][0], bq[slot ^ 1][1], bh + (t + 1) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf16x8 Bh = __builtin_bit_cast(bf16x8, bq[slot][0]), Bl = __builtin_bit_cast(bf16x8, bq[slot][1]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)                            // the two MFMAs on one accumulator are kept apart
+                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), Bh, acc[u][t], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), Bl, acc[u][t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (prefetch) wload(st + 3, w);
+    };
+    // Whole groups of three stages run without a branch, so that the compiler can count the loads in flight; the
+    // one or two stages left over request nothing any more.
+    int st = st_begin;
+    for (; st + 3 <= st_end; st += 3) {
+        step(st, w0, true);
+        step(st + 1, w1, true);
+        step(st + 2, w2, true);
+    }
+    if (st < st_end) {
+        step(st, w0, false);
+        if (st + 1 < st_end) step(st + 1, w1, false);
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // no transfer into LDS is left in flight at the end
     float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride;
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const int nb = n0 + u * 16 + 4 * lq;
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            const int m = t * 16 + li;
+        for (int t = 0; t < MTW; ++t) {
+            const int m = (wm * MTW + t) * 16 + li;
             if (m >= a.M) continue;
             float* o = out + (size_t)m * a.ldo + nb;
             if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
@@ -1022,14 +1044,22 @@ int gemm_row_tiles_nt(int rows) { return rows > 96 ? 2 : 1; }
 int gemm_splits(int dtype, int N, int K, int M) {
     if (dtype != BS_BF16) return 1;
     if (M <= 16) return m16_splits(N, K);
-    const int nt = gemm_row_tiles_nt(M > GEMM_MAX_ROWS ? GEMM_MAX_ROWS : M);
-    const int tiles = M > 128 ? (N + 255) / 256 : (N + 64 * nt - 1) / (64 * nt);     // more than 128 rows: 256 weight rows per workgroup
     const int stages = (K + 255) / 256;
+    if (M > 128) {
+        // 256 weight rows per workgroup, one workgroup per compute unit: as many splits as fill the chip once and no
+        // more -- at these row counts every further split writes and re-reads megabytes of partial sums
+        const int tiles = (N + 255) / 256;
+        int ks = 256 / tiles;
+        if (ks > stages) ks = stages;
+        if (ks > 16) ks = 16;
+        return ks < 1 ? 1 : ks;
+    }
+    const int nt = gemm_row_tiles_nt(M);
+    const int tiles = (N + 64 * nt - 1) / (64 * nt);
     int ks = (768 + tiles - 1) / tiles;
     if (ks > stages / 2) ks = stages / 2;
     if (ks > 16) ks = 16;
     if (ks < 1) ks = 1;
-    if (M > 128 && tiles * ks < 256 && 2 * ks <= stages && 2 * ks <= 16) ks *= 2;   // fewer workgroups than compute units
     return ks;
 }
 
@@ -1087,9 +1117,10 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         return BS_OK;
     }
     // bf16: at most GEMM_MAX_ROWS rows per launch (accumulators live in registers, the slice in LDS)
-    for (int m0 = 0; m0 < a.M; m0 += GEMM_MAX_ROWS) {
+    const int max_rows = a.K % 32 == 0 ? GEMM_MAX_ROWS : 128;       // the 256-row kernel works in whole 32-column stages
+    for (int m0 = 0; m0 < a.M; m0 += max_rows) {
         GemmArgs c = a;
-        c.M = (a.M - m0 < GEMM_MAX_ROWS) ? a.M - m0 : GEMM_MAX_ROWS;
+        c.M = (a.M - m0 < max_rows) ? a.M - m0 : max_rows;
         c.x = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m0 * a.K;
         c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
         const int mt = (c.M + 15) / 16;
