@@ -276,7 +276,7 @@ def prefill(model, kv, tokens, n, want_logits=False, workspace=None, stream=None
     B, stride = tokens.shape
     dev = tokens.device
     if workspace is None:
-        workspace = torch.empty(model.forward_workspace_bytes(B, min(n, 256 if B == 1 else 128), kv.max_len), dtype=torch.uint8,
+        workspace = torch.empty(model.forward_workspace_bytes(B, min(n, 1024 if B == 1 else 128), kv.max_len), dtype=torch.uint8,
                                 device=dev)
     logits = torch.empty(B, model.c["vocab"], dtype=torch.float32, device=dev) if want_logits else None
     check(lib.bs_prefill(model.h, kv.h, ptr(tokens), stride, n, ptr(logits), ptr(workspace), workspace.numel(),

@@ -437,8 +437,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
 //   * 8 wavefronts as 4 (weight rows) x 2 (activation rows): a wavefront multiplies 64 weight rows (4 tiles, in
 //     registers) with half of the activation tiles, so an activation tile read from LDS feeds 8 MFMAs;
 //   * stages of 32 columns; the activation slice of a stage goes memory -> LDS directly (16 bytes per lane, the
-//     lanes of a wavefront fill one contiguous KB = one 16-row tile of one plane, in the lane order of the MFMA
-//     B operand, so reading it back is one conflict-free 16-byte read per lane) into a ring of 4 buffers, three stages ahead;
+//     lanes of a wavefront fill one contiguous KB = one 16-row tile of one plane, chunks placed so that reading
+//     the MFMA B operand back is one conflict-free 16-byte read per lane) into a ring of 4 buffers, three stages ahead;
 //   * the weight tiles of a stage sit in a register ring of 3 stages.
 // Every load of a stage is issued unconditionally and in the same order by every wavefront, so the wait before a
 // stage is a count: all but the loads of the two stages behind it.  Rows past M re-read row M-1 (their results
@@ -475,7 +475,15 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
     const int wn = wave & 3, wm = wave >> 2;
-    const int n0 = blockIdx.x * 256 + wn * 64;
+    // blockIdx.x enumerates (tile of 256 weight rows, block of 256 activation rows): the blocks of one weight tile sit 8
+    // workgroups apart, i.e. on the same die (workgroups go round the 8 dies) and in flight together, so that the tile is
+    // fetched from memory once and found in that die's L2 by the others
+    const int n_mb = (a.M + 255) / 256, n_tiles = (a.N + 255) / 256;
+    const int grp = blockIdx.x / (8 * n_mb), rem = blockIdx.x - grp * (8 * n_mb);
+    const int tile = grp * 8 + (rem & 7), m_off = (rem >> 3) * 256;
+    if (tile >= n_tiles) return;                                   // the grid is padded to whole groups of 8 tiles
+    const int M = min(a.M - m_off, 256);
+    const int n0 = tile * 256 + wn * 64;
     const uint16_t* wrow[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -485,21 +493,24 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
         if (local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
         wrow[u] = wlane_ptr<TILED>(reinterpret_cast<const uint16_t*>(a.w[seg]), local, a.K, lq);
     }
-    const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x);
+    const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m_off * a.K;
     const int nstages = a.K / 32;                     // K % 32 == 0 (host check)
     const int ks = blockIdx.y, KS = gridDim.y;
     const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
     const int st_last = max(st_end - 1, st_begin);
-    // this wavefront's pieces of a stage: piece p = plane * MT + tile; lane (row l % 16, k-slot l / 16) fetches the 16
-    // bytes it will later read back as MFMA B operand, and the transfer puts lane l's bytes at offset 16 l of the piece
+    // this wavefront's pieces of a stage: piece p = plane * MT + tile.  The transfer puts lane l's 16 bytes at offset
+    // 16 l of the piece.  Four consecutive lanes fetch the four 16-byte chunks of one row (one 64-byte run: the
+    // address unit works on such lane quads), rotated by row / 2, so that row r's chunk c sits at slot
+    // 4 r + ((c + r / 2) & 3): LDS serves 8 lanes x 16 bytes per cycle, and the 8 lanes that read one k-slot of 8
+    // consecutive rows then hit 8 different 16-byte bank groups (measured: no conflicts; rotating by row / 4 gave 2-way).
     const uint16_t* fsrc[NF];
     int fpiece[NF];
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
         const int p = min(wave + BIG_WAVES * f, 2 * MT - 1);      // a surplus fetch repeats the last piece (same bytes)
-        const int plane = p / MT, tile = p - plane * MT;
+        const int plane = p / MT, rt = p - plane * MT;
         fpiece[f] = p;
-        fsrc[f] = xh + (size_t)plane * a.x_plane + (size_t)min(tile * 16 + li, a.M - 1) * a.K + lq * 8;
+        fsrc[f] = xh + (size_t)plane * a.x_plane + (size_t)min(rt * 16 + (lane >> 2), M - 1) * a.K + (((lane & 3) - (lane >> 3)) & 3) * 8;
     }
     auto fill = [&](int st, int buf) {
         const int s = min(st, st_last);
@@ -521,26 +532,32 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
     fill(st_begin, 0);     wload(st_begin, w0);
     fill(st_begin + 1, 1); wload(st_begin + 1, w1);
     fill(st_begin + 2, 2); wload(st_begin + 2, w2);
-    auto step = [&](int st, uint4 (&w)[4], bool prefetch) {
-        // This stage's pieces and weights have landed; then a bare barrier (everybody's have, and everybody has read
-        // stage st-1: its LDS reads were waited for before its MFMAs).  __syncthreads() would add a release fence,
-        // which has to wait for ALL transfers into LDS, the prefetched stages included.
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * SLOT));
+    // "Everything but the newest stage has landed", then a bare barrier: for every wavefront's pieces, and every
+    // wavefront is done reading the stage before.  __syncthreads() would add a release fence, which has to wait for ALL
+    // transfers into LDS, the prefetched stages included.
+    auto landed = [&]() {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(SLOT));
         __builtin_amdgcn_s_barrier();
+    };
+    // The activation tiles are read with explicit LDS instructions and explicit waits: an LDS load the compiler knows
+    // about would be made to wait for EVERY transfer into LDS still in flight (it cannot tell the buffers apart).
+    u32x4 bq[2][2];
+    landed();                                                      // stages st_begin and st_begin + 1
+    const int bslot = 4 * li + ((lq + (li >> 1)) & 3);              // where this lane's B operand (row li, k-slot lq) sits in a piece
+    lds_read_pair<0, MT * 1024>(bq[0][0], bq[0][1], lds_addr(&xs[0][wm * MTW][bslot * 8]));
+    // One stage.  On entry its first tile is already on its way into bq[0], and the next stage has landed as well, so
+    // that stage's first tile is requested before this stage's last MFMAs: no LDS latency is exposed at the barrier.
+    // The pieces of stage st+3 (into the buffer of stage st-1, which everybody has left) are requested between the MFMA groups.
+    auto step = [&](int st, uint4 (&w)[4], bool prefetch) {
         const int buf = (st - st_begin) & (BIG_STAGES - 1);
-        if (prefetch) fill(st + 3, (buf + 3) & (BIG_STAGES - 1));  // into the buffer of stage st-1
-        // The activation tiles are read with explicit LDS instructions and explicit waits: an LDS load the compiler
-        // knows about would be made to wait for EVERY transfer into LDS still in flight (it cannot tell the buffers
-        // apart), which is the prefetch of the next three stages.
-        const uint32_t bh = lds_addr(&xs[buf][wm * MTW][lane * 8]);      // plane 0; plane 1 is MT KB further
-        u32x4 bq[2][2];
-        lds_read_pair<0, MT * 1024>(bq[0][0], bq[0][1], bh);
+        const uint32_t bh = lds_addr(&xs[buf][wm * MTW][bslot * 8]);                         // plane 0; plane 1 is MT KB further
+        const uint32_t bh_next = lds_addr(&xs[(buf + 1) & (BIG_STAGES - 1)][wm * MTW][bslot * 8]);
+        const int s3 = min(st + 3, st_last), buf3 = (buf + 3) & (BIG_STAGES - 1);
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
             const int slot = t & 1;
             lds_wait(bq[slot][0], bq[slot][1]);
-            if (t + 1 < MTW)                                       // the next tile is read while this one multiplies
-                lds_read_pair<0, MT * 1024>(bq[slot ^ 1][0], bq[slot ^ 1][1], bh + (t + 1) * 1024);
+            lds_read_pair<0, MT * 1024>(bq[slot ^ 1][0], bq[slot ^ 1][1], t + 1 < MTW ? bh + (t + 1) * 1024 : bh_next);
             __builtin_amdgcn_sched_barrier(0);
             const bf16x8 Bh = __builtin_bit_cast(bf16x8, bq[slot][0]), Bl = __builtin_bit_cast(bf16x8, bq[slot][1]);
 #pragma unroll
@@ -550,8 +567,16 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
             for (int u = 0; u < 4; ++u)
                 acc[u][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), Bl, acc[u][t], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+            if (prefetch && t < NF)
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(fsrc[t] + (size_t)s3 * 32), (lds_void_ptr)&xs[buf3][fpiece[t]][0], 16, 0, 0);
         }
+        static_assert(NF <= MTW, "one piece per MFMA group");
         if (prefetch) wload(st + 3, w);
+        if (MTW & 1) {                                             // the next stage's first tile went to bq[1]: it is expected in bq[0]
+            lds_wait(bq[1][0], bq[1][1]);
+            bq[0][0] = bq[1][0]; bq[0][1] = bq[1][1];
+        }
+        landed();                                                  // stage st+2; and everybody is done with stage st
     };
     // Whole groups of three stages run without a branch, so that the compiler can count the loads in flight; the
     // one or two stages left over request nothing any more.
@@ -565,15 +590,20 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
         step(st, w0, false);
         if (st + 1 < st_end) step(st + 1, w1, false);
     }
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // no transfer into LDS is left in flight at the end
-    float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride;
+    lds_wait(bq[0][0], bq[0][1]);                                  // the read ahead of the last stage is not used
+    lds_wait(bq[1][0], bq[1][1]);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));                      // no transfer into LDS is left in flight
+    // Stored straight from the registers (a lane holds D[column 16u + 4 lq + e][row 16t + li]).  Routing the block through
+    // LDS to write whole 256-byte rows was measured and changed nothing: what the output costs is its size -- every
+    // split writes M x 256 floats per workgroup and the launch ends when they are in memory (7 us for 4 MB, 14 us for 64 MB).
+    float* out = reinterpret_cast<float*>(a.out) + (size_t)ks * a.ks_stride + (size_t)m_off * a.ldo;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int nb = n0 + u * 16 + 4 * lq;
 #pragma unroll
         for (int t = 0; t < MTW; ++t) {
             const int m = (wm * MTW + t) * 16 + li;
-            if (m >= a.M) continue;
+            if (m >= M) continue;
             float* o = out + (size_t)m * a.ldo + nb;
             if (nb + 3 < a.N && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {
                 *reinterpret_cast<float4*>(o) = make_float4(acc[u][t][0], acc[u][t][1], acc[u][t][2], acc[u][t][3]);
@@ -1048,8 +1078,18 @@ int gemm_splits(int dtype, int N, int K, int M) {
     if (M > 128) {
         // 256 weight rows per workgroup, one workgroup per compute unit: as many splits as fill the chip once and no
         // more -- at these row counts every further split writes and re-reads megabytes of partial sums
-        const int tiles = (N + 255) / 256;
+        const int tiles = (N + 255) / 256 * ((M + 255) / 256);       // blocks of 256 rows share a launch
         int ks = 256 / tiles;
+        if (ks < 1) {
+            // more tiles than compute units: splitting can still even out the last, partly filled round of workgroups
+            // (344 tiles: two rounds unsplit, three half-length rounds in two splits; measured 306 -> 262 us)
+            ks = 1;
+            double best = 1e30;
+            for (int c = 1; c <= 4; ++c) {
+                const double cost = (double)((tiles * c + 255) / 256) / c + 0.04 * (c - 1);
+                if (cost < best) { best = cost; ks = c; }
+            }
+        }
         if (ks > stages) ks = stages;
         if (ks > 16) ks = 16;
         return ks < 1 ? 1 : ks;
@@ -1117,7 +1157,29 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         return BS_OK;
     }
     // bf16: at most GEMM_MAX_ROWS rows per launch (accumulators live in registers, the slice in LDS)
-    const int max_rows = a.K % 32 == 0 ? GEMM_MAX_ROWS : 128;       // the 256-row kernel works in whole 32-column stages
+    const bool big_ok = a.K % 32 == 0;                              // the 256-row kernel works in whole 32-column stages
+    if (big_ok && a.M > GEMM_MAX_ROWS) {
+        // several blocks of 256 rows in one launch: more workgroups per weight tile instead of more splits of K
+        const int n_mb = (a.M + 255) / 256, groups = ((a.N + 255) / 256 + 7) / 8;
+        const dim3 grid(groups * 8 * n_mb, a.KS), block(64 * BIG_WAVES);
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (g_prof.on) {
+            BS_HIP(hipEventCreate(&e0));
+            BS_HIP(hipEventCreate(&e1));
+            BS_HIP(hipEventRecord(e0, s));
+        }
+        if (a.tiled) hipLaunchKernelGGL((gemm_bf16_big_kernel<16, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, false>), grid, block, 0, s, a);
+        BS_LAUNCH_CHECK();
+        if (g_prof.on) {
+            BS_HIP(hipEventRecord(e1, s));
+            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+            g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
+            g_prof.mt.push_back(16);
+        }
+        return BS_OK;
+    }
+    const int max_rows = big_ok ? GEMM_MAX_ROWS : 128;
     for (int m0 = 0; m0 < a.M; m0 += max_rows) {
         GemmArgs c = a;
         c.M = (a.M - m0 < max_rows) ? a.M - m0 : max_rows;
@@ -1128,6 +1190,7 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         const dim3 grid((a.N + 64 * nt - 1) / (64 * nt), a.KS), block(256);
         const int kper = ((a.K + a.KS - 1) / a.KS + 31) / 32 * 32;      // columns per split, whole k slices
         const bool m16 = a.M <= 16;
+        const dim3 big_grid(((a.N + 255) / 256 + 7) / 8 * 8, a.KS);     // one block of rows: whole groups of 8 weight tiles
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (g_prof.on) {
             BS_HIP(hipEventCreate(&e0));
@@ -1141,10 +1204,10 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
             else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 1, 128, TL>), grid, block, 0, s, c); \
             else if (mt <= 6) hipLaunchKernelGGL((gemm_bf16_kernel<6, 1, 128, TL>), grid, block, 0, s, c); \
             else if (mt <= 8) hipLaunchKernelGGL((gemm_bf16_kernel<8, 2, 64, TL>), grid, block, 0, s, c); \
-            else if (mt <= 10) hipLaunchKernelGGL((gemm_bf16_big_kernel<10, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
-            else if (mt <= 12) hipLaunchKernelGGL((gemm_bf16_big_kernel<12, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
-            else if (mt <= 14) hipLaunchKernelGGL((gemm_bf16_big_kernel<14, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); \
-            else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, TL>), dim3((a.N + 255) / 256, a.KS), dim3(64 * BIG_WAVES), 0, s, c); } while (0)
+            else if (mt <= 10) hipLaunchKernelGGL((gemm_bf16_big_kernel<10, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
+            else if (mt <= 12) hipLaunchKernelGGL((gemm_bf16_big_kernel<12, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
+            else if (mt <= 14) hipLaunchKernelGGL((gemm_bf16_big_kernel<14, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
+            else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); } while (0)
         if (a.tiled) BS_ROWS(true);
         else BS_ROWS(false);
 #undef BS_ROWS

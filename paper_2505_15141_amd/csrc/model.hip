@@ -350,9 +350,10 @@ extern "C" __attribute__((visibility("default"))) int bs_prefill(const bs_model*
     if (rc != BS_OK) return rc;
     BS_REQUIRE(dev_tokens && ws, BS_EINVAL, "bs_prefill: NULL pointer");
     BS_REQUIRE(n >= 1 && n <= token_stride && n <= kv->max_len, BS_ESHAPE, "bs_prefill: n=%d, stride=%d, max_len=%d", n, token_stride, kv->max_len);
-    // largest chunk the workspace allows: at most 128 query rows per sequence, 256 for a single sequence (one GEMM
-    // launch takes up to 256 rows, and from about 150 rows on the projections are bound by the matrix cores)
-    const int cap = kv->B == 1 ? 256 : 128;
+    // largest chunk the workspace allows: at most 128 query rows per sequence, 1024 for a single sequence (blocks of
+    // 256 rows share a GEMM launch: more rows mean more workgroups per weight tile, fewer splits of K, and so fewer
+    // partial sums written and re-read per multiply)
+    const int cap = kv->B == 1 ? 1024 : 128;
     int chunk = n < cap ? n : cap;
     while (chunk > 1 && bs_forward_workspace_bytes(&m->cfg, kv->B, chunk, kv->max_len) > ws_bytes) chunk /= 2;
     BS_REQUIRE(bs_forward_workspace_bytes(&m->cfg, kv->B, chunk, kv->max_len) <= ws_bytes, BS_EWORKSPACE,

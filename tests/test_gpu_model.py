@@ -45,9 +45,11 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     # prompt chunks of 97..128 rows (two weight tiles per wavefront) and of 129..256 rows (double-buffered kernel)
     (MID, 1, 120, 3, True), (MID_GQA, 3, 40, 2, False), (MID, 1, 250, 3, True), (ODD_BF16, 1, 290, 2, False),
     # 129..224 rows: the double-buffered kernel with 10, 12 and 14 row tiles; several 16-row attention tiles per head
-    (MID, 1, 150, 3, True), (ODD_BF16, 1, 185, 2, False), (MID_GQA, 1, 215, 2, True)])
+    (MID, 1, 150, 3, True), (ODD_BF16, 1, 185, 2, False), (MID_GQA, 1, 215, 2, True),
+    # more than 256 rows: several blocks of 256 rows in one GEMM launch (ragged last block), attention over many row tiles
+    (MID, 1, 700, 3, True), (MID_GQA, 4, 128, 2, False), (ODD_BF16, 1, 300, 2, True)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
-    W, m, kv = setup(c, B, 320, seed=3, packed=packed)
+    W, m, kv = setup(c, B, max(320, n_prefix + q_len + 8), seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
     dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
     last = bs().prefill(m, kv, dtoks, n_prefix, want_logits=True)
