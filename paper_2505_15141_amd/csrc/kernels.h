@@ -4,8 +4,7 @@
 
 namespace bs {
 
-constexpr int GEMM_MAX_ROWS = 256;  // rows of x one bf16 GEMM launch keeps in MFMA accumulators
-int gemm_row_tiles_nt(int rows);
+constexpr int GEMM_MAX_ROWS = 256;  // rows of x one workgroup of the many-row GEMM keeps in MFMA accumulators
 
 struct GemmArgs {
     const void* x;        // activations [M, K]: float, or bf16 hi plane (lo plane x_plane elements further)

@@ -267,7 +267,9 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_
 // slice [M, KC] of both planes is staged once per workgroup in LDS (rows padded by 16 bytes so that the
 // 16 rows read by one ds_read_b128 phase fall into distinct banks) and shared by the four wavefronts.
 // Each wavefront owns its output rows, so no cross-wavefront reduction is needed; split-K partials are
-// summed by the consumer kernel.
+// summed by the consumer kernel.  Three kernels by row count: gemm_bf16_m16_kernel (up to 16 rows, the
+// verification pass of one sequence: pure weight streaming), this one with two row tiles (17..32 rows, and the
+// fallback when K is not a multiple of 32), gemm_bf16_big_kernel from 33 rows on (measured faster from there).
 __device__ __forceinline__ uint4 ldg16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // Weight layouts.  Row-major [N][K], or TILED: the matrix is cut into 64-row x 32-column blocks stored
@@ -430,10 +432,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
     }
 }
 
-// ---- GEMM for 129..256 activation rows (prompt processing of one sequence, verification of a batch) ----
+// ---- GEMM for 33 activation rows and more (prompt processing, verification of a batch) -----------------
 // From about 150 rows on the projections are bound by the matrix cores, not by the weight stream (two MFMAs per
 // weight tile and activation tile because of the two planes), and what then limits a workgroup is how many
-// operand bytes it pulls out of LDS per MFMA and how far ahead its operands are requested.  Sized for that:
+// operand bytes it pulls out of LDS per MFMA and how far ahead its operands are requested.  Sized for that
+// (and, with fewer row tiles, still ahead of the kernel above from 33 rows on: 140 against 195 us for the four
+// projections of a 7B layer at 80 rows):
 //   * 8 wavefronts as 4 (weight rows) x 2 (activation rows): a wavefront multiplies 64 weight rows (4 tiles, in
 //     registers) with half of the activation tiles, so an activation tile read from LDS feeds 8 MFMAs;
 //   * stages of 32 columns; the activation slice of a stage goes memory -> LDS directly (16 bytes per lane, the
@@ -441,7 +445,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a) {
 //     the MFMA B operand back is one conflict-free 16-byte read per lane) into a ring of 4 buffers, three stages ahead;
 //   * the weight tiles of a stage sit in a register ring of 3 stages.
 // Every load of a stage is issued unconditionally and in the same order by every wavefront, so the wait before a
-// stage is a count: all but the loads of the two stages behind it.  Rows past M re-read row M-1 (their results
+// stage is a count: all but the loads of the newest stage (a stage is waited for one stage early, so that its first
+// tile can be read from LDS before the barrier).  Rows past M re-read row M-1 (their results
 // are not stored), stages past the end re-read the last stage into a buffer nobody reads.
 // MT (even) is the number of 16-row activation tiles: 144 rows (a batch of 16 sequences being verified) take 10
 // tiles, not 16, so the matrix cores do not multiply rows that do not exist.
@@ -1068,16 +1073,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs a) {
 
 // Weight tiles per wavefront of the many-row kernel: two from 97 rows on (halves the LDS reads per weight byte,
 // which is what bounds the kernel there).
-int gemm_row_tiles_nt(int rows) { return rows > 96 ? 2 : 1; }
-
-// Split-K factor: enough workgroups to cover the chip a few times, at least two stages per split.
 int gemm_splits(int dtype, int N, int K, int M) {
     if (dtype != BS_BF16) return 1;
     if (M <= 16) return m16_splits(N, K);
     const int stages = (K + 255) / 256;
-    if (M > 128) {
+    if (M > 32 && K % 32 == 0) {
         // 256 weight rows per workgroup, one workgroup per compute unit: as many splits as fill the chip once and no
-        // more -- at these row counts every further split writes and re-reads megabytes of partial sums
+        // more -- every further split writes and re-reads megabytes of partial sums
         const int tiles = (N + 255) / 256 * ((M + 255) / 256);       // blocks of 256 rows share a launch
         int ks = 256 / tiles;
         if (ks < 1) {
@@ -1094,8 +1096,7 @@ int gemm_splits(int dtype, int N, int K, int M) {
         if (ks > 16) ks = 16;
         return ks < 1 ? 1 : ks;
     }
-    const int nt = gemm_row_tiles_nt(M);
-    const int tiles = (N + 64 * nt - 1) / (64 * nt);
+    const int tiles = (N + 63) / 64;
     int ks = (768 + tiles - 1) / tiles;
     if (ks > stages / 2) ks = stages / 2;
     if (ks > 16) ks = 16;
@@ -1156,68 +1157,64 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         BS_LAUNCH_CHECK();
         return BS_OK;
     }
-    // bf16: at most GEMM_MAX_ROWS rows per launch (accumulators live in registers, the slice in LDS)
-    const bool big_ok = a.K % 32 == 0;                              // the 256-row kernel works in whole 32-column stages
-    if (big_ok && a.M > GEMM_MAX_ROWS) {
-        // several blocks of 256 rows in one launch: more workgroups per weight tile instead of more splits of K
-        const int n_mb = (a.M + 255) / 256, groups = ((a.N + 255) / 256 + 7) / 8;
-        const dim3 grid(groups * 8 * n_mb, a.KS), block(64 * BIG_WAVES);
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        if (g_prof.on) {
-            BS_HIP(hipEventCreate(&e0));
-            BS_HIP(hipEventCreate(&e1));
-            BS_HIP(hipEventRecord(e0, s));
-        }
-        if (a.tiled) hipLaunchKernelGGL((gemm_bf16_big_kernel<16, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, false>), grid, block, 0, s, a);
-        BS_LAUNCH_CHECK();
-        if (g_prof.on) {
-            BS_HIP(hipEventRecord(e1, s));
-            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
-            g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
-            g_prof.mt.push_back(16);
-        }
+    const bool big_ok = a.K % 32 == 0;                              // the many-row kernel works in whole 32-column stages
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto prof_begin = [&]() -> int {
+        if (!g_prof.on) return BS_OK;
+        BS_HIP(hipEventCreate(&e0));
+        BS_HIP(hipEventCreate(&e1));
+        BS_HIP(hipEventRecord(e0, s));
         return BS_OK;
+    };
+    auto prof_end = [&](int mt) -> int {                            // classes by 16-row tiles: 1, 2, 4, 6, 8, 16
+        if (!g_prof.on) return BS_OK;
+        BS_HIP(hipEventRecord(e1, s));
+        g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+        g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
+        g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
+        return BS_OK;
+    };
+    int rc;
+    if (big_ok && a.M > 32) {
+        // 33 rows and more: one launch; beyond 256 rows several blocks of 256 rows share it (more workgroups per
+        // weight tile instead of more splits of K)
+        const int mt = a.M > GEMM_MAX_ROWS ? 16 : (a.M + 15) / 16;
+        const int n_mb = (a.M + 255) / 256, groups = ((a.N + 255) / 256 + 7) / 8;      // whole groups of 8 weight tiles
+        const dim3 grid(groups * 8 * n_mb, a.KS), block(64 * BIG_WAVES);
+        if ((rc = prof_begin()) != BS_OK) return rc;
+#define BS_BIG(MT) do { if (a.tiled) hipLaunchKernelGGL((gemm_bf16_big_kernel<MT, true>), grid, block, 0, s, a); \
+                        else hipLaunchKernelGGL((gemm_bf16_big_kernel<MT, false>), grid, block, 0, s, a); } while (0)
+        if (mt <= 4) BS_BIG(4);
+        else if (mt <= 6) BS_BIG(6);
+        else if (mt <= 8) BS_BIG(8);
+        else if (mt <= 10) BS_BIG(10);
+        else if (mt <= 12) BS_BIG(12);
+        else if (mt <= 14) BS_BIG(14);
+        else BS_BIG(16);
+#undef BS_BIG
+        BS_LAUNCH_CHECK();
+        return prof_end(mt);
     }
-    const int max_rows = big_ok ? GEMM_MAX_ROWS : 128;
+    // up to 32 rows (or K not a multiple of 32: 32 rows at a time)
+    const int max_rows = a.M <= 16 ? 16 : 32;
     for (int m0 = 0; m0 < a.M; m0 += max_rows) {
         GemmArgs c = a;
         c.M = (a.M - m0 < max_rows) ? a.M - m0 : max_rows;
         c.x = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m0 * a.K;
         c.out = reinterpret_cast<float*>(a.out) + (size_t)m0 * a.ldo;
-        const int mt = (c.M + 15) / 16;
-        const int nt = gemm_row_tiles_nt(c.M);                  // weight tiles of 16 rows per wavefront
-        const dim3 grid((a.N + 64 * nt - 1) / (64 * nt), a.KS), block(256);
+        const dim3 grid((a.N + 63) / 64, a.KS), block(256);
         const int kper = ((a.K + a.KS - 1) / a.KS + 31) / 32 * 32;      // columns per split, whole k slices
-        const bool m16 = a.M <= 16;
-        const dim3 big_grid(((a.N + 255) / 256 + 7) / 8 * 8, a.KS);     // one block of rows: whole groups of 8 weight tiles
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        if (g_prof.on) {
-            BS_HIP(hipEventCreate(&e0));
-            BS_HIP(hipEventCreate(&e1));
-            BS_HIP(hipEventRecord(e0, s));
-        }
+        if ((rc = prof_begin()) != BS_OK) return rc;
         // one 16-row weight tile per wavefront measured faster than two (3.7 vs 3.2 TB/s over the 7B layer shapes)
-#define BS_ROWS(TL) do { \
-            if (m16) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, TL>), grid, block, 0, s, c, kper); \
-            else if (mt <= 2) hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, TL>), grid, block, 0, s, c); \
-            else if (mt <= 4) hipLaunchKernelGGL((gemm_bf16_kernel<4, 1, 128, TL>), grid, block, 0, s, c); \
-            else if (mt <= 6) hipLaunchKernelGGL((gemm_bf16_kernel<6, 1, 128, TL>), grid, block, 0, s, c); \
-            else if (mt <= 8) hipLaunchKernelGGL((gemm_bf16_kernel<8, 2, 64, TL>), grid, block, 0, s, c); \
-            else if (mt <= 10) hipLaunchKernelGGL((gemm_bf16_big_kernel<10, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
-            else if (mt <= 12) hipLaunchKernelGGL((gemm_bf16_big_kernel<12, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
-            else if (mt <= 14) hipLaunchKernelGGL((gemm_bf16_big_kernel<14, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); \
-            else hipLaunchKernelGGL((gemm_bf16_big_kernel<16, TL>), big_grid, dim3(64 * BIG_WAVES), 0, s, c); } while (0)
-        if (a.tiled) BS_ROWS(true);
-        else BS_ROWS(false);
-#undef BS_ROWS
-        BS_LAUNCH_CHECK();
-        if (g_prof.on) {
-            BS_HIP(hipEventRecord(e1, s));
-            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
-            g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
-            g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
+        if (a.M <= 16) {
+            if (a.tiled) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, true>), grid, block, 0, s, c, kper);
+            else hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, false>), grid, block, 0, s, c, kper);
+        } else {
+            if (a.tiled) hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, true>), grid, block, 0, s, c);
+            else hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, false>), grid, block, 0, s, c);
         }
+        BS_LAUNCH_CHECK();
+        if ((rc = prof_end((c.M + 15) / 16)) != BS_OK) return rc;
     }
     return BS_OK;
 }
