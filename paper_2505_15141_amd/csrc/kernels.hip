@@ -1428,7 +1428,8 @@ template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict__ q, const uint16_t* __restrict__ k_cache,
                                                         const uint16_t* __restrict__ v_cache,
                                                         const int32_t* __restrict__ pos, int q_len, int H, int KVH,
-                                                        int cache_len, float scale, float* __restrict__ part, int n_splits) {
+                                                        int cache_len, float scale, float* __restrict__ part, int n_splits,
+                                                        uint16_t* __restrict__ direct_out, size_t plane) {
     constexpr int DS = HD / 32, DT = HD / 16;
     __shared__ float wm[4][16], wl[4][16];
     __shared__ float wo[4][16][HD + 1];
@@ -1442,7 +1443,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
     const int m_first = b * q_len;
     const int pos0 = pos[m_first];
     const size_t pstride = (size_t)HD + 4;       // o[HD], max, sum, 2 pad: rows stay 16-byte aligned
-    if (pos0 < 0) {                                  // sequence skipped: empty partials
+    if (pos0 < 0) {                                  // sequence skipped: empty partials (zeros when writing the output itself)
+        if (direct_out) {
+            for (int idx = threadIdx.x + rt * 256; idx < R * HD; idx += 256 * n_rt) {
+                const int r = idx / HD, d = idx % HD;
+                Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + r % q_len) * H + kvh * G + r / q_len) * HD + d, 0.f);
+            }
+            return;
+        }
         for (int r = threadIdx.x; r < R; r += 256) {
             const int g = r / q_len, qi = r % q_len;
             float* dst = part + ((((size_t)(m_first + qi)) * H + kvh * G + g) * n_splits + split) * pstride;
@@ -1580,6 +1588,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
                 lv += wl[w][r] * f;
             }
             const int gg = (r0 + r) / q_len, qq = (r0 + r) % q_len;
+            if (direct_out) {                        // a single split of the keys: this is the attention output
+                Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + qq) * H + kvh * G + gg) * HD + d, lv > 0.f ? ov / lv : 0.f);
+                continue;
+            }
             float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
             dst[d] = ov;
             if (d == 0) { dst[HD] = mm; dst[HD + 1] = lv; }
@@ -1587,39 +1599,38 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
     }
 }
 
-// grid (M*H), threads hd: combine the splits, normalise, store in the storage dtype.
+// grid (M*H), threads hd: combine the splits, normalise, store in the storage dtype.  One pass: the (max, sum, o) of
+// 16 splits are requested together and folded into a running (max, sum, o) -- the partials were written by other dies
+// a moment ago, so every dependent round of loads is a trip to memory.
 template <typename T>
 __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, size_t plane, void* __restrict__ out) {
     const size_t mh = blockIdx.x;
     const int d = threadIdx.x;
     const size_t pstride = (size_t)hd + 4;       // o[hd], max, sum, 2 pad: rows stay 16-byte aligned
     const float* base = part + mh * n_splits * pstride;
-    // loads of up to 8 splits are issued together (they are independent), then combined
-    float mm = -INFINITY;
-    for (int s0 = 0; s0 < n_splits; s0 += 8) {
-        float mv[8];
+    float mm = -INFINITY, o = 0.f, l = 0.f;
+    for (int s0 = 0; s0 < n_splits; s0 += 16) {
+        float mv[16], lv[16], ov[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = (s0 + u < n_splits) ? base[(s0 + u) * pstride + hd] : -INFINITY;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) mm = fmaxf(mm, mv[u]);
-    }
-    float o = 0.f, l = 0.f;
-    for (int s0 = 0; s0 < n_splits; s0 += 8) {
-        float mv[8], lv[8], ov[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const bool ok = s0 + u < n_splits;
-            mv[u] = ok ? base[(s0 + u) * pstride + hd] : -INFINITY;
-            lv[u] = ok ? base[(s0 + u) * pstride + hd + 1] : 0.f;
-            ov[u] = ok ? base[(s0 + u) * pstride + d] : 0.f;
+        for (int u = 0; u < 16; ++u) {
+            const float* ps = base + (size_t)min(s0 + u, n_splits - 1) * pstride;
+            mv[u] = ps[hd]; lv[u] = ps[hd + 1]; ov[u] = ps[d];
+            if (s0 + u >= n_splits) mv[u] = -INFINITY;
         }
+        float gm = mm;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float f = (mv[u] == -INFINITY) ? 0.f : __expf(mv[u] - mm);
-            if (f == 0.f) continue;                      // an empty split's o[] was never written
+        for (int u = 0; u < 16; ++u) gm = fmaxf(gm, mv[u]);
+        if (gm == -INFINITY) continue;
+        const float keep = __expf(mm - gm);       // 0 when nothing was accumulated yet
+        o *= keep; l *= keep;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const float f = (mv[u] == -INFINITY) ? 0.f : __expf(mv[u] - gm);
+            if (f == 0.f) continue;               // an empty split's o[] was never written
             l += lv[u] * f;
             o += ov[u] * f;
         }
+        mm = gm;
     }
     Act<T>::store(out, plane, mh * hd + d, l > 0.f ? o / l : 0.f);
 }
@@ -1757,6 +1768,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
             n_splits = want < n_splits ? want : n_splits;
         }
         const dim3 mgrid(n_splits * (out ? n_rt : 1), KVH, B);
+        uint16_t* direct = (out && n_splits == 1) ? reinterpret_cast<uint16_t*>(out) : nullptr;     // no merge needed
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (g_prof.on) {
             BS_HIP(hipEventCreate(&e0));
@@ -1765,10 +1777,10 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         }
         if (hd == 128)
             hipLaunchKernelGGL((attn_mfma_kernel<128>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits);
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
         else if (hd == 64)
             hipLaunchKernelGGL((attn_mfma_kernel<64>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits);
+                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
         else
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
         BS_LAUNCH_CHECK();
@@ -1778,7 +1790,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
             g_prof.bytes.push_back(0.0);
             g_prof.mt.push_back(100);
         }
-        if (out) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
+        if (out && !direct) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
                            (const float*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);

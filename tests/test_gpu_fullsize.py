@@ -60,6 +60,27 @@ def test_draft_model_prefill_1024_then_steps_of_two_and_one_rows():
     assert e2 < 2e-2 and e1 < 2e-2, (e2, e1)
 
 
+def test_batch_of_16_sequences_verified_over_9_rows_at_full_layer_width():
+    """The batched workload's row count: 16 sequences x (gamma + 1 = 9) = 144 rows through the many-row GEMM at the 7B
+    layer widths (10 row tiles, the split factors of that row count), after a prompt pass of 16 x 24 = 384 rows (two
+    blocks of 256 rows in one launch).  Three of the sequences are checked against the oracle's full recompute."""
+    c = dict(synth.LLAMA7B_TARGET, n_layers=1)
+    W, m = build(c, 27)
+    B, P, q_len = 16, 24, 9
+    kv = bs().KV(m, B, P + 32)
+    toks = synth.make_prompts(B, P + q_len, c["vocab"], seed=28)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    last = bs().prefill(m, kv, dt, P, want_logits=True)
+    kvl = torch.full((B,), P, dtype=torch.int32, device="cuda")
+    logits = bs().verify_forward(m, kv, dt[:, P:P + q_len].contiguous(), kvl)
+    torch.cuda.synchronize()
+    for b in (0, 7, 15):
+        ref = forward(c, W, toks[b], storage="bf16")
+        assert np.max(np.abs(last[b].cpu().numpy() - ref[P - 1])) < 2e-2
+        err = np.max(np.abs(logits[b].cpu().numpy() - ref[P:P + q_len]))
+        assert err < 2e-2, (b, err)
+
+
 def test_attention_head_configuration_at_4096_cached_tokens():
     """32 heads x 128 against 4096 cached keys per sequence (the long-context workloads' attention shape); the FFN and
     the vocabulary are shrunk so that the fp64 full-recompute reference takes seconds."""
