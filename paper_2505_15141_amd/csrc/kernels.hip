@@ -6,7 +6,11 @@
 //   rmsnorm     completes the fp32 residual from pending split-K partials, normalises it
 //   gemm        y = x W^T: bf16 weights streamed once from HBM through MFMA 16x16x32 tiles (the
 //               contraction is skinny: M = B*(gamma+1) rows, so it is bound by weight bandwidth),
-//               split-K partials out; fp32 variant for the fp32 plumbing configuration
+//               split-K partials out; a many-row variant for prompt chunks and batches (activation
+//               stages memory -> LDS directly, 256 x 256 tiles); fp32 variant for the fp32 plumbing
+//               configuration
+//   resid_sum   bf16 models: completes the residual, writes the planes of gain .* x and partial sums
+//               of squares (the RMS scale is applied behind the projection)
 //   gemm_dec    the same contraction for one or two rows (draft steps) with the layer's small kernels
 //               folded into its epilogues (residual, RoPE + cache write, SwiGLU; RMSNorm by linearity)
 //   swiglu      sums gate/up partials, applies silu(g)*u

@@ -219,7 +219,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
     BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
                        w.rope, w.status, s));
     const float* pend = nullptr;      // split-K partials of the last residual projection, not yet added to x
-    // A handful of rows (draft steps): fused schedule, 6 kernels per layer; needs the tiled weights.
+    // A handful of rows (draft steps): fused schedule, 5 kernels per layer; needs the tiled weights.
     const bool few_rows = dt == BS_BF16 && m->packed && gemm_dec_fits(M, d) && gemm_dec_fits(M, nq) && gemm_dec_fits(M, ff);
     if (few_rows) {
         const size_t pd = (size_t)M * d;

@@ -42,9 +42,9 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     # at most four rows on packed weights: the fused few-row schedule of the draft steps
     (MID, 1, 70, 2, True), (MID_GQA, 2, 130, 1, True), (WIDE, 1, 200, 4, True), (ODD_BF16, 2, 150, 2, True),
     (MID, 4, 33, 1, True), (WIDE, 1, 1, 1, True),
-    # prompt chunks of 97..128 rows (two weight tiles per wavefront) and of 129..256 rows (double-buffered kernel)
+    # prompt chunks of 120 and 250..290 rows: the many-row kernel with 8 and 16 row tiles, one and two blocks of 256 rows
     (MID, 1, 120, 3, True), (MID_GQA, 3, 40, 2, False), (MID, 1, 250, 3, True), (ODD_BF16, 1, 290, 2, False),
-    # 129..224 rows: the double-buffered kernel with 10, 12 and 14 row tiles; several 16-row attention tiles per head
+    # 129..224 rows: the many-row kernel with 10, 12 and 14 row tiles; several 16-row attention tiles per head
     (MID, 1, 150, 3, True), (ODD_BF16, 1, 185, 2, False), (MID_GQA, 1, 215, 2, True),
     # more than 256 rows: several blocks of 256 rows in one GEMM launch (ragged last block), attention over many row tiles
     (MID, 1, 700, 3, True), (MID_GQA, 4, 128, 2, False), (ODD_BF16, 1, 300, 2, True)])
