@@ -94,9 +94,11 @@ def stage_probes(bs, synth, torch, np, stream):
     out = {}
     with torch.cuda.stream(stream):
         # ---- accept/reject + residual sampling: the stand-alone workload (B = 64) and the same rows at B = 1024 ----
-        gamma, V = 8, 32000
+        gamma = 8
         g = torch.Generator(device="cuda"); g.manual_seed(7)
-        for B, copies, key in ((64, 5, "sampling"), (1024, 2, "sampling_b1024")):    # 5 x 70 MB: more than the 256 MB last-level cache
+        # 5 x 70 MB: more than the 256 MB last-level cache; the other sizes exceed it with one or two copies
+        for B, V, copies, key in ((64, 32000, 5, "sampling"), (256, 32000, 2, "sampling_b256"), (1024, 32000, 2, "sampling_b1024"),
+                                  (64, 128256, 2, "sampling_v128256")):
             T = [(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 2).to(torch.bfloat16) for _ in range(copies)]
             Q = [(t[:, :gamma].float() + 0.5 * torch.randn(B, gamma, V, generator=g, device="cuda")).to(torch.bfloat16) for t in T]
             toks = [torch.multinomial(torch.softmax(q.float().view(-1, V), -1), 1).view(B, gamma).to(torch.int32) for q in Q]
@@ -115,10 +117,26 @@ def stage_probes(bs, synth, torch, np, stream):
             acc = res[0].cpu().numpy()
             alg = float(np.sum((acc + 1) + np.minimum(acc + 1, gamma))) * V * 2      # rows up to the deciding one
             touched = B * (2 * gamma + 1) * V * 2
-            out[key] = {"workload": f"B={B} gamma=8 V=32000 bf16 logits", "us": round(us, 2),
+            out[key] = {"workload": f"B={B} gamma=8 V={V} bf16 logits", "us": round(us, 2),
                         "touched_GBps": round(touched / us / 1e3, 1), "algorithmic_GBps": round(alg / us / 1e3, 1),
                         "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4)}
             del T, Q, toks
+        # ---- what this machine delivers to plain library kernels (yardsticks for the fractions of the published peaks) ----
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
+        a16 = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16); b16 = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+        def timed_us(fn, reps):
+            fn(); fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream); e1.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+        us_copy = timed_us(lambda: dst.copy_(src), 10)
+        us_mm = timed_us(lambda: torch.matmul(a16, b16), 10)
+        out["measured_peaks"] = {"device_copy_1GiB_GBps_read_plus_write": round(2 * (1 << 30) / us_copy / 1e3, 1),
+                                 "library_bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / us_mm / 1e6, 1)}
+        del src, dst, a16, b16
         # ---- verification attention at batch 16, 4096 cached tokens, one 7B-shaped layer ----
         c1 = dict(synth.LLAMA7B_TARGET, n_layers=1, vocab=1024)
         m1 = bs.Model(c1, gpu_weights(c1, 9, torch)).pack(release_originals=True)
