@@ -239,11 +239,14 @@ def main():
             arm = bandit.select()
             y, seconds = timed_round(arm)
             bandit.update(arm, bs.throughput_reward(y, seconds, canon_s, L) if by_throughput else y)
+            step_seconds.append(seconds)
             return arm, y
 
+        step_seconds = []
         for _ in range(args.warmup):
             one_round()
         torch.cuda.synchronize()
+        step_seconds.clear()                          # wall time of every timed round, for the spread
         t0 = time.perf_counter()
         ys, arms = [], []
         for _ in range(args.steps):
@@ -252,6 +255,7 @@ def main():
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         gen_tokens = float(np.sum(ys)) * B
+        step_ms = np.asarray(step_seconds[:args.steps]) * 1e3
 
         # ---- canonical decoding (Alg. 1) on the same kernels: gamma = 0 rounds, one token per target pass ----
         canonical = None
@@ -379,6 +383,8 @@ def main():
                       "graph": not args.no_graph},
            "mean_accepted_tokens": round(mean_y, 4), "generated_tokens": int(gen_tokens),
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
+           "ms_per_step_spread": ({"median": round(float(np.median(step_ms)), 4), "p10": round(float(np.percentile(step_ms, 10)), 4),
+                                   "p90": round(float(np.percentile(step_ms, 90)), 4)} if len(step_ms) else None),
            "round_ms_by_gamma": round_ms,
            "draft_step_us": (round((round_ms["8"] - round_ms["2"] - (verify_ms["8"] - verify_ms["2"])) / 6.0 * 1e3, 1)
                              if "8" in round_ms and "2" in round_ms and verify_ms else None),
