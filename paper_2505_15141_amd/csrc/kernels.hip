@@ -484,12 +484,18 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lq = lane >> 4;
     const int wn = wave & 3, wm = wave >> 2;
-    // blockIdx.x enumerates (tile of 256 weight rows, block of 256 activation rows): the blocks of one weight tile sit 8
-    // workgroups apart, i.e. on the same die (workgroups go round the 8 dies) and in flight together, so that the tile is
-    // fetched from memory once and found in that die's L2 by the others
+    // Work item = (split of K, tile of 256 weight rows, block of 256 activation rows), in that order of significance.
+    // Workgroups go round the 8 dies (linear id modulo 8), each die with its own L2: die x takes the x-th eighth of the
+    // item list, so that it works on one or two K ranges only -- it reads just that slice of the activations (which all
+    // its tiles share) and each of its weight tiles once for all row blocks.  With the tiles dealt round the dies
+    // instead, every die read ALL activations: 450 MB from memory for the 135 MB of the 7B down projection at 1024 rows.
     const int n_mb = (a.M + 255) / 256, n_tiles = (a.N + 255) / 256;
-    const int grp = blockIdx.x / (8 * n_mb), rem = blockIdx.x - grp * (8 * n_mb);
-    const int tile = grp * 8 + (rem & 7), m_off = (rem >> 3) * 256;
+    const int n_tiles_pad = (n_tiles + 7) & ~7, KS = gridDim.y;
+    const int lin = blockIdx.x + gridDim.x * blockIdx.y;           // gridDim.x = n_tiles_pad * n_mb
+    const int per_die = (n_tiles_pad * n_mb * KS) >> 3;
+    const int item = (lin & 7) * per_die + (lin >> 3);
+    const int ks = item / (n_tiles_pad * n_mb), rem = item - ks * (n_tiles_pad * n_mb);
+    const int tile = rem / n_mb, m_off = (rem - tile * n_mb) * 256;
     if (tile >= n_tiles) return;                                   // the grid is padded to whole groups of 8 tiles
     const int M = min(a.M - m_off, 256);
     const int n0 = tile * 256 + wn * 64;
@@ -504,7 +510,6 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
     }
     const uint16_t* xh = reinterpret_cast<const uint16_t*>(a.x) + (size_t)m_off * a.K;
     const int nstages = a.K / 32;                     // K % 32 == 0 (host check)
-    const int ks = blockIdx.y, KS = gridDim.y;
     const int st_begin = (int)((long long)nstages * ks / KS), st_end = (int)((long long)nstages * (ks + 1) / KS);
     const int st_last = max(st_end - 1, st_begin);
     // this wavefront's pieces of a stage: piece p = plane * MT + tile.  The transfer puts lane l's 16 bytes at offset
