@@ -47,7 +47,10 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     # 129..224 rows: the many-row kernel with 10, 12 and 14 row tiles; several 16-row attention tiles per head
     (MID, 1, 150, 3, True), (ODD_BF16, 1, 185, 2, False), (MID_GQA, 1, 215, 2, True),
     # more than 256 rows: several blocks of 256 rows in one GEMM launch (ragged last block), attention over many row tiles
-    (MID, 1, 700, 3, True), (MID_GQA, 4, 128, 2, False), (ODD_BF16, 1, 300, 2, True)])
+    (MID, 1, 700, 3, True), (MID_GQA, 4, 128, 2, False), (ODD_BF16, 1, 300, 2, True),
+    # 36..45 rows in the verification pass itself (a batch): the many-row kernel for every projection and for the LM head,
+    # with a vocabulary that is no multiple of 16
+    (ODD_BF16, 5, 20, 9, True), (MID, 4, 30, 9, False)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
     W, m, kv = setup(c, B, max(320, n_prefix + q_len + 8), seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
