@@ -118,7 +118,7 @@ __device__ __forceinline__ float load_one<uint16_t>(const uint16_t* row, int idx
 }
 
 struct RowShared {
-    float red[4][SW];
+    float red[4][SW];                 // also the staging of SLAB_BATCH slab sums
     float slab_tot[MAX_SLABS];
     float wave_tot[SW];
     int wave_first[SW];
@@ -126,6 +126,8 @@ struct RowShared {
     float bcast[8];
     int ibcast[4];
 };
+
+static_assert(SLAB_BATCH <= 4, "RowShared::red has four rows");
 
 struct RowResult {
     int token;        // candidate token of this row (valid in every lane)
