@@ -50,7 +50,9 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     (MID, 1, 700, 3, True), (MID_GQA, 4, 128, 2, False), (ODD_BF16, 1, 300, 2, True),
     # 36..45 rows in the verification pass itself (a batch): the many-row kernel for every projection and for the LM head,
     # with a vocabulary that is no multiple of 16
-    (ODD_BF16, 5, 20, 9, True), (MID, 4, 30, 9, False)])
+    (ODD_BF16, 5, 20, 9, True), (MID, 4, 30, 9, False),
+    # a prompt longer than the largest chunk: 1024 rows (four blocks of 256), then the rest against 1024 cached tokens
+    (MID_GQA, 1, 1100, 2, True)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
     W, m, kv = setup(c, B, max(320, n_prefix + q_len + 8), seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
