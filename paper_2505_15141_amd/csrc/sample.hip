@@ -181,20 +181,9 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
             }
         }
     } else if (!known) {
-        // four groups per lane requested together: a loop of one dependent load per trip costs a memory latency per trip
-        for (int g0 = tid; g0 < ngroups; g0 += 4 * ST) {
-            Raw<T> rp[4], rq[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int g = g0 + u * ST;
-                rp[u] = (g < ngroups) ? load_raw(p, g, V, vec_p) : neg_inf_raw(p);
-                rq[u] = (has_q && g < ngroups) ? load_raw(q, g, V, vec_q) : neg_inf_raw(p);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                online(mp, sp, rp[u]);
-                if (has_q) online(mq, sq, rq[u]);
-            }
+        for (int g = tid; g < ngroups; g += ST) {
+            online(mp, sp, load_raw(p, g, V, vec_p));
+            if (has_q) online(mq, sq, load_raw(q, g, V, vec_q));
         }
     }
     if constexpr (CACHED) {
