@@ -163,6 +163,53 @@ def stage_probes(bs, synth, torch, np, stream):
     return out
 
 
+def batch_rounds_stage(bs, synth, torch, np, stream, target, draft, tc, rounds=24):
+    """Whole rounds of the batched, non-stationary workload on the same models: 16 sequences with 4096 cached tokens each,
+    EXP3Spec over gamma in {2,3,4,5,6,8}, the draft-logit perturbation switching between 0.2 and 1.5 every 64 generated
+    tokens per sequence, one bandit for the batch with the mean accepted length as reward.  The cache holds the prompt
+    pass of random tokens; a short run (graph replay per arm), reported as a stage, not as the headline value."""
+    B, ctx, gam = 16, 4096, [2, 3, 4, 5, 6, 8]
+    L = max(gam)
+    max_len = ctx + (L + 1) * (rounds + 4) + L + 2
+    with torch.cuda.stream(stream):
+        tkv, dkv = bs.KV(target, B, max_len), bs.KV(draft, B, max_len)
+        tokens = torch.zeros(B, max_len, dtype=torch.int32, device="cuda")
+        tokens[:, :ctx] = torch.from_numpy(synth.make_prompts(B, ctx, tc["vocab"], 5).astype(np.int32)).cuda()
+        total = torch.full((B,), ctx, dtype=torch.int32, device="cuda")
+        goal = torch.full((B,), max_len, dtype=torch.int32, device="cuda")
+        plen = torch.full((B,), ctx, dtype=torch.int32, device="cuda")
+        t0 = time.perf_counter()
+        bs.prefill(target, tkv, tokens, ctx - 1)
+        bs.prefill(draft, dkv, tokens, ctx - 1)
+        stream.synchronize()
+        prefill_s = time.perf_counter() - t0
+        rnd = bs.Round(target, tkv, [draft], [dkv], [0] * len(gam), gam, tokens, total, goal, 1.0, 77, use_graph=True,
+                       prompt_len=plen, noise=(0.2, 1.5, 64))
+        rnd.reset(0)
+        bandit = bs.Bandit(bs.BS_EXP3SPEC, len(gam), L, 0.5, 11)
+        host_y = torch.zeros(B, dtype=torch.int32).pin_memory()
+
+        def one():
+            arm = bandit.select()
+            _, n_emitted = rnd.spec_round(arm)
+            host_y.copy_(n_emitted, non_blocking=True)
+            stream.synchronize()
+            y = float(host_y.float().mean())
+            bandit.update(arm, y)
+            return arm, y
+        for _ in range(len(gam)):                 # every arm once: the graphs are captured here
+            one()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        arms, ys = zip(*[one() for _ in range(rounds)])
+        stream.synchronize()
+        dt = time.perf_counter() - t0
+    return {"workload": "B=16, 4096 cached tokens, EXP3Spec over gamma in {2,3,4,5,6,8}, noise 0.2/1.5 every 64 tokens",
+            "rounds": rounds, "tokens_per_s": round(float(np.sum(ys)) * B / dt, 1), "ms_per_round": round(dt / rounds * 1e3, 3),
+            "mean_accepted_tokens": round(float(np.mean(ys)), 3), "arm_pulls": [int(np.sum(np.asarray(arms) == a)) for a in range(len(gam))],
+            "prompt_pass_s_both_models_65520_tokens": round(prefill_s, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -358,6 +405,7 @@ def main():
                                             "frac_hbm": round((wb_b + kv_bytes_b) / ms_b / 1e6 / HBM_PEAK_GBS, 4),
                                             "mfma_issue_frac_of_peak": round(2 * wb_b * Bb * q_len / (ms_b * 1e-3) / 2.5e15, 4)}
             del kvb, wsb, lgb
+        stages["rounds_b16_ctx4096"] = batch_rounds_stage(bs, synth, torch, np, stream, target, draft, tc)
     # a plain device copy of known size: the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a --pmc run
     cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
     cal_dst = torch.empty_like(cal_src)
