@@ -263,8 +263,9 @@ int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const flo
 
 /* ------------------------------------------------------------------------------------------------
  * Measurement hook (not part of the method): while enabled, every launch of the bf16 weight-streaming
- * GEMM and of the bf16 attention kernel made OUTSIDE a graph capture is bracketed by HIP events on its
- * own stream.  bs_profile_collect synchronises on those events and returns, for launches of the asked
+ * GEMM and of the bf16 attention kernel made OUTSIDE a graph capture carries its own start and stop
+ * events (they take the begin and end times of the dispatch itself, so the elapsed time is the kernel's
+ * alone).  bs_profile_collect synchronises on those events and returns, for launches of the asked
  * class, the summed kernel time in ms, the summed algorithmic bytes and the launch count.  Classes:
  * 1, 2, 4, 6, 8, 16 = GEMM launches with up to that many tiles of 16 activation rows (bytes: each weight element
  * once, N*K*2); 50 = the fused few-row projections of draft steps (same bytes); 100 = attention (bytes

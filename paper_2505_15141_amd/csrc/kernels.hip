@@ -19,6 +19,7 @@
 //               keys with online softmax; merge kernel combines the splits
 #include <math.h>
 #include <vector>
+#include <hip/hip_ext.h>
 #include "common.h"
 #include "kernels.h"
 
@@ -1113,6 +1114,13 @@ int gemm_splits(int dtype, int N, int K, int M) {
     return ks;
 }
 
+// A kernel launch that, while the measurement hook is on (e0 != nullptr), carries its own start and stop events: they
+// take the dispatch's begin and end times, so the elapsed time is the kernel's and nothing else (two events recorded
+// around a launch also measure 2-3 us of dispatch).
+#define BS_LAUNCH_TIMED(kernel, grid, block, lds, stream, e0, e1, ...) \
+    do { if (e0) hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)(lds), stream, e0, e1, 0, __VA_ARGS__); \
+         else hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__); } while (0)
+
 // ---- optional per-launch timing of the weight-streaming GEMM (measurement hook) ----------------------
 struct GemmProfile {
     bool on = false;
@@ -1172,12 +1180,10 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         if (!g_prof.on) return BS_OK;
         BS_HIP(hipEventCreate(&e0));
         BS_HIP(hipEventCreate(&e1));
-        BS_HIP(hipEventRecord(e0, s));
         return BS_OK;
     };
     auto prof_end = [&](int mt) -> int {                            // classes by 16-row tiles: 1, 2, 4, 6, 8, 16
         if (!g_prof.on) return BS_OK;
-        BS_HIP(hipEventRecord(e1, s));
         g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
         g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
         g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
@@ -1191,8 +1197,8 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         const int n_mb = (a.M + 255) / 256, groups = ((a.N + 255) / 256 + 7) / 8;      // whole groups of 8 weight tiles
         const dim3 grid(groups * 8 * n_mb, a.KS), block(64 * BIG_WAVES);
         if ((rc = prof_begin()) != BS_OK) return rc;
-#define BS_BIG(MT) do { if (a.tiled) hipLaunchKernelGGL((gemm_bf16_big_kernel<MT, true>), grid, block, 0, s, a); \
-                        else hipLaunchKernelGGL((gemm_bf16_big_kernel<MT, false>), grid, block, 0, s, a); } while (0)
+#define BS_BIG(MT) do { if (a.tiled) BS_LAUNCH_TIMED((gemm_bf16_big_kernel<MT, true>), grid, block, 0, s, e0, e1, a); \
+                        else BS_LAUNCH_TIMED((gemm_bf16_big_kernel<MT, false>), grid, block, 0, s, e0, e1, a); } while (0)
         if (mt <= 4) BS_BIG(4);
         else if (mt <= 6) BS_BIG(6);
         else if (mt <= 8) BS_BIG(8);
@@ -1216,11 +1222,11 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
         if ((rc = prof_begin()) != BS_OK) return rc;
         // one 16-row weight tile per wavefront measured faster than two (3.7 vs 3.2 TB/s over the 7B layer shapes)
         if (a.M <= 16) {
-            if (a.tiled) hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, true>), grid, block, 0, s, c, kper);
-            else hipLaunchKernelGGL((gemm_bf16_m16_kernel<1, false>), grid, block, 0, s, c, kper);
+            if (a.tiled) BS_LAUNCH_TIMED((gemm_bf16_m16_kernel<1, true>), grid, block, 0, s, e0, e1, c, kper);
+            else BS_LAUNCH_TIMED((gemm_bf16_m16_kernel<1, false>), grid, block, 0, s, e0, e1, c, kper);
         } else {
-            if (a.tiled) hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, true>), grid, block, 0, s, c);
-            else hipLaunchKernelGGL((gemm_bf16_kernel<2, 1, 256, false>), grid, block, 0, s, c);
+            if (a.tiled) BS_LAUNCH_TIMED((gemm_bf16_kernel<2, 1, 256, true>), grid, block, 0, s, e0, e1, c);
+            else BS_LAUNCH_TIMED((gemm_bf16_kernel<2, 1, 256, false>), grid, block, 0, s, e0, e1, c);
         }
         BS_LAUNCH_CHECK();
         if ((rc = prof_end((c.M + 15) / 16)) != BS_OK) return rc;
@@ -1683,11 +1689,10 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
     if (g_prof.on) {
         BS_HIP(hipEventCreate(&e0));
         BS_HIP(hipEventCreate(&e1));
-        BS_HIP(hipEventRecord(e0, s));
     }
     const size_t lds = dec_lds_bytes(a.M, a.K);
-#define BS_DEC(E, MG) do { if (deep) hipLaunchKernelGGL((gemm_dec_kernel<E, 8, MG>), grid, block, lds, s, a); \
-                           else hipLaunchKernelGGL((gemm_dec_kernel<E, 4, MG>), grid, block, lds, s, a); } while (0)
+#define BS_DEC(E, MG) do { if (deep) BS_LAUNCH_TIMED((gemm_dec_kernel<E, 8, MG>), grid, block, lds, s, e0, e1, a); \
+                           else BS_LAUNCH_TIMED((gemm_dec_kernel<E, 4, MG>), grid, block, lds, s, e0, e1, a); } while (0)
     if (epi == EPI_RESID && a.att_part) BS_DEC(EPI_RESID, true);
     else if (epi == EPI_RESID) BS_DEC(EPI_RESID, false);
     else if (epi == EPI_QKV) BS_DEC(EPI_QKV, false);
@@ -1695,7 +1700,6 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
 #undef BS_DEC
     BS_LAUNCH_CHECK();
     if (g_prof.on) {                                       // class 50: fused few-row projections
-        BS_HIP(hipEventRecord(e1, s));
         g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
         g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0));
         g_prof.mt.push_back(50);
@@ -1782,19 +1786,17 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         if (g_prof.on) {
             BS_HIP(hipEventCreate(&e0));
             BS_HIP(hipEventCreate(&e1));
-            BS_HIP(hipEventRecord(e0, s));
         }
         if (hd == 128)
-            hipLaunchKernelGGL((attn_mfma_kernel<128>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
+            BS_LAUNCH_TIMED((attn_mfma_kernel<128>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache,
+                            (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
         else if (hd == 64)
-            hipLaunchKernelGGL((attn_mfma_kernel<64>), mgrid, block, 0, s, q, (const uint16_t*)k_cache,
-                               (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
+            BS_LAUNCH_TIMED((attn_mfma_kernel<64>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache,
+                            (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
         else
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
         BS_LAUNCH_CHECK();
         if (g_prof.on) {                                   // class 100: the split attention kernel (bytes known to the caller)
-            BS_HIP(hipEventRecord(e1, s));
             g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
             g_prof.bytes.push_back(0.0);
             g_prof.mt.push_back(100);
