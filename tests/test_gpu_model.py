@@ -71,6 +71,28 @@ def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packe
         assert np.max(np.abs(got - ref[n_prefix:n_prefix + q_len])) < tol, np.max(np.abs(got - ref[n_prefix:n_prefix + q_len]))
 
 
+@pytest.mark.parametrize("B,n_prefix,q_len,max_len", [
+    (1, 63, 2, 1100),      # three key splits of one 32-key block each: the two new keys fall into different splits
+    (1, 64, 2, 1100), (2, 95, 1, 1100), (1, 1000, 2, 1100), (1, 31, 1, 2100), (1, 1, 1, 600), (2, 300, 1, 4200)])
+def test_one_and_two_rows_on_a_narrow_model_with_a_long_cache(B, n_prefix, q_len, max_len):
+    """Draft steps: one or two rows against a cache whose full length asks for several key splits, the new keys sitting
+    at the edge of a 32-key block or of a split; the second pass reads what the first one put into the cache."""
+    W, m, kv = setup(MID, B, max_len, seed=31, packed=True)
+    toks = synth.make_prompts(B, n_prefix + 2 * q_len, MID["vocab"], seed=32)
+    dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
+    bs().prefill(m, kv, dtoks, n_prefix, want_logits=False)
+    kvl = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
+    first = bs().verify_forward(m, kv, dtoks[:, n_prefix:n_prefix + q_len].contiguous(), kvl)
+    kvl += q_len                                      # the second pass reads what the first one put into the cache
+    second = bs().verify_forward(m, kv, dtoks[:, n_prefix + q_len:n_prefix + 2 * q_len].contiguous(), kvl)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = forward(MID, W, toks[b], storage="bf16")
+        e1 = np.max(np.abs(first[b].cpu().numpy() - ref[n_prefix:n_prefix + q_len]))
+        e2 = np.max(np.abs(second[b].cpu().numpy() - ref[n_prefix + q_len:n_prefix + 2 * q_len]))
+        assert e1 < TOL["bf16"] and e2 < TOL["bf16"], (b, e1, e2)
+
+
 @pytest.mark.parametrize("c,B,n_prefix,q_len", [(MID_GQA, 2, 140, 9), (ODD_BF16, 1, 33, 5), (WIDE, 1, 20, 16)])
 def test_packed_weights_give_bit_identical_logits(c, B, n_prefix, q_len):
     """The tiled copy only changes where each weight is read from, not the order of the arithmetic."""
