@@ -210,6 +210,78 @@ def batch_rounds_stage(bs, synth, torch, np, stream, target, draft, tc, rounds=2
             "prompt_pass_s_both_models_65520_tokens": round(prefill_s, 3)}
 
 
+def multi_draft_rounds_stage(bs, synth, torch, np, stream, rounds=12):
+    """Whole rounds of the multi-draft workload at its full size: Llama-3-8B-shaped target (grouped-query attention 32 / 8
+    heads, FFN 14336, vocabulary 128256), three draft models of 1, 2 and 4 layers (d = 1024) as the arms of UCBSpec, gamma = 5
+    for each, 32 sequences with 8192 cached tokens each.  A draft model that was not pulled catches up before its next
+    proposal (eager passes ahead of the replayed graph).  A short run, reported as a stage."""
+    tc, dcs = synth.LLAMA3_8B_TARGET, synth.LLAMA3_DRAFTS
+    B, ctx, gamma = 32, 8192, 5
+    max_len = ctx + (gamma + 1) * (rounds + len(dcs) + 2) + gamma + 2
+    with torch.cuda.stream(stream):
+        target = bs.Model(tc, synth.make_weights_device(tc, 61, "cuda")).pack(release_originals=True)
+        drafts = [bs.Model(dc, synth.make_weights_device(dc, 62 + i, "cuda")).pack(release_originals=True) for i, dc in enumerate(dcs)]
+        tkv = bs.KV(target, B, max_len)
+        dkvs = [bs.KV(d, B, max_len) for d in drafts]
+        tokens = torch.zeros(B, max_len, dtype=torch.int32, device="cuda")
+        tokens[:, :ctx] = torch.from_numpy(synth.make_prompts(B, ctx, tc["vocab"], 6).astype(np.int32)).cuda()
+        total = torch.full((B,), ctx, dtype=torch.int32, device="cuda")
+        goal = torch.full((B,), max_len, dtype=torch.int32, device="cuda")
+        stream.synchronize()
+        t0 = time.perf_counter()
+        bs.prefill(target, tkv, tokens, ctx - 1)
+        stream.synchronize()
+        prefill_target_s = time.perf_counter() - t0
+        for d, kv in zip(drafts, dkvs):
+            bs.prefill(d, kv, tokens, ctx - 1)
+        rnd = bs.Round(target, tkv, drafts, dkvs, list(range(len(drafts))), [gamma] * len(drafts), tokens, total, goal, 1.0, 78,
+                       use_graph=True)
+        rnd.reset(0)
+        bandit = bs.Bandit(bs.BS_UCBSPEC, len(drafts), gamma, 0.5, 12)
+        host_y = torch.zeros(B, dtype=torch.int32).pin_memory()
+
+        def one():
+            arm = bandit.select()
+            _, n_emitted = rnd.spec_round(arm)
+            host_y.copy_(n_emitted, non_blocking=True)
+            stream.synchronize()
+            y = float(host_y.float().mean())
+            bandit.update(arm, y)
+            return arm, y
+        for _ in range(len(drafts)):              # UCBSpec pulls every arm once first: the graphs are captured here
+            one()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        arms, ys = zip(*[one() for _ in range(rounds)])
+        stream.synchronize()
+        dt = time.perf_counter() - t0
+        # one verification pass of the same shape by itself (6 rows per sequence against the cache as it stands)
+        q_len = gamma + 1
+        ws = torch.empty(target.forward_workspace_bytes(B, q_len, max_len), dtype=torch.uint8, device="cuda")
+        lg = torch.empty(B, q_len, tc["vocab"], dtype=torch.float32, device="cuda")
+        kvl = (total - 1 - q_len).clamp(min=0).to(torch.int32)
+        qtok = tokens[:, ctx:ctx + q_len].contiguous()
+        ts = []
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            bs.verify_forward(target, tkv, qtok, kvl, workspace=ws, logits=lg)
+            e1.record(stream); e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms_v = float(np.median(ts[1:]))
+    nq, nkv = tc["n_heads"] * tc["head_dim"], tc["n_kv_heads"] * tc["head_dim"]
+    w_bytes = 2 * (tc["n_layers"] * (tc["d_model"] * (nq + 2 * nkv) + nq * tc["d_model"] + 3 * tc["d_model"] * tc["d_ff"]) + tc["vocab"] * tc["d_model"])
+    kv_bytes = 2 * ctx * nkv * 2 * B * tc["n_layers"]
+    return {"workload": "B=32, 8192 cached tokens, Llama-3-8B-shaped target (GQA 32/8, vocab 128256), UCBSpec over three draft models "
+                        "(1/2/4 layers, d=1024), gamma=5",
+            "rounds": rounds, "tokens_per_s": round(float(np.sum(ys)) * B / dt, 1), "ms_per_round": round(dt / rounds * 1e3, 3),
+            "mean_accepted_tokens": round(float(np.mean(ys)), 3), "arm_pulls": [int(np.sum(np.asarray(arms) == a)) for a in range(len(drafts))],
+            "verify_ms": round(ms_v, 3), "verify_rows": B * q_len,
+            "verify_weight_plus_kv_GBps": round((w_bytes + kv_bytes) / ms_v / 1e6, 1),
+            "verify_frac_hbm": round((w_bytes + kv_bytes) / ms_v / 1e6 / HBM_PEAK_GBS, 4),
+            "prompt_pass_s_target_%d_tokens" % (B * (ctx - 1)): round(prefill_target_s, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -222,6 +294,7 @@ def main():
                     help="accepted: reward = accepted length y (the headline configuration); throughput: arms gamma in "
                          "{0,2,4,6,8} with the measured tokens/s of the round as the reward (bs_throughput_reward)")
     ap.add_argument("--canonical-rounds", type=int, default=32, help="rounds of gamma = 0 (canonical decoding) timed as the baseline")
+    ap.add_argument("--no-multi-draft", action="store_true", help="skip the stage with the 8B-shaped target and three draft models")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for `rocprofv3 --pmc` runs: only the eager, event-timed rounds are executed, so the 16-row GEMM "
                          "dispatches of the counter file are exactly the launches whose algorithmic bytes are printed")
@@ -406,6 +479,9 @@ def main():
                                             "mfma_issue_frac_of_peak": round(2 * wb_b * Bb * q_len / (ms_b * 1e-3) / 2.5e15, 4)}
             del kvb, wsb, lgb
         stages["rounds_b16_ctx4096"] = batch_rounds_stage(bs, synth, torch, np, stream, target, draft, tc)
+        if not args.no_multi_draft:
+            torch.cuda.empty_cache()
+            stages["rounds_b32_ctx8192_three_drafts"] = multi_draft_rounds_stage(bs, synth, torch, np, stream)
     # a plain device copy of known size: the yardstick for the FETCH_SIZE / WRITE_SIZE counters of a --pmc run
     cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
     cal_dst = torch.empty_like(cal_src)
