@@ -1427,7 +1427,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 //   online softmax     a row lives in one lane column (l % 16); its 32 scores sit in 4 lanes -> 2 shuffles
 //   O^T += V^T . P^T   A = transposed V block (one 16-byte load per lane), B = P^T taken from the score
 //                      accumulators as they are (hi/lo pair), no LDS, no transposes
-// Bytes: every K and V element is read once per 16 rows.  Un-normalised partials (m, l, o[hd]) per split.
+// Bytes: every K and V element is read once per 16 rows (per 32 with two tiles per wavefront, below).  Un-normalised
+// partials (m, l, o[hd]) per split.
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return (uint32_t)from_f<uint16_t>(a) | ((uint32_t)from_f<uint16_t>(b) << 16);
 }
@@ -1439,7 +1440,13 @@ __device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
     lo = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
 }
 
-template <int HD>
+// NT = 16-row tiles a wavefront holds at the same time: every K and V block it loads is multiplied with all of them.
+// With grouped queries a verification pass has G * (gamma + 1) rows per kv head, more than one tile from 17 rows on, and a
+// second workgroup for the second tile walks the whole cache a second time (batch 32, 8192 cached keys, 24 rows: 3.7
+// TB/s of distinct K/V bytes against 5.3 with one tile).  Two tiles take about 320 registers, one wavefront per SIMD;
+// its next block is therefore requested before the current one is multiplied (two register sets, loop unrolled by two;
+// two blocks ahead measured the same).
+template <int HD, int NT>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict__ q, const uint16_t* __restrict__ k_cache,
                                                         const uint16_t* __restrict__ v_cache,
                                                         const int32_t* __restrict__ pos, int q_len, int H, int KVH,
@@ -1448,8 +1455,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
     constexpr int DS = HD / 32, DT = HD / 16;
     __shared__ float wm[4][16], wl[4][16];
     __shared__ float wo[4][16][HD + 1];
-    // blockIdx.x = (group of row tiles, split of the keys): with many query rows (a prompt chunk) the tiles of 16
-    // rows are spread over workgroups and the keys over few splits; with one tile all of gridDim.x are key splits
+    // blockIdx.x = (group of NT row tiles, split of the keys): with many query rows (a prompt chunk) the groups are
+    // spread over workgroups and the keys over few splits; with one group all of gridDim.x are key splits
     const int split = blockIdx.x % n_splits, rt = blockIdx.x / n_splits, n_rt = gridDim.x / n_splits;
     const int kvh = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1477,19 +1484,24 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
     const uint16_t* kb = k_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
     const uint16_t* vb = v_cache + ((size_t)b * KVH + kvh) * (size_t)cache_len * HD;
 
-    for (int r0 = rt * 16; r0 < R; r0 += 16 * n_rt) {
-        // keys any row of this tile may see (causal): up to the tile's latest query position
-        const int r_last = min(r0 + 15, R - 1);
+    for (int r0 = rt * 16 * NT; r0 < R; r0 += 16 * NT * n_rt) {
+        // keys any row of this group may see (causal): up to the group's latest query position
+        const int r_last = min(r0 + 16 * NT - 1, R - 1);
         const int qi_max = (r0 / q_len == r_last / q_len) ? r_last % q_len : q_len - 1;
         const int nblk = (pos0 + qi_max + 1 + 31) / 32;
         const int per = (nblk + n_splits - 1) / n_splits;
         const int b_begin = split * per, b_end = min(nblk, b_begin + per);
-        const int row = r0 + li;
-        const bool rvalid = row < R;
-        const int g = rvalid ? row / q_len : 0, qi = rvalid ? row % q_len : 0;
-        const int row_pos = pos0 + qi;
-        uint4 qh[DS], ql[DS];
-        {
+        bool rvalid[NT];
+        int row_pos[NT];
+        uint4 qh[NT][DS], ql[NT][DS];
+        float m_run[NT], l_run[NT];
+        f32x4 o[NT][DT];
+#pragma unroll
+        for (int x = 0; x < NT; ++x) {
+            const int row = r0 + 16 * x + li;
+            rvalid[x] = row < R;
+            const int g = rvalid[x] ? row / q_len : 0, qi = rvalid[x] ? row % q_len : 0;
+            row_pos[x] = pos0 + qi;
             const float* qrow = q + ((size_t)(m_first + qi) * H + kvh * G + g) * HD;
 #pragma unroll
             for (int ds = 0; ds < DS; ++ds) {
@@ -1498,68 +1510,26 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
                 const float4 c = *reinterpret_cast<const float4*>(qrow + ds * 32 + lq * 8 + 4);
                 v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = rvalid ? v[e] * scale : 0.f;
-                split8(v, qh[ds], ql[ds]);
+                for (int e = 0; e < 8; ++e) v[e] = rvalid[x] ? v[e] * scale : 0.f;
+                split8(v, qh[x][ds], ql[x][ds]);
             }
-        }
-        float m_run = -INFINITY, l_run = 0.f;
-        f32x4 o[DT];
+            m_run[x] = -INFINITY; l_run[x] = 0.f;
 #pragma unroll
-        for (int t = 0; t < DT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        for (int blk = b_begin + wave; blk < b_end; blk += 4) {
+            for (int t = 0; t < DT; ++t) o[x][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        auto fetch = [&](int blk, uint4 (&kf)[2][DS], uint4 (&vf)[DT]) {
             const int key0 = blk * 32;
-            // ---- scores of 32 keys x 16 rows ----
-            f32x4 sc[2];
-            uint4 kf[2][DS];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const int krow = min(key0 + t * 16 + li, n_keys - 1);
 #pragma unroll
                 for (int ds = 0; ds < DS; ++ds) kf[t][ds] = ldg16(kb + (size_t)krow * HD + ds * 32 + lq * 8);
             }
-            uint4 vf[DT];
 #pragma unroll
             for (int t = 0; t < DT; ++t) vf[t] = ldg16(vb + ((size_t)blk * HD + t * 16 + li) * 32 + lq * 8);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ds = 0; ds < DS; ++ds) {
-                    const bf16x8 A = __builtin_bit_cast(bf16x8, kf[t][ds]);
-                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, qh[ds]), sc[t], 0, 0, 0);
-                    sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ql[ds]), sc[t], 0, 0, 0);
-                }
-            }
-            // lane holds S^T[key0 + 16t + 4lq + e][row li]
-            float sv[8];
-            float bm = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int key = key0 + t * 16 + 4 * lq + e;
-                    const bool vis = rvalid && key < n_keys && key <= row_pos;       // causal
-                    sv[t * 4 + e] = vis ? sc[t][e] : -INFINITY;
-                    bm = fmaxf(bm, sv[t * 4 + e]);
-                }
-            bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
-            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-            const float m_new = fmaxf(m_run, bm);
-            float pv[8];
-            float alpha = 1.f, psum = 0.f;
-            if (m_new == -INFINITY) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pv[e] = 0.f;
-            } else {
-                alpha = __expf(m_run - m_new);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { pv[e] = __expf(sv[e] - m_new); psum += pv[e]; }
-            }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-            uint4 ph, pl;
-            split8(pv, ph, pl);
+        };
+        auto block = [&](int blk, uint4 (&kf)[2][DS], uint4 (&vf)[DT]) {
+            const int key0 = blk * 32;
             // ---- values: keys past n_keys may hold anything, even NaN patterns: zero them ----
             if (key0 + 32 > n_keys) {
 #pragma unroll
@@ -1574,42 +1544,111 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
                 }
             }
 #pragma unroll
-            for (int t = 0; t < DT; ++t) {
-                o[t][0] *= alpha; o[t][1] *= alpha; o[t][2] *= alpha; o[t][3] *= alpha;
-                const bf16x8 A = __builtin_bit_cast(bf16x8, vf[t]);
-                o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ph), o[t], 0, 0, 0);
-                o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, pl), o[t], 0, 0, 0);
+            for (int x = 0; x < NT; ++x) {
+                // ---- scores of 32 keys x 16 rows ----
+                f32x4 sc[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) {
+                        const bf16x8 A = __builtin_bit_cast(bf16x8, kf[t][ds]);
+                        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, qh[x][ds]), sc[t], 0, 0, 0);
+                        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ql[x][ds]), sc[t], 0, 0, 0);
+                    }
+                }
+                // lane holds S^T[key0 + 16t + 4lq + e][row li]
+                float sv[8];
+                float bm = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int key = key0 + t * 16 + 4 * lq + e;
+                        const bool vis = rvalid[x] && key < n_keys && key <= row_pos[x];       // causal
+                        sv[t * 4 + e] = vis ? sc[t][e] : -INFINITY;
+                        bm = fmaxf(bm, sv[t * 4 + e]);
+                    }
+                bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+                bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+                const float m_new = fmaxf(m_run[x], bm);
+                float pv[8];
+                float alpha = 1.f, psum = 0.f;
+                if (m_new == -INFINITY) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pv[e] = 0.f;
+                } else {
+                    alpha = __expf(m_run[x] - m_new);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) { pv[e] = __expf(sv[e] - m_new); psum += pv[e]; }
+                }
+                l_run[x] = l_run[x] * alpha + psum;
+                m_run[x] = m_new;
+                uint4 ph, pl;
+                split8(pv, ph, pl);
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    o[x][t][0] *= alpha; o[x][t][1] *= alpha; o[x][t][2] *= alpha; o[x][t][3] *= alpha;
+                    const bf16x8 A = __builtin_bit_cast(bf16x8, vf[t]);
+                    o[x][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, ph), o[x][t], 0, 0, 0);
+                    o[x][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8, pl), o[x][t], 0, 0, 0);
+                }
+            }
+        };
+        if constexpr (NT == 1) {
+            for (int blk = b_begin + wave; blk < b_end; blk += 4) {
+                uint4 kf[2][DS], vf[DT];
+                fetch(blk, kf, vf);
+                block(blk, kf, vf);
+            }
+        } else if (b_begin + wave < b_end) {
+            // a request past the wavefront's last block repeats that block: in bounds, never used
+            const int blk_last = b_begin + wave + ((b_end - 1 - b_begin - wave) >> 2) * 4;
+            uint4 kf0[2][DS], vf0[DT], kf1[2][DS], vf1[DT];
+            fetch(b_begin + wave, kf0, vf0);
+            for (int blk = b_begin + wave; blk < b_end; blk += 8) {
+                fetch(min(blk + 4, blk_last), kf1, vf1);
+                block(blk, kf0, vf0);
+                if (blk + 4 >= b_end) break;
+                fetch(min(blk + 8, blk_last), kf0, vf0);
+                block(blk + 4, kf1, vf1);
             }
         }
-        // ---- combine the 4 wavefronts: lane holds O^T[d = 16t + 4lq + e][row li] ----
-        l_run += __shfl_xor(l_run, 16, 64);
-        l_run += __shfl_xor(l_run, 32, 64);
-        __syncthreads();
-        if (lq == 0) { wm[wave][li] = m_run; wl[wave][li] = l_run; }
+        // ---- combine the 4 wavefronts, one tile at a time: lane holds O^T[d = 16t + 4lq + e][row li] ----
 #pragma unroll
-        for (int t = 0; t < DT; ++t)
+        for (int x = 0; x < NT; ++x) {
+            const int rbase = r0 + 16 * x;
+            if (rbase >= R) break;
+            float lr = l_run[x];
+            lr += __shfl_xor(lr, 16, 64);
+            lr += __shfl_xor(lr, 32, 64);
+            __syncthreads();
+            if (lq == 0) { wm[wave][li] = m_run[x]; wl[wave][li] = lr; }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) wo[wave][li][t * 16 + 4 * lq + e] = o[t][e];
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
-            const int r = idx / HD, d = idx % HD;
-            if (r0 + r >= R) continue;
-            const float mm = fmaxf(fmaxf(wm[0][r], wm[1][r]), fmaxf(wm[2][r], wm[3][r]));
-            float ov = 0.f, lv = 0.f;
+            for (int t = 0; t < DT; ++t)
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                const float f = (wm[w][r] == -INFINITY) ? 0.f : __expf(wm[w][r] - mm);
-                ov += wo[w][r][d] * f;
-                lv += wl[w][r] * f;
+                for (int e = 0; e < 4; ++e) wo[wave][li][t * 16 + 4 * lq + e] = o[x][t][e];
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < 16 * HD; idx += 256) {
+                const int r = idx / HD, d = idx % HD;
+                if (rbase + r >= R) continue;
+                const float mm = fmaxf(fmaxf(wm[0][r], wm[1][r]), fmaxf(wm[2][r], wm[3][r]));
+                float ov = 0.f, lv = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float f = (wm[w][r] == -INFINITY) ? 0.f : __expf(wm[w][r] - mm);
+                    ov += wo[w][r][d] * f;
+                    lv += wl[w][r] * f;
+                }
+                const int gg = (rbase + r) / q_len, qq = (rbase + r) % q_len;
+                if (direct_out) {                    // a single split of the keys: this is the attention output
+                    Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + qq) * H + kvh * G + gg) * HD + d, lv > 0.f ? ov / lv : 0.f);
+                    continue;
+                }
+                float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
+                dst[d] = ov;
+                if (d == 0) { dst[HD] = mm; dst[HD + 1] = lv; }
             }
-            const int gg = (r0 + r) / q_len, qq = (r0 + r) % q_len;
-            if (direct_out) {                        // a single split of the keys: this is the attention output
-                Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + qq) * H + kvh * G + gg) * HD + d, lv > 0.f ? ov / lv : 0.f);
-                continue;
-            }
-            float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
-            dst[d] = ov;
-            if (d == 0) { dst[HD] = mm; dst[HD + 1] = lv; }
         }
     }
 }
@@ -1775,7 +1814,11 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
     if (dtype == BS_BF16) {
         // Many query rows per head group (prompt chunks): one workgroup per tile of 16 rows and only as many key splits
         // as it takes to reach about a thousand workgroups; a single tile keeps all the splits.
-        const int n_rt = (H / KVH * q_len + 15) / 16;
+        const int n_tiles = (H / KVH * q_len + 15) / 16;
+        // two tiles per wavefront for the few-tile case of a verification pass with grouped queries (17..32 rows per kv
+        // head); prompt chunks (many tiles, a short causal horizon each) keep one tile per workgroup
+        const int nt = (n_tiles == 2) ? 2 : 1;
+        const int n_rt = (n_tiles + nt - 1) / nt;
         if (out && n_rt > 1) {
             const int want = (1024 + B * KVH * n_rt - 1) / (B * KVH * n_rt);
             n_splits = want < n_splits ? want : n_splits;
@@ -1787,14 +1830,13 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
             BS_HIP(hipEventCreate(&e0));
             BS_HIP(hipEventCreate(&e1));
         }
-        if (hd == 128)
-            BS_LAUNCH_TIMED((attn_mfma_kernel<128>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache,
-                            (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
-        else if (hd == 64)
-            BS_LAUNCH_TIMED((attn_mfma_kernel<64>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache,
-                            (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane);
+#define BS_ATTN(HD, NT) BS_LAUNCH_TIMED((attn_mfma_kernel<HD, NT>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache, \
+                                        (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane)
+        if (hd == 128) { if (nt == 2) BS_ATTN(128, 2); else BS_ATTN(128, 1); }
+        else if (hd == 64) { if (nt == 2) BS_ATTN(64, 2); else BS_ATTN(64, 1); }
         else
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
+#undef BS_ATTN
         BS_LAUNCH_CHECK();
         if (g_prof.on) {                                   // class 100: the split attention kernel (bytes known to the caller)
             g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
