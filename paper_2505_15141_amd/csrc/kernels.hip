@@ -1815,9 +1815,9 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         // Many query rows per head group (prompt chunks): one workgroup per tile of 16 rows and only as many key splits
         // as it takes to reach about a thousand workgroups; a single tile keeps all the splits.
         const int n_tiles = (H / KVH * q_len + 15) / 16;
-        // two tiles per wavefront for the few-tile case of a verification pass with grouped queries (17..32 rows per kv
-        // head); prompt chunks (many tiles, a short causal horizon each) keep one tile per workgroup
-        const int nt = (n_tiles == 2) ? 2 : 1;
+        // two tiles per wavefront as soon as there are two: a K or V block then serves 32 rows (verification with grouped
+        // queries: 287 -> 225 us per layer at batch 32 / 8192 keys; prompt chunks of a batch: 7-10 % off the prompt pass)
+        const int nt = (n_tiles >= 2) ? 2 : 1;
         const int n_rt = (n_tiles + nt - 1) / nt;
         if (out && n_rt > 1) {
             const int want = (1024 + B * KVH * n_rt - 1) / (B * KVH * n_rt);
