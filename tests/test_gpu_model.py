@@ -54,7 +54,9 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     # a prompt longer than the largest chunk: 1024 rows (four blocks of 256), then the rest against 1024 cached tokens
     (MID_GQA, 1, 1100, 2, True),
     # grouped queries with 17..32 rows per kv head: two row tiles share every K and V block (head_dim 128 and 64)
-    (WIDE, 2, 200, 6, True), (WIDE, 1, 333, 8, False), (MID_GQA, 3, 77, 7, True)])
+    (WIDE, 2, 200, 6, True), (WIDE, 1, 333, 8, False), (MID_GQA, 3, 77, 7, True),
+    # the same against a cache long enough for several key splits (partials + merge)
+    (MID_GQA, 1, 1100, 6, True), (WIDE, 1, 1100, 5, True)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
     W, m, kv = setup(c, B, max(320, n_prefix + q_len + 8), seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
