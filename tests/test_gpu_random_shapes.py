@@ -108,6 +108,7 @@ def test_lockstep_runs_on_drawn_configurations(seed):
             arm_gamma[0] = 2
         L = max(arm_gamma)
         B, P, n_gen = int(rng.integers(1, 5)), int(rng.choice([2, 5, 31, 32, 33, 40, 64])), int(rng.integers(8, 40))
+        n_gen = max(n_gen, 24 - P)                  # catch-up passes work on 16 tokens: the library wants max_len >= 16
         rseed = int(rng.integers(1, 1 << 20))
         noise = None if rng.random() < 0.6 else (0.2, 1.5, int(rng.choice([4, 8, 16])))
         if rng.random() < 0.5:
