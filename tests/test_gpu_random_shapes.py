@@ -111,6 +111,7 @@ def test_lockstep_runs_on_drawn_configurations(seed):
         n_gen = max(n_gen, 24 - P)                  # catch-up passes work on 16 tokens: the library wants max_len >= 16
         rseed = int(rng.integers(1, 1 << 20))
         noise = None if rng.random() < 0.6 else (0.2, 1.5, int(rng.choice([4, 8, 16])))
+        temperature = float(rng.choice([1.0, 1.0, 0.6, 1.7, 0.0]))       # 0: greedy mode
         if rng.random() < 0.5:
             alg_o, alg_g = UCBSpec(K, L), b.Bandit(b.BS_UCBSPEC, K, L)
         else:
@@ -118,6 +119,6 @@ def test_lockstep_runs_on_drawn_configurations(seed):
         side = torch.cuda.Stream()                  # stream capture needs a non-null stream
         with torch.cuda.stream(side):
             stats, seqs = rounds.lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_gen, seed=rseed, storage=storage,
-                                          logit_tol=tol, use_graph=bool(rng.random() < 0.5), noise=noise)
+                                          logit_tol=tol, use_graph=bool(rng.random() < 0.5), noise=noise, temperature=temperature)
         side.synchronize()
         assert stats["max_logit_err"] < tol and all(len(s) == P + n_gen for s in seqs), (seed, case, stats)
