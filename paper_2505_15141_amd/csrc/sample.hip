@@ -427,30 +427,51 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const T* __restrict__ p_
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int ngroups = (V + GE - 1) / GE;
     const bool vec = (reinterpret_cast<uintptr_t>(row) & 15) == 0;
-    float m = -INFINITY, sum = 0.f;
-    auto online = [&](const Raw<T>& raw) {
+    // Arithmetic per logit is what bounds this kernel as much as the bytes do (a compute unit retires 64 lane-operations
+    // per cycle, and 17 rows of 32000 logits per sequence are 2100 logits per compute unit and sequence), so the inner
+    // loop is kept to: widen, max (on the raw values: the scale is positive), one fused multiply-add into the base-2
+    // exponent, v_exp_f32, add.  Running maximum mr in raw units; the sum is rescaled once per batch of loads.
+    const float c2 = inv_temp * 1.4426950408889634f;             // logit -> base-2 exponent
+    float mr = -INFINITY, sum = 0.f;
+    auto raw_max = [&](const Raw<T>& raw, float cur) {
         float v[GE];
-        expand(raw, inv_temp, v);
-        float gm = v[0];
+        expand(raw, 1.0f, v);
 #pragma unroll
-        for (int e = 1; e < GE; ++e) gm = fmaxf(gm, v[e]);
-        const float mn = fmaxf(m, gm);
-        if (mn == -INFINITY) return;
+        for (int e = 0; e < GE; ++e) cur = fmaxf(cur, v[e]);
+        return cur;
+    };
+    auto accumulate = [&](const Raw<T>& raw, float off) {       // off = -mr * c2
+        float v[GE];
+        expand(raw, 1.0f, v);
         float acc = 0.f;
 #pragma unroll
-        for (int e = 0; e < GE; ++e) acc += __expf(v[e] - mn);
-        sum = sum * __expf(m - mn) + acc;
-        m = mn;
+        for (int e = 0; e < GE; ++e) acc += __builtin_amdgcn_exp2f(fmaf(v[e], c2, off));
+        sum += acc;
+    };
+    auto rebase = [&](float mn) {                               // new running maximum mn >= mr (raw units)
+        if (mn > mr) {
+            sum = (mr == -INFINITY) ? 0.f : sum * __builtin_amdgcn_exp2f((mr - mn) * c2);
+            mr = mn;
+        }
     };
     int g = tid;
     if (vec && V % GE == 0) {
         for (; g + 3 * 256 < ngroups; g += 4 * 256) {
             Raw<T> a0 = load_raw_vec(row, g), a1 = load_raw_vec(row, g + 256), a2 = load_raw_vec(row, g + 512),
                    a3 = load_raw_vec(row, g + 768);
-            online(a0); online(a1); online(a2); online(a3);
+            rebase(raw_max(a3, raw_max(a2, raw_max(a1, raw_max(a0, mr)))));
+            if (mr != -INFINITY) {
+                const float off = -mr * c2;
+                accumulate(a0, off); accumulate(a1, off); accumulate(a2, off); accumulate(a3, off);
+            }
         }
     }
-    for (; g < ngroups; g += 256) online(load_raw(row, g, V, vec));
+    for (; g < ngroups; g += 256) {
+        const Raw<T> a0 = load_raw(row, g, V, vec);
+        rebase(raw_max(a0, mr));
+        if (mr != -INFINITY) accumulate(a0, -mr * c2);
+    }
+    const float m = (mr == -INFINITY) ? -INFINITY : mr * inv_temp;     // the statistics are in natural-log units
     const float bm = wave_max(m);
     if (lane == 0) red[0][wid] = bm;
     __syncthreads();
