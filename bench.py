@@ -295,6 +295,8 @@ def main():
                          "{0,2,4,6,8} with the measured tokens/s of the round as the reward (bs_throughput_reward)")
     ap.add_argument("--canonical-rounds", type=int, default=32, help="rounds of gamma = 0 (canonical decoding) timed as the baseline")
     ap.add_argument("--no-multi-draft", action="store_true", help="skip the stage with the 8B-shaped target and three draft models")
+    ap.add_argument("--only-multi-draft", action="store_true",
+                    help="run only that stage and print its JSON (for profiling it by itself); not the benchmark line")
     ap.add_argument("--pmc-mode", action="store_true",
                     help="for `rocprofv3 --pmc` runs: only the eager, event-timed rounds are executed, so the 16-row GEMM "
                          "dispatches of the counter file are exactly the launches whose algorithmic bytes are printed")
@@ -311,6 +313,10 @@ def main():
     from paper_2505_15141_amd import binding as bs, synth
 
     torch.cuda.set_device(0)
+    if args.only_multi_draft:
+        print(json.dumps({"stage": "rounds_b32_ctx8192_three_drafts",
+                          **multi_draft_rounds_stage(bs, synth, torch, np, torch.cuda.Stream())}))
+        return
     tc, dc = synth.LLAMA7B_TARGET, synth.LLAMA7B_DRAFT
     by_throughput = args.reward == "throughput"
     gammas = [0, 2, 4, 6, 8] if by_throughput else [2, 4, 6, 8]     # the bandit's arms
