@@ -1812,8 +1812,8 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
     const float scale = 1.0f / sqrtf((float)hd);
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
-        // Many query rows per head group (prompt chunks): one workgroup per tile of 16 rows and only as many key splits
-        // as it takes to reach about a thousand workgroups; a single tile keeps all the splits.
+        // Many query rows per head group (prompt chunks): one workgroup per group of row tiles and only as many key
+        // splits as it takes to reach about a thousand workgroups; a single group keeps all the splits.
         const int n_tiles = (H / KVH * q_len + 15) / 16;
         // two tiles per wavefront as soon as there are two: a K or V block then serves 32 rows (verification with grouped
         // queries: 287 -> 225 us per layer at batch 32 / 8192 keys; prompt chunks of a batch: 7-10 % off the prompt pass)
