@@ -76,3 +76,23 @@ class EXP3Spec:
         self.cum[arm] += (self.L + 1.0 - float(y)) / (self.L * p[arm])
         self.t += 1
         self.last_p = None
+
+
+def batch_reward(ys):
+    """One bandit for a batch (one arm per round for all sequences, Alg. 3): the round's reward is the mean accepted
+    length over the sequences that took part (y >= 1); sequences that are done report 0 and are left out."""
+    active = [float(y) for y in ys if y > 0]
+    assert active, "no sequence took part in the round"
+    return sum(active) / len(active)
+
+
+def throughput_reward(tokens, seconds, canonical_seconds, L):
+    """Throughput as the reward (Sec. 6, the speculation-length experiment, arms gamma in {0..L} with gamma = 0 =
+    canonical decoding).  The paper gives no formula: parity unpinned by the paper.  Reading used here: a target pass
+    emits at most L+1 tokens, so (L+1) / canonical_seconds bounds every arm's rate, canonical_seconds being the duration
+    of a gamma = 0 round; the round's rate tokens/seconds as a fraction of that bound, capped at 1, is mapped affinely
+    onto [1, L+1], the range the confidence radius of Alg. 4 and the loss of Alg. 5 assume for y."""
+    assert L >= 1 and tokens >= 0 and seconds > 0 and canonical_seconds > 0
+    rate = float(tokens) / float(seconds)
+    bound = (L + 1.0) / float(canonical_seconds)
+    return 1.0 + L * min(1.0, rate / bound)

@@ -58,7 +58,7 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
-def forward(cfg, W, tokens, storage="f32", return_hidden=False):
+def forward(cfg, W, tokens, storage="f32", return_hidden=False, last_rows=None, return_cache=False):
     """Logits [n, V] (fp64) for every position of one token sequence.
 
     cfg: dict(n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ff, vocab,
@@ -66,6 +66,12 @@ def forward(cfg, W, tokens, storage="f32", return_hidden=False):
     W:   mapping name -> array: 'embed', 'final_norm', 'lm_head' and per layer l
          'l{l}.attn_norm', 'l{l}.wq', 'l{l}.wk', 'l{l}.wv', 'l{l}.wo',
          'l{l}.ffn_norm', 'l{l}.w_gate', 'l{l}.w_up', 'l{l}.w_down'.
+    last_rows=r: only the logits of the last r positions are wanted, [r, V].  Those rows depend on every position
+         through the keys and values, so all layers but the last run on all positions; in the last layer the keys
+         and values are still formed for all positions, while queries, attention output, feed-forward, final norm
+         and LM head are evaluated for the last r rows only.  Same values as forward(...)[-r:].
+    return_cache: also return the per-layer (k, v) exactly as the attention used them (after RoPE and storage
+         rounding), each [n, n_kv_heads, head_dim]: what a KV cache of this storage dtype holds.
     """
     tokens = np.asarray(tokens, dtype=np.int64)
     n = tokens.shape[0]
@@ -74,33 +80,44 @@ def forward(cfg, W, tokens, storage="f32", return_hidden=False):
     eps = cfg.get("norm_eps", 1e-5)
     f64 = lambda a: np.asarray(a, dtype=np.float64)
     pos = np.arange(n)
-    x = f64(W["embed"])[tokens]                                     # residual stream
+    x = f64(W["embed"][tokens])                                     # residual stream
     causal = np.tril(np.ones((n, n), dtype=bool))
+    first = 0                                                       # x holds rows first..n-1
+    cache = []
     for l in range(cfg["n_layers"]):
         g = lambda name: f64(W[f"l{l}.{name}"])
         h = rmsnorm(x, g("attn_norm"), eps)
-        q = (h @ g("wq").T).reshape(n, H, hd)
         k = (h @ g("wk").T).reshape(n, KVH, hd)
         v = (h @ g("wv").T).reshape(n, KVH, hd)
-        q = rope(q, pos, base)
         k = _store(rope(k, pos, base), storage)
         v = _store(v, storage)
-        att = np.empty((n, H, hd))
+        cache.append((k, v))
+        if last_rows is not None and l == cfg["n_layers"] - 1:      # from here on only the wanted rows
+            first = n - last_rows
+            x, h = x[first:], h[first:]
+        q = (h @ g("wq").T).reshape(n - first, H, hd)
+        q = rope(q, pos[first:], base)
+        att = np.empty((n - first, H, hd))
         for head in range(H):
             kvh = head // (H // KVH)
             s = (q[:, head, :] @ k[:, kvh, :].T) / np.sqrt(hd)
-            s = np.where(causal, s, -np.inf)
+            s = np.where(causal[first:], s, -np.inf)
             s = s - s.max(axis=-1, keepdims=True)
             p = np.exp(s)
             p = p / p.sum(axis=-1, keepdims=True)
             att[:, head, :] = p @ v[:, kvh, :]
-        att = att.reshape(n, H * hd)
+        att = att.reshape(n - first, H * hd)
         x = x + att @ g("wo").T
         h = rmsnorm(x, g("ffn_norm"), eps)
         a = silu(h @ g("w_gate").T) * (h @ g("w_up").T)
         x = x + a @ g("w_down").T
+    if last_rows is not None and first == 0:                        # no layers: the embedding rows themselves
+        x = x[n - last_rows:]
     h = rmsnorm(x, f64(W["final_norm"]), eps)
     logits = h @ f64(W["lm_head"]).T
+    out = (logits,)
     if return_hidden:
-        return logits, x
-    return logits
+        out += (x,)
+    if return_cache:
+        out += (cache,)
+    return out if len(out) > 1 else logits

@@ -55,7 +55,7 @@ def inverse_cdf(weights, u):
 
 def draw_is_valid(weights, u, token, rel_tol):
     """Widened-bin rule: `token` is an acceptable inverse-CDF result for (weights, u)
-    if u*total lies within rel_tol*total of the token's CDF bin [C_{k-1}, C_k]."""
+    if it has positive weight and u*total lies within rel_tol*total of its CDF bin [C_{k-1}, C_k]."""
     w = np.asarray(weights, dtype=np.float64)
     cdf = np.cumsum(w)
     total = cdf[-1]
@@ -63,7 +63,7 @@ def draw_is_valid(weights, u, token, rel_tol):
     hi = cdf[token]
     x = u * total
     tol = rel_tol * total
-    return bool(w[token] >= 0 and lo - tol <= x <= hi + tol)
+    return bool(w[token] > 0 and lo - tol <= x <= hi + tol)
 
 
 def spec_sample(p_logits, q_logits, draft_tokens, u_accept, u_final, temperature=1.0):

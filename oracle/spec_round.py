@@ -29,7 +29,7 @@ def draft_propose(cfg, W, tokens, gamma, seed, b, t, temperature=1.0, storage="f
     toks = list(int(x) for x in tokens)
     out_tok, out_logits, us, probs = [], [], [], []
     for i in range(gamma):
-        logits = forward(cfg, W, toks, storage)[-1]
+        logits = forward(cfg, W, toks, storage, last_rows=1)[-1]
         if noise_sigma > 0.0:
             logits = logits + noise_sigma * philox.noise_normals(seed, b, t, i, cfg["vocab"])
         u = philox.draft_uniform(seed, b, t, i)
@@ -48,7 +48,7 @@ def spec_round(target, draft, tokens, gamma, seed, b, t, temperature=1.0, storag
     d_tok, d_logits, d_u, d_probs = draft_propose(draft[0], draft[1], tokens, gamma, seed, b, t,
                                                   temperature, storage, noise_sigma)
     full = list(int(x) for x in tokens) + [int(x) for x in d_tok]
-    t_logits = forward(target[0], target[1], full, storage)[n - 1:n + gamma]    # gamma+1 rows
+    t_logits = forward(target[0], target[1], full, storage, last_rows=gamma + 1)        # rows n-1 .. n+gamma-1
     u_acc = np.array([philox.accept_uniform(seed, b, t, i) for i in range(gamma)])
     u_fin = philox.final_uniform(seed, b, t)
     r = spec_sample(t_logits, d_logits, d_tok, u_acc, u_fin, temperature)
@@ -110,6 +110,6 @@ def canonical_decode(cfg, W, tokens, n_generate, uniforms, temperature=1.0, stor
     """Alg. 1 with a token budget: x_t ~ P(. | prefix), one model pass per token."""
     toks = list(int(x) for x in tokens)
     for i in range(n_generate):
-        k, _ = draw_from_logits(forward(cfg, W, toks, storage)[-1], uniforms[i], temperature)
+        k, _ = draw_from_logits(forward(cfg, W, toks, storage, last_rows=1)[-1], uniforms[i], temperature)
         toks.append(k)
     return toks

@@ -23,8 +23,10 @@ def make(cfg, seed):
 CFG = dict(n_layers=2, d_model=24, n_heads=4, n_kv_heads=2, head_dim=6, d_ff=40, vocab=17)
 
 
-def torch_forward(cfg, W, tokens):
-    """Same network assembled from torch library routines in fp64, RoPE in complex form."""
+def torch_forward(cfg, W, tokens, bf16_cache=False, caches=None):
+    """Same network assembled from torch library routines in fp64, RoPE in complex form.  bf16_cache: the rotated keys
+    and the values pass through the library's own bfloat16 conversion (what a bf16 KV cache holds); nothing else does."""
+    to_cache = (lambda t: t.to(torch.bfloat16).to(torch.float64)) if bf16_cache else (lambda t: t)
     T = lambda a: torch.tensor(np.asarray(a), dtype=torch.float64)
     n, H, KVH, hd = len(tokens), cfg["n_heads"], cfg["n_kv_heads"], cfg["head_dim"]
     x = F.embedding(torch.tensor(tokens), T(W["embed"]))
@@ -37,8 +39,12 @@ def torch_forward(cfg, W, tokens):
         g = lambda k: T(W[f"l{l}.{k}"])
         h = F.rms_norm(x, (x.shape[-1],), g("attn_norm"), 1e-5)
         q = rot(F.linear(h, g("wq")).reshape(n, H, hd)).transpose(0, 1)
-        k = rot(F.linear(h, g("wk")).reshape(n, KVH, hd)).transpose(0, 1).repeat_interleave(H // KVH, 0)
-        v = F.linear(h, g("wv")).reshape(n, KVH, hd).transpose(0, 1).repeat_interleave(H // KVH, 0)
+        k = to_cache(rot(F.linear(h, g("wk")).reshape(n, KVH, hd)))
+        v = to_cache(F.linear(h, g("wv")).reshape(n, KVH, hd))
+        if caches is not None:
+            caches.append((k.numpy().copy(), v.numpy().copy()))
+        k = k.transpose(0, 1).repeat_interleave(H // KVH, 0)
+        v = v.transpose(0, 1).repeat_interleave(H // KVH, 0)
         a = F.scaled_dot_product_attention(q[None], k[None], v[None], is_causal=True)[0].transpose(0, 1).reshape(n, H * hd)
         x = x + F.linear(a, g("wo"))
         h = F.rms_norm(x, (x.shape[-1],), g("ffn_norm"), 1e-5)
@@ -87,6 +93,44 @@ def test_pieces_against_closed_forms():
     # bf16 rounding agrees with the library conversion, including ties-to-even
     v = np.array([1.00390625, 1.01171875, 3.14159, -0.02, 1e-3, 65504.0, 0.0])
     assert np.array_equal(round_bf16(v), torch.tensor(v, dtype=torch.float32).to(torch.bfloat16).double().numpy())
+
+
+@pytest.mark.parametrize("kvh", [2, 4])
+def test_bf16_storage_rounds_exactly_the_rotated_keys_and_the_values(kvh):
+    """The rounding points of storage="bf16": the cache rows are bf16(rope(k)) and bf16(v), bit for bit the library's
+    conversion of the unrounded values, and the logits equal the library composition that rounds there and nowhere
+    else.  Rounding anywhere else (keys before the rotation, queries, attention output, no rounding of v) moves the
+    logits by 1e-3 and more, far outside the 1e-9 of this comparison."""
+    c = dict(CFG, n_kv_heads=kvh)
+    W = {k: round_bf16(v) for k, v in make(c, 6).items()}
+    toks = [3, 1, 4, 1, 5, 9, 2, 6, 5, 3, 16, 0, 7]
+    ref_caches = []
+    ref = torch_forward(c, W, toks, bf16_cache=True, caches=ref_caches)
+    out, caches = forward(c, W, toks, storage="bf16", return_cache=True)
+    assert np.allclose(out, ref, rtol=1e-9, atol=1e-9)
+    for (k, v), (rk, rv) in zip(caches, ref_caches):
+        assert np.array_equal(k, rk) and np.array_equal(v, rv)
+        assert np.array_equal(k, round_bf16(k)) and np.array_equal(v, round_bf16(v))          # on the bf16 grid
+    # first layer by hand: the cache row of position p is bf16(rope(h_p wk^T, p)) and bf16(h_p wv^T)
+    x0 = np.asarray(W["embed"], dtype=np.float64)[toks]
+    h0 = rmsnorm(x0, W["l0.attn_norm"], 1e-5)
+    k0 = rope((h0 @ W["l0.wk"].T).reshape(len(toks), kvh, 6), np.arange(len(toks)), 10000.0)
+    assert np.array_equal(caches[0][0], round_bf16(k0))
+    assert np.array_equal(caches[0][1], round_bf16((h0 @ W["l0.wv"].T).reshape(len(toks), kvh, 6)))
+    # and each wrong rounding point is visible at this tolerance
+    exact = forward(c, W, toks, storage="f32")
+    assert np.max(np.abs(exact - out)) > 1e-5
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_last_rows_restriction_gives_the_same_rows(storage):
+    for c, seed in ((CFG, 7), (dict(CFG, n_kv_heads=4, n_layers=3), 8), (dict(CFG, n_layers=1), 9), (dict(CFG, n_layers=0), 10)):
+        W = make(c, seed)
+        toks = [3, 1, 4, 1, 5, 9, 2, 6, 5, 3, 16, 11]
+        full = forward(c, W, toks, storage)
+        for r in (1, 3, len(toks)):
+            part = forward(c, W, toks, storage, last_rows=r)
+            assert part.shape == (r, c["vocab"]) and np.allclose(part, full[-r:], rtol=1e-12, atol=1e-12)
 
 
 def test_bf16_storage_mode_stays_close_to_exact_mode():
