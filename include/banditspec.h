@@ -99,14 +99,20 @@ int bs_bandit_update(bs_bandit* b, int arm, double y); /* arm must be the last s
 int bs_bandit_probs(bs_bandit* b, double* host_out_K);
 /* pulls n_i, and per arm sum of y (UCBSpec) or cumulative estimated loss (EXP3Spec); rounds so far */
 int bs_bandit_stats(bs_bandit* b, double* host_n_K, double* host_sum_K, int64_t* rounds_out);
-/* Throughput as the reward (Sec. 6, second experiment: arms gamma in {0..L} incl. canonical decoding, "the current
- * throughput as the reward"; the paper prints no formula, this normalisation is this library's and has no parity pin):
+/* Throughput as the reward (Sec. 6, second experiment: arms gamma in {0..L} incl. canonical decoding, the reward is the
+ * round's throughput; the paper prints no formula, this normalisation is this library's and has no parity pin):
  *   y = 1 + L * min(1, (tokens / seconds) / ((L + 1) / canonical_seconds))
  * tokens = mean tokens the round emitted per sequence, seconds = its duration, canonical_seconds = duration of a
  * gamma = 0 round (one target pass).  The reference rate (L+1 tokens per target pass) bounds any arm, so y lies in
  * [1, L+1], the range bs_bandit_update and the confidence radius of Alg. 4 expect.
  * Errors: BS_EINVAL (NULL, non-positive times, negative tokens, L < 1). */
 int bs_throughput_reward(double tokens, double seconds, double canonical_seconds, int L, double* y_out);
+/* Reward of one round for a batch that shares one bandit (Alg. 3 with one arm per round for all sequences): the mean of
+ * the accepted lengths y = host_n_emitted[b] over the sequences that took part in the round (entries > 0; a sequence
+ * already at its goal, or skipped, reports 0 and is left out), so the value stays in [1, L+1].
+ * host_n_emitted [B] int32 HOST memory (the copy of bs_spec_round's dev_n_emitted); n_active_out may be NULL.
+ * Errors: BS_EINVAL (NULL, B < 1, a negative entry), BS_ESTATE (no entry > 0: there is no reward to feed back). */
+int bs_batch_reward(const int32_t* host_n_emitted, int B, double* y_out, int* n_active_out);
 
 /* ------------------------------------------------------------------------------------------------
  * Models (Sec. 2: a model is the conditional distribution softmax(logits/T); the network itself is
@@ -168,7 +174,7 @@ int bs_kv_destroy(bs_kv* kv);
 size_t bs_forward_workspace_bytes(const bs_model_cfg* cfg, int B, int max_q_len, int max_len);
 
 /* ------------------------------------------------------------------------------------------------
- * Target verification forward (App. A, "calculate P(x~_i | pt, x~_{1:i-1}) for all i in parallel"):
+ * Target verification forward (App. A, the step that scores all gamma+1 positions of the draft block in one pass):
  * runs the model over q_len query tokens per sequence against its KV cache.
  *   query j of sequence b sits at position pos = kv_len[b] + j, attends to cache positions
  *   0..pos (causal), and its K/V are written to the cache at pos (the cache length itself is the
@@ -198,7 +204,11 @@ int bs_prefill(const bs_model* m, const bs_kv* kv, const int32_t* dev_tokens, in
  *   dev_tokens [B, max_len] int32   the growing prompts (Alg. 3, pt_t)
  *   dev_total_len [B] int32         tokens per sequence; invariant: the target cache holds total_len-1
  *   dev_goal_len [B] int32          generation stops here (tokens beyond it are dropped; the reported
- *                                   accepted length is not truncated)
+ *                                   accepted length is not truncated).  A round of speculation length gamma needs
+ *                                   total_len + gamma <= max_len (its verification pass appends gamma+1 keys to a cache
+ *                                   that holds total_len-1); a sequence for which that fails takes no part in the round:
+ *                                   nothing is read or written for it, n_emitted is 0 and bit 8 of bs_round_status is
+ *                                   set.  goal_len <= max_len - L therefore lets every arm run until the goal.
  * Random numbers: Philox(seed; b, t, slot, purpose) with t the device round counter (bs_round_reset).
  * ---------------------------------------------------------------------------------------------- */
 typedef struct {
@@ -255,6 +265,14 @@ int bs_draft_propose(bs_round* r, int arm, int32_t* dev_draft_tokens, float* dev
  *  dev_n_emitted [B] int32 out: y = tau + 1 (the reward of Sec. 3; 0 for sequences already at goal)
  * The caller copies dev_n_emitted to the host and synchronises before bs_bandit_update. */
 int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emitted, void* stream);
+/* Device status since the last bs_round_reset, OR of:
+ *   1  a forward pass left out a sequence whose query rows would have run past max_len
+ *   2  a token id outside [0, vocab) was replaced by 0
+ *   4  total_len < 2 or > max_len at the start of a round (sequence left out)
+ *   8  a sequence still generating had total_len + gamma > max_len (left out, see dev_goal_len above)
+ * Copies the word to *host_out (HOST memory) and WAITS for `stream`: this call synchronises.  Not for use while the
+ * stream is being captured. */
+int bs_round_status(bs_round* r, int32_t* host_out, void* stream);
 /* Views into the round workspace for parity checks (valid after the round's stream work is done):
  * target logits [B, gamma+1, V] f32, draft logits [B, gamma, V] f32, draft tokens [B, gamma] int32,
  * margins [B, gamma] f32 of the most recent round. */

@@ -68,6 +68,7 @@ _sig("bs_bandit_update", C.c_int, vp, C.c_int, f64)
 _sig("bs_bandit_probs", C.c_int, vp, C.POINTER(f64))
 _sig("bs_bandit_stats", C.c_int, vp, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_int64))
 _sig("bs_throughput_reward", C.c_int, f64, f64, f64, C.c_int, C.POINTER(f64))
+_sig("bs_batch_reward", C.c_int, C.POINTER(i32), C.c_int, C.POINTER(f64), C.POINTER(C.c_int))
 _sig("bs_model_create", C.c_int, C.POINTER(ModelCfg), C.POINTER(ModelWeights), C.POINTER(vp))
 _sig("bs_model_destroy", C.c_int, vp)
 _sig("bs_model_packed_bytes", sz, C.POINTER(ModelCfg))
@@ -83,6 +84,7 @@ _sig("bs_round_create", C.c_int, C.POINTER(RoundCfg), C.POINTER(vp))
 _sig("bs_round_destroy", C.c_int, vp)
 _sig("bs_round_reset", C.c_int, vp, u32, vp)
 _sig("bs_spec_round", C.c_int, vp, C.c_int, vp, vp, vp)
+_sig("bs_round_status", C.c_int, vp, C.POINTER(i32), vp)
 _sig("bs_draft_propose", C.c_int, vp, C.c_int, vp, vp, vp)
 _sig("bs_profile_enable", C.c_int, C.c_int)
 _sig("bs_profile_collect", C.c_int, C.c_int, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_longlong))
@@ -146,6 +148,16 @@ def throughput_reward(tokens, seconds, canonical_seconds, L):
     y = f64()
     check(lib.bs_throughput_reward(tokens, seconds, canonical_seconds, L, C.byref(y)))
     return y.value
+
+
+def batch_reward(n_emitted):
+    """bs_batch_reward: mean accepted length over the sequences that took part in the round.
+    n_emitted: HOST int32 values (CPU tensor, numpy array or list).  Returns (y, n_active)."""
+    vals = [int(v) for v in (n_emitted.tolist() if hasattr(n_emitted, "tolist") else n_emitted)]
+    arr = (i32 * len(vals))(*vals)
+    y, n = f64(), C.c_int()
+    check(lib.bs_batch_reward(arr, len(vals), C.byref(y), C.byref(n)))
+    return y.value, n.value
 
 
 class Bandit:
@@ -318,6 +330,12 @@ class Round:
     def spec_round(self, arm, stream=None):
         check(lib.bs_spec_round(self.h, arm, ptr(self.emitted), ptr(self.n_emitted), stream_ptr(stream)))
         return self.emitted, self.n_emitted
+
+    def status(self, stream=None):
+        """bs_round_status: the device status word since the last reset (synchronises the stream)."""
+        w = i32()
+        check(lib.bs_round_status(self.h, C.byref(w), stream_ptr(stream)))
+        return w.value
 
     def draft_propose(self, arm, stream=None):
         """bs_draft_propose: (draft_tokens [B,gamma] int32, draft_logits [B,gamma,V] float32) without verification or commit."""

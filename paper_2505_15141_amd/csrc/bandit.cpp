@@ -134,3 +134,19 @@ extern "C" __attribute__((visibility("default"))) int bs_throughput_reward(doubl
     *y_out = 1.0 + (double)L * frac;
     return BS_OK;
 }
+
+// One bandit per batch: the reward of a round is the mean accepted length over the sequences that took part in it.
+extern "C" __attribute__((visibility("default"))) int bs_batch_reward(const int32_t* host_n_emitted, int B, double* y_out, int* n_active_out) {
+    BS_REQUIRE(host_n_emitted && y_out, BS_EINVAL, "bs_batch_reward: NULL argument");
+    BS_REQUIRE(B >= 1, BS_EINVAL, "bs_batch_reward: B=%d", B);
+    long long sum = 0;
+    int active = 0;
+    for (int b = 0; b < B; ++b) {
+        BS_REQUIRE(host_n_emitted[b] >= 0, BS_EINVAL, "bs_batch_reward: n_emitted[%d]=%d is negative", b, host_n_emitted[b]);
+        if (host_n_emitted[b] > 0) { sum += host_n_emitted[b]; ++active; }
+    }
+    if (n_active_out) *n_active_out = active;
+    BS_REQUIRE(active > 0, BS_ESTATE, "bs_batch_reward: no sequence took part in the round (all at their goal, or skipped)");
+    *y_out = (double)sum / (double)active;
+    return BS_OK;
+}

@@ -494,9 +494,12 @@ __global__ void noise_kernel(float* __restrict__ rows, size_t row_stride, int V,
         if (4 * g + e < V) row[4 * g + e] += sg * z[e];
 }
 
-// Start of a round: gather the draft's first two inputs and the target's first query token.
+// Start of a round: gather the draft's first two inputs and the target's first query token.  A sequence takes part
+// only if the whole round fits its caches: the verification pass writes keys at total-1 .. total-1+gamma and the draft
+// steps stay below that, so total + gamma <= max_len.  One that does not fit is skipped by every forward pass of the
+// round (cache length max_len), emits nothing and commits nothing; status bit 8 says so if it was still generating.
 __global__ void round_begin_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ total_len,
-                                   const int32_t* __restrict__ goal_len, int B, int max_len, int tq_stride,
+                                   const int32_t* __restrict__ goal_len, int B, int max_len, int gamma, int tq_stride,
                                    int32_t* __restrict__ q_draft2, int32_t* __restrict__ q_target,
                                    int32_t* __restrict__ kvlen_draft, int32_t* __restrict__ kvlen_target,
                                    int32_t* __restrict__ active, int32_t* __restrict__ status,
@@ -509,15 +512,18 @@ __global__ void round_begin_kernel(const int32_t* __restrict__ tokens, const int
         const int generated = max(total - (prompt_len ? prompt_len[b] : 0), 0);
         sigma[b] = (period > 0 && ((generated / period) & 1)) ? sigma_b : sigma_a;
     }
-    const bool ok = total >= 2 && total <= max_len;
-    if (!ok) atomicOr(status, 4);
+    const bool sane = total >= 2 && total <= max_len;
+    const bool ok = sane && total + gamma <= max_len;
+    const bool wants = goal_len == nullptr || total < goal_len[b];
+    if (!sane) atomicOr(status, 4);
+    else if (!ok && wants) atomicOr(status, 8);
     const int t1 = ok ? tokens[(size_t)b * max_len + total - 1] : 0;
     const int t0 = ok ? tokens[(size_t)b * max_len + total - 2] : 0;
     q_draft2[2 * b] = t0; q_draft2[2 * b + 1] = t1;
     q_target[(size_t)b * tq_stride] = t1;
     kvlen_draft[b] = ok ? total - 2 : max_len;        // max_len: makes the forward skip the sequence
     kvlen_target[b] = ok ? total - 1 : max_len;
-    active[b] = ok && (goal_len == nullptr || total < goal_len[b]);
+    active[b] = ok && wants;
 }
 
 // End of a round (Alg. 3: pt_t = concat(pt_{t-1}, x_t); reward y = len(x_t)).
@@ -649,7 +655,7 @@ static int enqueue_draft(bs_round* r, int arm, hipStream_t s) {
     const bool noisy = c.noise_sigma[0] > 0.f || c.noise_sigma[1] > 0.f;
     int rc;
     hipLaunchKernelGGL(bs::round_begin_kernel, dim3((B + 127) / 128), dim3(128), 0, s, c.dev_tokens, c.dev_total_len,
-                       c.dev_goal_len, B, c.max_len, gamma + 1, w.q_draft2, w.q_target, w.kvlen_draft, w.kvlen_target,
+                       c.dev_goal_len, B, c.max_len, gamma, gamma + 1, w.q_draft2, w.q_target, w.kvlen_draft, w.kvlen_target,
                        w.active, w.status, c.dev_prompt_len, c.noise_sigma[0], c.noise_sigma[1], c.noise_period, w.sigma);
     BS_LAUNCH_CHECK();
     for (int i = 0; i < gamma; ++i) {
@@ -749,6 +755,17 @@ extern "C" __attribute__((visibility("default"))) int bs_draft_propose(bs_round*
     const int gamma = r->arm_gamma[arm], B = r->cfg.B, V = r->cfg.target->cfg.vocab;
     if (dev_draft_tokens) BS_HIP(hipMemcpyAsync(dev_draft_tokens, r->ws.draft_tokens, (size_t)B * gamma * 4, hipMemcpyDeviceToDevice, s));
     if (dev_draft_logits) BS_HIP(hipMemcpyAsync(dev_draft_logits, r->ws.draft_logits, (size_t)B * gamma * V * 4, hipMemcpyDeviceToDevice, s));
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_round_status(bs_round* r, int32_t* host_out, void* stream) {
+    BS_REQUIRE(r && host_out, BS_EINVAL, "bs_round_status: NULL argument");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    int32_t words[2] = {0, 0};
+    BS_HIP(hipMemcpyAsync(&words[0], r->ws.status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    BS_HIP(hipMemcpyAsync(&words[1], r->ws.fwd, sizeof(int32_t), hipMemcpyDeviceToHost, s));      // the forward passes' word
+    BS_HIP(hipStreamSynchronize(s));
+    *host_out = words[0] | words[1];
     return BS_OK;
 }
 

@@ -381,7 +381,9 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
     float before = base;
     for (int wv = 0; wv < wid; ++wv) before += sh.wave_tot[wv];
     incl += before;
-    const bool hit = incl > thr;
+    // The shuffled prefix is not monotone in fp32 (every lane sums in its own order), so an empty group can be the first
+    // whose prefix exceeds thr: only groups that carry mass may be hit, and below only tokens that do.
+    const bool hit = incl > thr && gs > 0.f;
     const uint64_t mhit = __ballot(hit);
     const uint64_t mpos = __ballot(gs > 0.f);
     if (lane == 0) {
@@ -403,7 +405,7 @@ __device__ RowResult process_row(const T* __restrict__ p, const T* __restrict__ 
         for (int e = 0; e < GE; ++e) {
             run += w[e];
             if (w[e] > 0.f) lastpos = e;
-            if (pick < 0 && !forced && run > thr) pick = e;
+            if (pick < 0 && !forced && run > thr && w[e] > 0.f) pick = e;
         }
         if (pick < 0) pick = lastpos;
         sh.ibcast[0] = (tid + kstar * ST) * GE + pick;
@@ -704,21 +706,31 @@ extern "C" __attribute__((visibility("default"))) size_t bs_spec_sample_workspac
     return bs::spec_scratch_bytes(B, gamma);
 }
 
+// Argument checks shared by the two entry points (everything but the scratch memory).
+static int check_spec_sample_args(const char* who, const void* dev_target_logits, const void* dev_draft_logits,
+                                  const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype, float temperature,
+                                  const int32_t* dev_accept_len, const int32_t* dev_next_token) {
+    BS_REQUIRE(B >= 0 && gamma >= 0, BS_EINVAL, "%s: B=%d gamma=%d must be >= 0", who, B, gamma);
+    BS_REQUIRE(V >= 1 && V <= (1 << 20), BS_ESHAPE, "%s: V=%d outside [1, 2^20]", who, V);
+    BS_REQUIRE(gamma <= 512, BS_ESHAPE, "%s: gamma=%d > 512", who, gamma);
+    BS_REQUIRE((long long)B * (gamma + 1) < (1LL << 31), BS_ESHAPE, "%s: B*(gamma+1) overflows", who);
+    BS_REQUIRE(dtype == BS_F32 || dtype == BS_BF16, BS_EDTYPE, "%s: dtype %d", who, dtype);
+    BS_REQUIRE(temperature >= 0.f && isfinite(temperature), BS_EINVAL, "%s: temperature %g", who, (double)temperature);
+    if (B == 0) return BS_OK;
+    BS_REQUIRE(dev_target_logits && dev_accept_len && dev_next_token, BS_EINVAL, "%s: NULL pointer", who);
+    BS_REQUIRE(gamma == 0 || (dev_draft_tokens && (dev_draft_logits || temperature == 0.f)), BS_EINVAL, "%s: NULL draft input", who);
+    return BS_OK;
+}
+
 extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
                               const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype, float temperature,
                               const float* dev_uniforms, uint64_t seed, uint32_t round, int32_t* dev_accept_len,
                               int32_t* dev_next_token, float* dev_margins, void* dev_workspace,
                               size_t workspace_bytes, void* stream) {
-    BS_REQUIRE(B >= 0 && gamma >= 0, BS_EINVAL, "bs_spec_sample: B=%d gamma=%d must be >= 0", B, gamma);
-    BS_REQUIRE(V >= 1 && V <= (1 << 20), BS_ESHAPE, "bs_spec_sample: V=%d outside [1, 2^20]", V);
-    BS_REQUIRE(gamma <= 512, BS_ESHAPE, "bs_spec_sample: gamma=%d > 512", gamma);
-    BS_REQUIRE((long long)B * (gamma + 1) < (1LL << 31), BS_ESHAPE, "bs_spec_sample: B*(gamma+1) overflows");
-    BS_REQUIRE(dtype == BS_F32 || dtype == BS_BF16, BS_EDTYPE, "bs_spec_sample: dtype %d", dtype);
-    BS_REQUIRE(temperature >= 0.f && isfinite(temperature), BS_EINVAL, "bs_spec_sample: temperature %g", (double)temperature);
-    if (B == 0) return BS_OK;
-    BS_REQUIRE(dev_target_logits && dev_accept_len && dev_next_token && dev_workspace, BS_EINVAL,
-               "bs_spec_sample: NULL pointer");
-    BS_REQUIRE(gamma == 0 || (dev_draft_tokens && (dev_draft_logits || temperature == 0.f)), BS_EINVAL, "bs_spec_sample: NULL draft input");
+    const int rc = check_spec_sample_args("bs_spec_sample", dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype,
+                                          temperature, dev_accept_len, dev_next_token);
+    if (rc != BS_OK || B == 0) return rc;
+    BS_REQUIRE(dev_workspace, BS_EINVAL, "bs_spec_sample: NULL pointer");
     BS_REQUIRE(workspace_bytes >= bs_spec_sample_workspace_bytes(B, gamma), BS_EWORKSPACE,
                "bs_spec_sample: workspace %zu < %zu bytes", workspace_bytes, bs_spec_sample_workspace_bytes(B, gamma));
     BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 15) == 0, BS_EWORKSPACE, "bs_spec_sample: workspace misaligned");

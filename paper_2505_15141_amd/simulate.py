@@ -23,8 +23,8 @@ def tgd_sample(rng, alpha, gamma):
 
 def run(kind, alphas, gammas, n_tokens, seed=0, delta=0.5):
     """Generates n_tokens tokens with one bandit over arms (alpha_i, gamma_i).
-    Returns dict(rounds, pulls [K], tokens, stopping_time_regret): the regret is the number of rounds spent beyond
-    what the best single arm needs in expectation, n_tokens / max_i mean_i (the stopping-time regret of Sec. 3)."""
+    Returns dict(rounds, pulls [K], tokens, means [K], stopping_time_regret): the regret is the number of rounds spent
+    beyond what the best single arm needs in expectation, n_tokens / max_i mean_i (the stopping-time regret of Sec. 3)."""
     K, L = len(alphas), max(gammas)
     kind_id = binding.BS_UCBSPEC if kind == "ucb" else binding.BS_EXP3SPEC
     b = binding.Bandit(kind_id, K, L, delta, seed)
@@ -38,5 +38,5 @@ def run(kind, alphas, gammas, n_tokens, seed=0, delta=0.5):
         pulls[arm] += 1
         tokens += y
         rounds += 1
-    best = max(tgd_mean(a, g) for a, g in zip(alphas, gammas))
-    return dict(rounds=rounds, pulls=pulls, tokens=tokens, stopping_time_regret=rounds - n_tokens / best)
+    means = np.array([tgd_mean(a, g) for a, g in zip(alphas, gammas)])
+    return dict(rounds=rounds, pulls=pulls, tokens=tokens, means=means, stopping_time_regret=rounds - n_tokens / means.max())

@@ -46,7 +46,8 @@ def test_forward_on_drawn_shapes(seed):
         c, B, n_prefix, q_len, packed, max_len, wseed = draw_model_case(rng)
         bf16 = c["dtype"] == "bf16"
         what = (seed, case, c, B, n_prefix, q_len, packed, max_len)
-        W = synth.make_weights(c, wseed, 0.02 * (4096 / c["d_model"]) ** 0.5 if bf16 else 0.05)
+        # bf16: wider weights on narrow models keep the logits at the 7B shape's scale; fp32: the workload's N(0, 0.02)
+        W = synth.make_weights(c, wseed, 0.02 * (4096 / c["d_model"]) ** 0.5 if bf16 else synth.WEIGHT_STD)
         if bf16:
             W = {k: (v if k.endswith("norm") else synth.to_bf16_grid(v)) for k, v in W.items()}
         m = bs().Model.from_numpy(c, W)
@@ -59,7 +60,7 @@ def test_forward_on_drawn_shapes(seed):
         kvl = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
         logits = bs().verify_forward(m, kv, dt[:, n_prefix:n_prefix + q_len].contiguous(), kvl)
         torch.cuda.synchronize()
-        tol = 2e-2 if bf16 else 1e-4          # fp32: weights of std 0.05 make logits of a few units
+        tol = 2e-2 if bf16 else 1e-5
         for b in range(B):
             ref = forward(c, W, toks[b], storage=c["dtype"])
             assert np.max(np.abs(last[b].cpu().numpy() - ref[n_prefix - 1])) < tol, what
@@ -100,7 +101,7 @@ def test_lockstep_runs_on_drawn_configurations(seed):
             nd = int(rng.choice([1, 2]))
             dcs = [synth.cfg(1, 8 * int(rng.integers(2, 10)), 2, int(rng.choice([16, 32])), 8 * int(rng.integers(2, 20)),
                              tc["vocab"], dtype="f32") for _ in range(nd)]
-            storage, tol = "f32", 1e-4
+            storage, tol = "f32", 1e-5
         K = int(rng.integers(1, 5))
         arm_draft = [int(rng.integers(0, nd)) for _ in range(K)]
         arm_gamma = [int(rng.choice([0, 1, 2, 3, 5, 8])) for _ in range(K)]
@@ -112,6 +113,8 @@ def test_lockstep_runs_on_drawn_configurations(seed):
         rseed = int(rng.integers(1, 1 << 20))
         noise = None if rng.random() < 0.6 else (0.2, 1.5, int(rng.choice([4, 8, 16])))
         temperature = float(rng.choice([1.0, 1.0, 0.6, 1.7, 0.0]))       # 0: greedy mode
+        if noise is not None and storage == "f32":
+            tol = 2e-5                              # Box-Muller in fp32 on the device: sigma * 5.8 * 4e-7 on top of the logits' 1e-5
         if rng.random() < 0.5:
             alg_o, alg_g = UCBSpec(K, L), b.Bandit(b.BS_UCBSPEC, K, L)
         else:

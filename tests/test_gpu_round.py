@@ -5,10 +5,9 @@ import torch
 
 from oracle import philox
 from oracle.bandit import UCBSpec, EXP3Spec
-from oracle.sampling import draw_is_valid
 from oracle.spec_round import spec_round, noise_sigma_of
 from paper_2505_15141_amd import synth
-from helpers import MARGIN, BIN_TOL
+from helpers import judge_round
 
 pytestmark = pytest.mark.gpu
 
@@ -22,21 +21,25 @@ class Harness:
     """Device state of one batch plus re-synchronisation to a given token history."""
 
     def __init__(self, tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph=False, noise=None,
-                 temperature=1.0):
+                 temperature=1.0, max_len=None, models=None, prompt_len=None):
         b = bs()
         self.B, self.P = prompts.shape
-        self.max_len = self.P + n_generate + max(arm_gamma) + 2
-        self.target = b.Model.from_numpy(tc, Wt)
-        self.drafts = [b.Model.from_numpy(c, W) for c, W in zip(dcs, Wds)]
-        for m in [self.target] + self.drafts:          # the layout the benchmark runs in, wherever the shapes allow it
-            if m.packed_bytes() > 0:
-                m.pack(release_originals=True)
+        self.max_len = self.P + n_generate + max(arm_gamma) + 2 if max_len is None else max_len
+        if models is None:
+            self.target = b.Model.from_numpy(tc, Wt)
+            self.drafts = [b.Model.from_numpy(c, W) for c, W in zip(dcs, Wds)]
+            for m in [self.target] + self.drafts:          # the layout the benchmark runs in, wherever the shapes allow it
+                if m.packed_bytes() > 0:
+                    m.pack(release_originals=True)
+        else:
+            self.target, self.drafts = models
         self.tkv = b.KV(self.target, self.B, self.max_len)
         self.dkvs = [b.KV(d, self.B, self.max_len) for d in self.drafts]
         self.tokens = torch.zeros(self.B, self.max_len, dtype=torch.int32, device="cuda")
         self.total = torch.zeros(self.B, dtype=torch.int32, device="cuda")
         self.goal = torch.full((self.B,), self.P + n_generate, dtype=torch.int32, device="cuda")
-        self.prompt_len = torch.full((self.B,), self.P, dtype=torch.int32, device="cuda")
+        pl = np.full(self.B, self.P) if prompt_len is None else np.asarray(prompt_len)
+        self.prompt_len = torch.from_numpy(pl.astype(np.int32)).cuda()
         self.round = b.Round(self.target, self.tkv, self.drafts, self.dkvs, arm_draft, arm_gamma, self.tokens, self.total,
                              self.goal, temperature, seed, use_graph, prompt_len=self.prompt_len, noise=noise)
         self.sync_to([list(p) for p in prompts], 0)
@@ -61,21 +64,29 @@ class Harness:
 
 
 def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed, storage, logit_tol, use_graph=False,
-             max_rounds=10 ** 9, wseed=1, noise=None, temperature=1.0):
-    Wt = synth.make_weights(tc, wseed)
-    Wds = [synth.make_weights(c, wseed + 1 + i) for i, c in enumerate(dcs)]
+             max_rounds=10 ** 9, wseed=1, noise=None, temperature=1.0, seconds=None, canonical_seconds=None,
+             weights=None, models=None, check=None, prompt_len=None, max_len=None):
+    """Alg. 3 on both sides, round by round from the same history: the oracle's BanditSpec loop and bs_spec_round with
+    the library's bandit.  seconds (a list, one scripted duration per round) switches the reward to the throughput of the
+    round (Sec. 6, second experiment), each side through its own function.  check: the sequences the oracle recomputes
+    (default all); the others follow the device's tokens.  weights / models: prebuilt (oracle weights, device models)."""
+    from oracle.bandit import batch_reward, throughput_reward
+    b_ = bs()
+    if weights is None:
+        Wt = synth.make_weights(tc, wseed)
+        Wds = [synth.make_weights(c, wseed + 1 + i) for i, c in enumerate(dcs)]
+    else:
+        Wt, Wds = weights
     prompts = synth.make_prompts(B, P, tc["vocab"], seed + 17)
-    h = Harness(tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph, noise, temperature)
-    greedy = temperature == 0.0
-
-    def near_tie(row):                       # greedy: an argmax decided by less than the logit tolerance may go either way
-        top = np.sort(np.asarray(row))[-2:]
-        return top[1] - top[0] < 2 * logit_tol
+    h = Harness(tc, dcs, Wt, Wds, arm_draft, arm_gamma, prompts, n_generate, seed, use_graph, noise, temperature,
+                max_len=max_len, models=models, prompt_len=prompt_len)
+    plen = np.full(B, P) if prompt_len is None else np.asarray(prompt_len)
+    check = list(range(B)) if check is None else list(check)
     seqs = [list(int(x) for x in p) for p in prompts]
     goal = P + n_generate
     L = max(arm_gamma)
     t = 0
-    stats = dict(rounds=0, decisions=0, excused=0, resyncs=0, max_logit_err=0.0)
+    stats = dict(rounds=0, decisions=0, excused=0, resyncs=0, max_logit_err=0.0, skipped=0)
     while any(len(s) < goal for s in seqs) and t < max_rounds:
         arm_o = alg_o.select(philox.bandit_uniform(seed, t))
         arm_g = alg_g.select()
@@ -85,50 +96,48 @@ def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed
         torch.cuda.synchronize()
         emitted, n_emitted = emitted.cpu().numpy(), n_emitted.cpu().numpy()
         tl, dl, dt, mg = (x.cpu().numpy() for x in h.round.debug_views(gamma))
-        ys, need_sync = [], False
+        ys, need_sync = {}, False
         for b in range(B):
             if len(seqs[b]) >= goal:
                 assert n_emitted[b] == 0
                 continue
+            if len(seqs[b]) + gamma > h.max_len:         # the round does not fit this sequence's caches: left out
+                assert n_emitted[b] == 0 and h.round.status() & 8
+                stats["skipped"] += 1
+                continue
+            if b not in check:                           # follows the device
+                assert 1 <= n_emitted[b] <= gamma + 1
+                seqs[b].extend(int(x) for x in emitted[b, :n_emitted[b]]); del seqs[b][goal:]
+                continue
             r = spec_round((tc, Wt), (dcs[arm_draft[arm_o]], Wds[arm_draft[arm_o]]), seqs[b], gamma, seed, b, t, temperature, storage,
-                           noise_sigma_of(noise, len(seqs[b]) - P))
-            ys.append(r["y"])
-            # draft draws: identical, or inside the widened CDF bin of the oracle's distribution
-            same_drafts = True
-            for i in range(gamma):
-                if same_drafts:
-                    err = float(np.max(np.abs(dl[b, i] - r["draft_logits"][i])))
-                    stats["max_logit_err"] = max(stats["max_logit_err"], err)
-                    assert err < logit_tol, f"round {t} seq {b} draft logits row {i}: {err}"
-                if same_drafts and int(dt[b, i]) != int(r["draft_tokens"][i]):
-                    assert (greedy and near_tie(r["draft_logits"][i])) or \
-                        draw_is_valid(r["draft_probs"][i], r["draft_uniforms"][i], int(dt[b, i]), BIN_TOL), \
-                        f"round {t} seq {b}: draft token {i} {int(dt[b, i])} vs {int(r['draft_tokens'][i])}"
-                    same_drafts = False          # later positions are conditioned on different prefixes
-            if not same_drafts:                      # a draw on a bin edge: both are valid, histories diverge
-                stats["excused"] += 1; need_sync = True
-            else:
-                err = float(np.max(np.abs(tl[b] - r["target_logits"])))
-                stats["max_logit_err"] = max(stats["max_logit_err"], err)
-                assert err < logit_tol, f"round {t} seq {b} target logits: {err}"
-                tested = r["margins"][~np.isnan(r["margins"])]
-                if greedy:                   # the margin of a greedy decision is the gap between the two largest logits
-                    shaky = any(near_tie(r["target_logits"][i]) for i in range(r["tau"] + 1))
-                else:
-                    shaky = bool(tested.size and np.min(np.abs(tested)) < MARGIN)
-                if shaky:
-                    stats["excused"] += 1
-                    need_sync = need_sync or int(n_emitted[b]) != r["y"] or list(emitted[b, :r["y"]]) != r["emitted"]
-                else:
-                    stats["decisions"] += 1
-                    assert int(n_emitted[b]) == r["y"], f"round {t} seq {b}: y {int(n_emitted[b])} != {r['y']}"
-                    assert list(emitted[b, :r["tau"]]) == r["emitted"][:r["tau"]]
-                    if int(emitted[b, r["tau"]]) != r["token"]:
-                        assert draw_is_valid(r["final_weights"], r["u_final"], int(emitted[b, r["tau"]]), BIN_TOL)
-                        need_sync = True
+                           noise_sigma_of(noise, len(seqs[b]) - int(plen[b])))
+            ys[b] = r["y"]
+            # every checked sequence is judged: draft rows and draws, target rows, then (tau, token) against the branches
+            # the accept loop can reach when only tests inside the margin may flip
+            kind, same, err = judge_round(r, gamma, dl[b], dt[b], tl[b], emitted[b], n_emitted[b], logit_tol, temperature,
+                                          what=f"round {t} seq {b}:")
+            stats["max_logit_err"] = max(stats["max_logit_err"], err)
+            stats["decisions" if kind == "firm" else "excused"] += 1
+            need_sync = need_sync or not same        # a valid but different outcome: histories diverge, re-synchronise
             seqs[b].extend(r["emitted"]); del seqs[b][goal:]
-        y = float(np.mean(ys))
-        alg_o.update(arm_o, y); alg_g.update(arm_g, y)
+        if (n_emitted > 0).any():
+            # reward of the round: the mean accepted length over the sequences that took part, each side's own function
+            y_g, _ = b_.batch_reward(n_emitted)
+            if len(check) == B and not need_sync:
+                assert y_g == batch_reward([ys.get(b, 0) for b in range(B)]), f"round {t}: batch reward"
+            y_o = batch_reward([ys.get(b, 0) for b in range(B)]) if len(check) == B else y_g
+            if need_sync:
+                y_g = y_o                               # the device took a valid other branch: follow the oracle's history
+            if seconds is not None:
+                y_o = throughput_reward(y_o, seconds[t], canonical_seconds, L)
+                y_g = b_.throughput_reward(y_g, seconds[t], canonical_seconds, L)
+            alg_o.update(arm_o, y_o); alg_g.update(arm_g, y_g)
+        else:
+            # nobody could take part (every unfinished sequence lacks room for this arm): the arm learns nothing; a
+            # scripted arm list moves on, a bandit would have to be given another arm set by the caller
+            assert stats["skipped"] > 0
+            if hasattr(alg_o, "skip"):
+                alg_o.skip(); alg_g.skip()
         t += 1
         stats["rounds"] += 1
         if need_sync:
@@ -140,6 +149,7 @@ def lockstep(tc, dcs, arm_draft, arm_gamma, alg_o, alg_g, B, P, n_generate, seed
             dev_tok = h.tokens.cpu().numpy()
             for b in range(B):
                 assert list(dev_tok[b, :len(seqs[b])]) == seqs[b]
+    stats["status"] = h.round.status()
     return stats, seqs
 
 
@@ -185,6 +195,9 @@ class Scripted:
         return self.arms[self.t % len(self.arms)]
 
     def update(self, arm, y):
+        self.t += 1
+
+    def skip(self):
         self.t += 1
 
 
@@ -257,3 +270,33 @@ def test_canonical_arm_with_sampling_bf16():
     stats, seqs = lockstep(MID_T, [MID_D], [0, 0], [0, 3], UCBSpec(2, 3), b.Bandit(b.BS_UCBSPEC, 2, 3),
                            2, 24, 24, seed=13, storage="bf16", logit_tol=2e-2)
     assert stats["rounds"] >= 8 and stats["decisions"] >= 8
+
+
+def test_throughput_as_the_reward_with_a_scripted_clock():
+    """Sec. 6, second experiment: arms gamma in {0..L} including canonical decoding, reward = throughput of the round.
+    The durations are scripted (a clock is not reproducible): longer rounds for larger gamma plus a seeded jitter; the
+    oracle's bandit is fed through oracle.bandit.throughput_reward, the library's through bs_throughput_reward, and
+    both must keep choosing the same arms."""
+    b = bs()
+    gammas = [0, 2, 4]
+    rng = np.random.default_rng(5)
+    canon = 3.6e-3
+    # every arm's duration appears in the list in the order the arms can be pulled: scripted per round as a function of
+    # nothing but the round index, so both sides see the same number whatever they choose
+    seconds = [float(canon * (1.0 + 0.3 * rng.integers(0, 5)) * rng.uniform(0.9, 1.1)) for _ in range(400)]
+    stats, seqs = lockstep(synth.TINY_TARGET, [synth.TINY_DRAFT], [0, 0, 0], gammas, UCBSpec(3, 4), b.Bandit(b.BS_UCBSPEC, 3, 4),
+                           2, 16, 48, seed=19, storage="f32", logit_tol=1e-5, seconds=seconds, canonical_seconds=canon)
+    assert all(len(s) == 64 for s in seqs) and stats["decisions"] > 10 and stats["status"] & 12 == 0
+
+
+def test_sequence_without_room_for_the_round_is_left_out_and_reported():
+    """goal_len == max_len: near the end a round of gamma = 4 would append keys past the cache.  Such a sequence takes
+    no part (n_emitted 0, nothing committed, status bit 8) instead of committing tokens from stale logits; the gamma = 0
+    arm, which needs no room beyond the next token, then finishes the generation."""
+    b = bs()
+    script = [1] * 14 + [0] * 40          # gamma = 4 until well past the point where it stops fitting, then gamma = 0
+    P, n_gen = 12, 20
+    stats, seqs = lockstep(synth.TINY_TARGET, [synth.TINY_DRAFT], [0, 0], [0, 4], Scripted(script), Scripted(script),
+                           3, P, n_gen, seed=23, storage="f32", logit_tol=1e-5, max_len=P + n_gen, max_rounds=len(script))
+    assert all(len(s) == P + n_gen for s in seqs)          # ran to the end
+    assert stats["skipped"] > 0 and stats["status"] & 8

@@ -50,7 +50,7 @@ def run_case(B, gamma, V, dtype, seed, temperature=1.0, noise=0.5, use_philox=Fa
         acc, tok, mg = bs().spec_sample(dt, dq, dtok, temperature, du, want_margins=gamma > 0)
     torch.cuda.synchronize()
     acc, tok = acc.cpu().numpy(), tok.cpu().numpy()
-    compared, excused = judge_sampling(infos, u[:, gamma], acc, tok)
+    compared, excused = judge_sampling(t.astype(np.float64), q.astype(np.float64), toks, u, temperature, infos, acc, tok)
     if gamma > 0:
         mg = mg.cpu().numpy()
         for b, r in enumerate(infos):              # margins of the positions the oracle tested
@@ -63,7 +63,7 @@ def run_case(B, gamma, V, dtype, seed, temperature=1.0, noise=0.5, use_philox=Fa
 def test_full_size_sampling_workload_bf16():
     # B=64, gamma=8, V=32000, bf16 logits: the stand-alone sampling configuration, element by element
     compared, excused, acc_o = run_case(64, 8, 32000, "bf16", seed=1)
-    assert compared >= 56
+    assert compared >= 62 and compared + excused == 64      # every sequence is checked; a marginal test is rare
     # acceptance statistics of the generator: alpha = 2*Phi(-sigma/2) = 0.803 at sigma 0.5 -> E[y] = 4.37
     assert 2.4 < acc_o.mean() + 1 < 6.4
 
@@ -104,7 +104,7 @@ def test_identical_models_accept_everything_and_bonus_follows_target():
                                    1.0, torch.from_numpy(u).cuda())
     assert (acc.cpu().numpy() == gamma).all()
     _, tok_o, infos = spec_sample_batch(t.astype(np.float64), q.astype(np.float64), toks, u.astype(np.float64))
-    judge_sampling(infos, u[:, gamma].astype(np.float64), acc.cpu().numpy(), tok.cpu().numpy())
+    judge_sampling(t.astype(np.float64), q.astype(np.float64), toks, u.astype(np.float64), 1.0, infos, acc.cpu().numpy(), tok.cpu().numpy())
 
 
 def test_disjoint_supports_reject_immediately():
