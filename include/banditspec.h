@@ -81,6 +81,19 @@ int bs_spec_sample(const void* dev_target_logits, const void* dev_draft_logits,
                    int32_t* dev_accept_len, int32_t* dev_next_token, float* dev_margins,
                    void* dev_workspace, size_t workspace_bytes, void* stream);
 
+/* The same operation for callers that cannot allocate device memory or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the per-row statistics go to a static array in device memory
+ * that every GPU the library runs on holds until the process ends (512 KiB).  Same arguments and results as
+ * bs_spec_sample without the workspace.  Limit: B * (2 * gamma + 1) <= bs_spec_sample_static_max_rows() (65536) logit
+ * rows per call, BS_ESHAPE beyond that.  Calls no allocating routine.  All calls on one GPU share that GPU's array:
+ * calls that overlap in time on the same GPU (different streams, different host threads) race; calls on one stream do
+ * not.  The first call on a device looks the array's address up (a host-side lock, no stream work). */
+size_t bs_spec_sample_static_max_rows(void);
+int bs_spec_sample_static(const void* dev_target_logits, const void* dev_draft_logits,
+                          const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype,
+                          float temperature, const float* dev_uniforms, uint64_t seed, uint32_t round,
+                          int32_t* dev_accept_len, int32_t* dev_next_token, float* dev_margins, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Arm selection (host only).  UCBSpec: Alg. 4 / its full version - arms 0..K-1 in order for the
  * first K rounds, then argmax of mean + (L/2) sqrt((1+n)/n^2 (1 + 2 ln(K t^2 sqrt(1+n)/delta))),

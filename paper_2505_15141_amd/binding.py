@@ -61,6 +61,8 @@ _sig("bs_version", C.c_int)
 _sig("bs_philox_word", u32, u64, u32, u32, u32, u32)
 _sig("bs_spec_sample_workspace_bytes", sz, C.c_int, C.c_int)
 _sig("bs_spec_sample", C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, u64, u32, vp, vp, vp, vp, sz, vp)
+_sig("bs_spec_sample_static_max_rows", sz)
+_sig("bs_spec_sample_static", C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, f32, vp, u64, u32, vp, vp, vp, vp)
 _sig("bs_bandit_create", C.c_int, C.c_int, C.c_int, C.c_int, f64, u64, C.POINTER(vp))
 _sig("bs_bandit_destroy", C.c_int, vp)
 _sig("bs_bandit_select", C.c_int, vp, C.POINTER(C.c_int))
@@ -140,6 +142,19 @@ def spec_sample(target_logits, draft_logits, draft_tokens, temperature=1.0, unif
                              DTYPES[target_logits.dtype], temperature, ptr(uniforms), seed, round,
                              ptr(out[0]), ptr(out[1]), ptr(margins), ptr(workspace), workspace.numel(),
                              stream_ptr(stream)))
+    return out[0], out[1], margins
+
+
+def spec_sample_static(target_logits, draft_logits, draft_tokens, temperature=1.0, uniforms=None, seed=0, round=0,
+                       out=None, margins=None, stream=None):
+    """bs_spec_sample_static: as spec_sample, statistics in the library's static device array; this wrapper allocates
+    only if `out` is not given."""
+    B, g1, V = target_logits.shape
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=target_logits.device), torch.empty(B, dtype=torch.int32, device=target_logits.device))
+    check(lib.bs_spec_sample_static(ptr(target_logits), ptr(draft_logits), ptr(draft_tokens), B, g1 - 1, V,
+                                    DTYPES[target_logits.dtype], temperature, ptr(uniforms), seed, round,
+                                    ptr(out[0]), ptr(out[1]), ptr(margins), stream_ptr(stream)))
     return out[0], out[1], margins
 
 

@@ -15,6 +15,7 @@
 // 4096 consecutive tokens of groups [512k, 512k+512).  Slab totals locate the slab, a block-wide
 // scan of the 512 group sums locates the group, a serial scan of 8 weights locates the token.
 #include <math.h>
+#include <mutex>
 #include "common.h"
 #include "sample.h"
 
@@ -736,5 +737,51 @@ extern "C" __attribute__((visibility("default"))) int bs_spec_sample(const void*
     BS_REQUIRE((reinterpret_cast<uintptr_t>(dev_workspace) & 15) == 0, BS_EWORKSPACE, "bs_spec_sample: workspace misaligned");
     return bs::launch_spec_sample(dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype, temperature,
                                   dev_uniforms, seed, nullptr, round, dev_workspace, nullptr, nullptr, dev_accept_len,
+                                  dev_next_token, dev_margins, reinterpret_cast<hipStream_t>(stream));
+}
+
+// ---- the same call for callers that cannot allocate: the per-row statistics live in a static device array ----------
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process ends.  The
+// array's name is only a host-side handle: the address the kernels get is looked up once per device.
+namespace {
+constexpr int STATIC_ROWS = 65536;                         // logit rows B * (2 gamma + 1) one call may have: 512 KiB
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) float2 scratch[STATIC_ROWS];
+void* g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+int static_scratch(void** out) {
+    int dev = -1;
+    BS_HIP(hipGetDevice(&dev));
+    BS_REQUIRE(dev >= 0 && dev < STATIC_MAX_DEVICES, BS_ESTATE, "bs_spec_sample_static: device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        BS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // this device's copy (the current device)
+        BS_REQUIRE(p, BS_EHIP, "bs_spec_sample_static: no address for the static scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return BS_OK;
+}
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) size_t bs_spec_sample_static_max_rows(void) { return STATIC_ROWS; }
+
+extern "C" __attribute__((visibility("default"))) int bs_spec_sample_static(const void* dev_target_logits, const void* dev_draft_logits,
+                              const int32_t* dev_draft_tokens, int B, int gamma, int V, int dtype, float temperature,
+                              const float* dev_uniforms, uint64_t seed, uint32_t round, int32_t* dev_accept_len,
+                              int32_t* dev_next_token, float* dev_margins, void* stream) {
+    int rc = check_spec_sample_args("bs_spec_sample_static", dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype,
+                                    temperature, dev_accept_len, dev_next_token);
+    if (rc != BS_OK || B == 0) return rc;
+    BS_REQUIRE((long long)B * (2 * gamma + 1) <= STATIC_ROWS, BS_ESHAPE,
+               "bs_spec_sample_static: B*(2*gamma+1) = %lld logit rows exceed the static scratch of %d rows; use bs_spec_sample",
+               (long long)B * (2 * gamma + 1), STATIC_ROWS);
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != BS_OK) return rc;
+    // nothing in the scratch has to start at zero: phase A writes every row's statistics before phase B reads them
+    return bs::launch_spec_sample(dev_target_logits, dev_draft_logits, dev_draft_tokens, B, gamma, V, dtype, temperature,
+                                  dev_uniforms, seed, nullptr, round, ws, nullptr, nullptr, dev_accept_len,
                                   dev_next_token, dev_margins, reinterpret_cast<hipStream_t>(stream));
 }
