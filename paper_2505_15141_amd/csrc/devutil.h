@@ -1,0 +1,60 @@
+// Device-side helpers shared by the kernel files (internal): storage dtype conversion, wavefront reductions, the
+// bf16 hi/lo split of fp32 operands, the KV cache's value layout.
+#pragma once
+#include "common.h"
+
+namespace bs {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- storage dtype helpers ----------------------------------------------------------------------
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+template <typename T> __device__ __forceinline__ T from_f(float f);
+template <> __device__ __forceinline__ float from_f<float>(float f) { return f; }
+template <> __device__ __forceinline__ uint16_t from_f<uint16_t>(float f) {   // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float wsum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wmax(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- KV cache layout --------------------------------------------------------------------------------
+// Per (sequence, kv head): K is [cache_len][hd] (a key's row is contiguous: MFMA A operand of K.Q^T).
+// V of a bf16 cache is stored transposed in blocks of 32 keys, [cache_len/32][hd][32], and inside a block
+// the key k = 16t + 4q + e sits at slot 8q + 4t + e: lane (d, q) of the MFMA A operand of V^T.P^T then
+// finds its 8 keys in one 16-byte load, in exactly the key order in which the score accumulators of
+// K.Q^T hold the probabilities.  cache_len is a multiple of 32.  fp32 caches keep V as [cache_len][hd].
+template <typename T> __device__ __forceinline__ size_t v_index(int key, int d, int hd);
+template <> __device__ __forceinline__ size_t v_index<float>(int key, int d, int hd) { return (size_t)key * hd + d; }
+template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, int hd) {
+    const int k = key & 31;
+    const int slot = ((k & 15) >> 2) * 8 + (k >> 4) * 4 + (k & 3);
+    return ((size_t)(key >> 5) * hd + d) * 32 + slot;
+}
+
+__device__ __forceinline__ uint4 ldg16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    return (uint32_t)from_f<uint16_t>(a) | ((uint32_t)from_f<uint16_t>(b) << 16);
+}
+__device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
+    float r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = v[e] - to_f(from_f<uint16_t>(v[e]));
+    hi = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    lo = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
+}
+
+}  // namespace bs

@@ -35,6 +35,33 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s);
 int launch_embed_dec(const int32_t* tok, const void* embed, const float* gain, int M, int d, float* x, void* planes,
                      size_t plane, float* ssq, hipStream_t s);
 
+// One resident kernel for a whole forward pass over one or two rows of a small model (see step.hip).
+constexpr int STEP_MAXL = 16;            // layers whose pointers travel as kernel arguments
+struct StepArgs {
+    const uint16_t* w[STEP_MAXL][7];     // tiled wq wk wv wo w_gate w_up w_down
+    const float* an[STEP_MAXL];          // attention / feed-forward norm gains
+    const float* fn[STEP_MAXL];
+    const uint16_t* embed; const float* final_norm; const uint16_t* lm_head;
+    int n_layers, d, H, KVH, hd, ff, V; float eps;
+    int B, q_len, M, logit_rows;
+    const int32_t* pos; const int32_t* tok; const float2* rope;      // written by the prep kernel
+    char* kv; size_t kv_layer; int cache_len;
+    void *X, *Q, *KVN, *PA, *ACT;        // exchange buffers of 8-byte cells {value, flag}: residual [M][d], queries [M][nq],
+                                         // new keys|values [M][2 nkv], attention partials [M][H][splits][hd + 4], SwiGLU output [M][ff];
+                                         // every flag is zero when the kernel starts (the prep kernel clears them)
+    int32_t* status; int splits;
+    float* logits; size_t logits_bstride;
+    unsigned spin_limit;                 // polls of a cell before a workgroup gives up (status bit 16)
+    int kp;                              // set by the launcher: padded row of the staged planes
+};
+bool step_fits(const bs_model_cfg& c, int B, int q_len, int n_layers);
+// bytes of the exchange buffers X, Q, KVN, PA, ACT (each 256-byte aligned, in this order; off[i] = where buffer i starts)
+// splits of the cached keys the resident step uses for B sequences and this cache length; 0: no room for the units
+int step_splits(const bs_model_cfg& c, int B, int max_len);
+size_t step_exchange_bytes(const bs_model_cfg& c, int M, int splits, size_t off[5]);
+int step_grid();                         // workgroups of the resident kernel = compute units of the device
+int launch_step(const StepArgs& a, hipStream_t s);
+
 int gemm_splits(int dtype, int N, int K, int M);
 int profile_enable(int on);
 int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches);
@@ -42,9 +69,11 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s);
 size_t packed_elems(int N, int K);                       // elements of the tiled copy of an [N][K] matrix
 int launch_pack_weights(const void* src, void* dst, int N, int K, hipStream_t s);
 
+// clear_bytes > 0: also zeroes that many bytes at `clear` (a multiple of 16, 16-byte aligned): the exchange cells of the
+// resident step kernel that follows
 int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, int kv_base, int B, int q_len,
                 int max_len, int V, int hd, float rope_base, int32_t* pos, int32_t* tok, float2* rope,
-                int32_t* status, hipStream_t s);
+                int32_t* status, void* clear, size_t clear_bytes, hipStream_t s);
 int launch_embed(int dtype, const int32_t* tok, const void* embed, int M, int d, float* x, hipStream_t s);
 int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d,
                    float eps, int n_seq, int rows_in, int rows_out, size_t plane, void* out, hipStream_t s);

@@ -22,47 +22,9 @@
 #include <hip/hip_ext.h>
 #include "common.h"
 #include "kernels.h"
+#include "devutil.h"
 
 namespace bs {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-// ---- storage dtype helpers ----------------------------------------------------------------------
-__device__ __forceinline__ float to_f(float v) { return v; }
-__device__ __forceinline__ float to_f(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
-template <typename T> __device__ __forceinline__ T from_f(float f);
-template <> __device__ __forceinline__ float from_f<float>(float f) { return f; }
-template <> __device__ __forceinline__ uint16_t from_f<uint16_t>(float f) {   // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ float wsum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-__device__ __forceinline__ float wmax(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
-// ---- KV cache layout --------------------------------------------------------------------------------
-// Per (sequence, kv head): K is [cache_len][hd] (a key's row is contiguous: MFMA A operand of K.Q^T).
-// V of a bf16 cache is stored transposed in blocks of 32 keys, [cache_len/32][hd][32], and inside a block
-// the key k = 16t + 4q + e sits at slot 8q + 4t + e: lane (d, q) of the MFMA A operand of V^T.P^T then
-// finds its 8 keys in one 16-byte load, in exactly the key order in which the score accumulators of
-// K.Q^T hold the probabilities.  cache_len is a multiple of 32.  fp32 caches keep V as [cache_len][hd].
-template <typename T> __device__ __forceinline__ size_t v_index(int key, int d, int hd);
-template <> __device__ __forceinline__ size_t v_index<float>(int key, int d, int hd) { return (size_t)key * hd + d; }
-template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, int hd) {
-    const int k = key & 31;
-    const int slot = ((k & 15) >> 2) * 8 + (k >> 4) * 4 + (k & 3);
-    return ((size_t)(key >> 5) * hd + d) * 32 + slot;
-}
 
 // ---- prep ---------------------------------------------------------------------------------------
 // One workgroup per sequence.  pos[m] = kv_len[b] + kv_base + j, or -1 for a sequence that would run
@@ -70,7 +32,13 @@ template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, 
 __global__ void prep_kernel(const int32_t* __restrict__ q_tokens, int q_stride, const int32_t* __restrict__ kv_len,
                             int kv_base, int q_len, int max_len, int V, int half_hd, float rope_base,
                             int32_t* __restrict__ pos, int32_t* __restrict__ tok, float2* __restrict__ rope,
-                            int32_t* __restrict__ status) {
+                            int32_t* __restrict__ status, int B, uint4* __restrict__ clear, size_t clear16) {
+    if ((int)blockIdx.x >= B) {                       // the blocks behind the sequences zero the exchange cells
+        const size_t nb = gridDim.x - B;
+        for (size_t i = (size_t)(blockIdx.x - B) * blockDim.x + threadIdx.x; i < clear16; i += nb * blockDim.x)
+            clear[i] = make_uint4(0u, 0u, 0u, 0u);
+        return;
+    }
     const int b = blockIdx.x;
     const int kvl = (kv_len ? kv_len[b] : 0) + kv_base;
     const bool ok = kvl >= 0 && kvl + q_len <= max_len;
@@ -275,7 +243,6 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_
 // summed by the consumer kernel.  Three kernels by row count: gemm_bf16_m16_kernel (up to 16 rows, the
 // verification pass of one sequence: pure weight streaming), this one with two row tiles (17..32 rows, and the
 // fallback when K is not a multiple of 32), gemm_bf16_big_kernel from 33 rows on (measured faster from there).
-__device__ __forceinline__ uint4 ldg16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
 // Weight layouts.  Row-major [N][K], or TILED: the matrix is cut into 64-row x 32-column blocks stored
 // [N/64][K/32][4][64][8]: inside a block the four 16-row MFMA A tiles follow each other, and inside a tile the
@@ -1429,17 +1396,6 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 //                      accumulators as they are (hi/lo pair), no LDS, no transposes
 // Bytes: every K and V element is read once per 16 rows (per 32 with two tiles per wavefront, below).  Un-normalised
 // partials (m, l, o[hd]) per split.
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    return (uint32_t)from_f<uint16_t>(a) | ((uint32_t)from_f<uint16_t>(b) << 16);
-}
-__device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
-    float r[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = v[e] - to_f(from_f<uint16_t>(v[e]));
-    hi = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
-    lo = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
-}
-
 // NT = 16-row tiles a wavefront holds at the same time: every K and V block it loads is multiplied with all of them.
 // With grouped queries a verification pass has G * (gamma + 1) rows per kv head, more than one tile from 17 rows on, and a
 // second workgroup for the second tile walks the whole cache a second time (batch 32, 8192 cached keys, 24 rows: 3.7
@@ -1692,9 +1648,14 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
 // ---- launchers -----------------------------------------------------------------------------------
 int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, int kv_base, int B, int q_len,
                 int max_len, int V, int hd, float rope_base, int32_t* pos, int32_t* tok, float2* rope,
-                int32_t* status, hipStream_t s) {
-    hipLaunchKernelGGL(prep_kernel, dim3(B), dim3(q_len > 16 ? 1024 : 128), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
-                       hd / 2, rope_base, pos, tok, rope, status);
+                int32_t* status, void* clear, size_t clear_bytes, hipStream_t s) {
+    const int threads = q_len > 16 ? 1024 : 128;
+    const size_t clear16 = clear_bytes / 16;
+    // one clearing block per 32 KiB, at most 64
+    int extra = (int)((clear_bytes + 32767) / 32768);
+    if (extra > 64) extra = 64;
+    hipLaunchKernelGGL(prep_kernel, dim3(B + extra), dim3(threads), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
+                       hd / 2, rope_base, pos, tok, rope, status, B, reinterpret_cast<uint4*>(clear), clear16);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }

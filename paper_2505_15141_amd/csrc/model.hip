@@ -147,6 +147,7 @@ static int attn_splits(int B, int H, int max_len) {
 
 struct FwdWs {
     int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* q; void* att; void* act; float* ssq;
+    char* xch; size_t xch_bytes;    // resident step kernel: exchange cells (one or two rows only)
     float *part_qkv, *part_o, *part_gu, *part_d, *part_attn;
     int ks_qkv, ks_o, ks_gu, ks_d;
     size_t total;
@@ -173,6 +174,8 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.att = take(M * nq * 4);
     w.act = take(M * c.d_ff * 4);
     w.ssq = (float*)take(M * (c.d_model / 16 + 1) * 4);
+    w.xch_bytes = (M <= 2 && step_splits(c, B, max_len) > 0) ? step_exchange_bytes(c, (int)M, step_splits(c, B, max_len), nullptr) : 0;
+    w.xch = take(w.xch_bytes);
     w.part_qkv = (float*)take(M * (nq + 2 * nkv) * 4 * w.ks_qkv);
     w.part_o = (float*)take(M * c.d_model * 4 * w.ks_o);
     w.part_gu = (float*)take(M * 2 * c.d_ff * 4 * w.ks_gu);
@@ -216,11 +219,37 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
     const int splits = attn_splits(B, H, kv->max_len);
     int rc;
 #define BS_TRY(expr) do { rc = (expr); if (rc != BS_OK) return rc; } while (0)
-    BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
-                       w.rope, w.status, s));
     const float* pend = nullptr;      // split-K partials of the last residual projection, not yet added to x
     // A handful of rows (draft steps): fused schedule, 5 kernels per layer; needs the tiled weights.
     const bool few_rows = dt == BS_BF16 && m->packed && gemm_dec_fits(M, d) && gemm_dec_fits(M, nq) && gemm_dec_fits(M, ff);
+    // One or two rows of a small model: one resident kernel for the whole pass.
+    const int st_splits = M <= 2 ? step_splits(c, B, kv->max_len) : 0;
+    const bool resident = few_rows && st_splits > 0 && step_fits(c, B, q_len, c.n_layers);
+    BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
+                       w.rope, w.status, resident ? w.xch : nullptr, resident ? w.xch_bytes : 0, s));
+    if (resident) {
+        StepArgs a = {};
+        for (int l = 0; l < c.n_layers; ++l) {
+            const bs_layer_weights& L = m->layers[l];
+            const void* ptrs[7] = {L.wq, L.wk, L.wv, L.wo, L.w_gate, L.w_up, L.w_down};
+            for (int i = 0; i < 7; ++i) a.w[l][i] = reinterpret_cast<const uint16_t*>(ptrs[i]);
+            a.an[l] = L.attn_norm; a.fn[l] = L.ffn_norm;
+        }
+        a.embed = reinterpret_cast<const uint16_t*>(m->embed); a.final_norm = m->final_norm;
+        a.lm_head = reinterpret_cast<const uint16_t*>(m->lm_head);
+        a.n_layers = c.n_layers; a.d = d; a.H = H; a.KVH = KVH; a.hd = hd; a.ff = ff; a.V = c.vocab; a.eps = c.norm_eps;
+        a.B = B; a.q_len = q_len; a.M = M; a.logit_rows = logit_rows;
+        a.pos = w.pos; a.tok = w.tok; a.rope = w.rope;
+        a.kv = kv->buf; a.kv_layer = kv_layer; a.cache_len = crow;
+        size_t off[5];
+        step_exchange_bytes(c, M, st_splits, off);
+        a.X = w.xch + off[0]; a.Q = w.xch + off[1]; a.KVN = w.xch + off[2]; a.PA = w.xch + off[3]; a.ACT = w.xch + off[4];
+        a.status = w.status; a.splits = st_splits;
+        a.logits = logits; a.logits_bstride = logits_bstride;
+        a.spin_limit = 1u << 18;      // about a quarter of a second of polling: then the pass is given up (status bit 16)
+        BS_TRY(launch_step(a, s));
+        return BS_OK;
+    }
     if (few_rows) {
         const size_t pd = (size_t)M * d;
         uint16_t* hp = reinterpret_cast<uint16_t*>(w.h);
