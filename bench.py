@@ -43,8 +43,6 @@ def cpu_baseline(tc, dc, prefix, gamma, mean_y):
         cores = os.cpu_count() or 1
     rng = np.random.default_rng(0)
     toks = rng.integers(0, tc["vocab"], prefix + gamma)
-    slice_layers = 12
-
     block = synth.to_bf16_grid((rng.standard_normal(1 << 22, dtype=np.float32) * 0.02))
 
     def tiled_weights(cc):
@@ -53,26 +51,55 @@ def cpu_baseline(tc, dc, prefix, gamma, mean_y):
         return {name: (np.ones(shape, dtype=np.float32) if name.endswith("norm") else np.resize(block, shape))
                 for name, shape in synth.weight_shapes(cc).items()}
 
-    def timed(c, n_layers, n_tokens):
+    def timed(c, n_layers, n_tokens, last_rows):
         cc = dict(c, n_layers=n_layers)
         W = tiled_weights(cc)
         t0 = time.perf_counter()
-        lg = forward(cc, W, toks[:n_tokens], storage="bf16")
+        lg = forward(cc, W, toks[:n_tokens], storage="bf16", last_rows=last_rows)      # as oracle.spec_round calls it
         return time.perf_counter() - t0, lg
 
-    t_t0, _ = timed(tc, 0, prefix + gamma)          # embedding + final norm + LM head
-    t_ts, lg_t = timed(tc, slice_layers, prefix + gamma)
-    t_d, lg_d = timed(dc, dc["n_layers"], prefix + gamma - 1)     # one draft step of the full draft model (full recompute)
-    t0 = time.perf_counter()
-    spec_sample(lg_t[-(gamma + 1):], lg_d[-gamma:], toks[-gamma:], np.full(gamma, 0.5), 0.5)
-    t_s = time.perf_counter() - t0
-    t_target = t_t0 + tc["n_layers"] * max(t_ts - t_t0, 0.0) / slice_layers
-    t_round = t_target + gamma * t_d + t_s
-    return {"value": mean_y / t_round, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": (f"one round at gamma={gamma}, {prefix + gamma} tokens, full recompute in fp64: target embedding + LM head and a "
-                       f"{slice_layers}-layer slice timed (layers extrapolated to {tc['n_layers']}), the {dc['n_layers']}-layer draft timed whole "
-                       f"(one of its {gamma} steps), one accept/reject call: {t_round:.1f} s per round; tokens per round taken from the GPU run"),
-            "seconds_measured": round(t_t0 + t_ts + t_d + t_s, 2)}
+    def one_round_seconds(k):
+        # T(n layers) = fixed + (n - 1) full layers + the last layer (restricted to the wanted rows): two depths give both
+        t_1, _ = timed(tc, 1, prefix + gamma, gamma + 1)
+        t_k, lg_t = timed(tc, k, prefix + gamma, gamma + 1)
+        t_d, lg_d = timed(dc, dc["n_layers"], prefix + gamma - 1, 1)   # one draft step of the full draft model (full recompute)
+        t0 = time.perf_counter()
+        spec_sample(lg_t, np.repeat(lg_d, gamma, axis=0), toks[-gamma:], np.full(gamma, 0.5), 0.5)
+        t_s = time.perf_counter() - t0
+        t_target = t_1 + (tc["n_layers"] - 1) * max(t_k - t_1, 0.0) / (k - 1)
+        return t_target + gamma * t_d + t_s, t_1 + t_k + t_d + t_s
+
+    slice_layers = 5
+    t_round, t_meas = one_round_seconds(slice_layers)
+    out = {"value": mean_y / t_round, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+           "sample": (f"one round at gamma={gamma}, {prefix + gamma} tokens, full recompute in fp64 (the forward pass as oracle.spec_round calls "
+                      f"it: all layers over all tokens, the last layer's queries and the LM head only for the wanted rows): the target timed at 1 "
+                      f"and {slice_layers} layers and extrapolated to {tc['n_layers']} (identical layers), the {dc['n_layers']}-layer draft timed "
+                      f"whole (one of its {gamma} steps), one accept/reject call: {t_round:.1f} s per round; tokens per round taken from the GPU run"),
+           "seconds_measured": round(t_meas, 2)}
+    try:                                                            # the same with one thread, on a one-layer slice
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            t_round1, t_meas1 = one_round_seconds(2)
+        out["single_thread"] = {"value": mean_y / t_round1, "unit": "tokens/s", "cores": 1,
+                                "sample": f"the same round with the BLAS limited to one thread, the target timed at 1 and 2 layers: "
+                                          f"{t_round1:.1f} s per round", "seconds_measured": round(t_meas1, 2)}
+    except ImportError:
+        out["single_thread"] = None
+    return out
+
+
+def spread(np, values_ms):
+    """median / 10th / 90th percentile of a list of durations (ms)."""
+    v = np.asarray(values_ms, dtype=np.float64)
+    return {"median": round(float(np.median(v)), 4), "p10": round(float(np.percentile(v, 10)), 4),
+            "p90": round(float(np.percentile(v, 90)), 4), "n": int(v.size)}
+
+
+def hbm_roofline(kernel, achieved_gbps, note):
+    """The roofline record of an HBM-bound stage in the same form as the headline kernel's."""
+    return {"bound": "hbm", "kernel": kernel, "achieved": round(achieved_gbps, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved_gbps / HBM_PEAK_GBS, 4), "bytes": note}
 
 
 def pmc_traffic_ratio():
@@ -87,18 +114,20 @@ def pmc_traffic_ratio():
     return None
 
 
-def stage_probes(bs, synth, torch, np, stream):
-    """HBM rates of the two other bandwidth-bound stages at the sizes where they matter (HIP-event timed):
-    the stand-alone sampling workload (B=64, gamma=8, V=32000, bf16 logits) and the verification attention
-    of one 7B-shaped layer at batch 16 with 4096 cached tokens per sequence."""
+SAMPLING_CASES = ((64, 32000, 5, "sampling"), (256, 32000, 2, "sampling_b256"), (1024, 32000, 2, "sampling_b1024"),
+                  (64, 128256, 2, "sampling_v128256"))
+
+
+def sampling_stage(bs, torch, np, stream, cases=SAMPLING_CASES, reps=20):
+    """Accept/reject + residual sampling by itself (HIP-event timed): the stand-alone workload (B = 64, gamma = 8, V = 32000,
+    bf16 logits), the same rows at larger batches, and the 128256-token vocabulary.  Logits: target N(0, 2), draft = target
+    + N(0, 0.5), drafted tokens drawn from the draft's distribution.  Several copies of the inputs are cycled so that the
+    rows come from HBM, not from the 256 MB last-level cache (5 x 70 MB at B = 64)."""
     out = {}
+    gamma = 8
     with torch.cuda.stream(stream):
-        # ---- accept/reject + residual sampling: the stand-alone workload (B = 64) and the same rows at B = 1024 ----
-        gamma = 8
         g = torch.Generator(device="cuda"); g.manual_seed(7)
-        # 5 x 70 MB: more than the 256 MB last-level cache; the other sizes exceed it with one or two copies
-        for B, V, copies, key in ((64, 32000, 5, "sampling"), (256, 32000, 2, "sampling_b256"), (1024, 32000, 2, "sampling_b1024"),
-                                  (64, 128256, 2, "sampling_v128256")):
+        for B, V, copies, key in cases:
             T = [(torch.randn(B, gamma + 1, V, generator=g, device="cuda") * 2).to(torch.bfloat16) for _ in range(copies)]
             Q = [(t[:, :gamma].float() + 0.5 * torch.randn(B, gamma, V, generator=g, device="cuda")).to(torch.bfloat16) for t in T]
             toks = [torch.multinomial(torch.softmax(q.float().view(-1, V), -1), 1).view(B, gamma).to(torch.int32) for q in Q]
@@ -108,7 +137,6 @@ def stage_probes(bs, synth, torch, np, stream):
             for i in range(3):
                 bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 20
             e0.record(stream)
             for i in range(reps):
                 bs.spec_sample(T[i % copies], Q[i % copies], toks[i % copies], 1.0, u, workspace=ws, out=res)
@@ -119,8 +147,20 @@ def stage_probes(bs, synth, torch, np, stream):
             touched = B * (2 * gamma + 1) * V * 2
             out[key] = {"workload": f"B={B} gamma=8 V={V} bf16 logits", "us": round(us, 2),
                         "touched_GBps": round(touched / us / 1e3, 1), "algorithmic_GBps": round(alg / us / 1e3, 1),
-                        "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4)}
+                        "frac_hbm_touched": round(touched / us / 1e3 / HBM_PEAK_GBS, 4),
+                        "mean_accepted_drafts": round(float(acc.mean()), 3),
+                        "roofline": hbm_roofline("bs::row_stats_kernel + bs::spec_decide_kernel (both launches of one call)", touched / us / 1e3,
+                                                 "every logit row once: B*(2*gamma+1)*V*2 bytes per call")}
             del T, Q, toks
+    return out
+
+
+def stage_probes(bs, synth, torch, np, stream):
+    """HBM rates of the two other bandwidth-bound stages at the sizes where they matter (HIP-event timed):
+    the stand-alone sampling workload (B=64, gamma=8, V=32000, bf16 logits) and the verification attention
+    of one 7B-shaped layer at batch 16 with 4096 cached tokens per sequence."""
+    out = sampling_stage(bs, torch, np, stream)
+    with torch.cuda.stream(stream):
         # ---- what this box delivers to plain library kernels (yardsticks for the fractions of the published peaks) ----
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda"); dst = torch.empty_like(src)
         a16 = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16); b16 = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
@@ -159,7 +199,9 @@ def stage_probes(bs, synth, torch, np, stream):
         kv_bytes = 2 * (ctx + q_len) * c1["n_kv_heads"] * c1["head_dim"] * 2 * Bb
         us_a = ms_a * 1e3 / max(n_a, 1)
         out["attention_b16_ctx4096"] = {"us": round(us_a, 2), "kv_bytes": int(kv_bytes), "GBps": round(kv_bytes / us_a / 1e3, 1),
-                                        "frac_hbm": round(kv_bytes / us_a / 1e3 / HBM_PEAK_GBS, 4)}
+                                        "frac_hbm": round(kv_bytes / us_a / 1e3 / HBM_PEAK_GBS, 4),
+                                        "roofline": hbm_roofline("bs::attn_mfma_kernel<128> (one launch per layer, HIP events of the dispatch)",
+                                                                 kv_bytes / us_a / 1e3, "keys and values of every sequence once: 2*(ctx+q_len)*n_kv*hd*2*B bytes")}
     return out
 
 
@@ -194,17 +236,21 @@ def batch_rounds_stage(bs, synth, torch, np, stream, target, draft, tc, rounds=2
             _, n_emitted = rnd.spec_round(arm)
             host_y.copy_(n_emitted, non_blocking=True)
             stream.synchronize()
-            y = float(host_y.float().mean())
+            y = bs.batch_reward(host_y)[0]
             bandit.update(arm, y)
             return arm, y
         for _ in range(len(gam)):                 # every arm once: the graphs are captured here
             one()
         stream.synchronize()
         t0 = time.perf_counter()
-        arms, ys = zip(*[one() for _ in range(rounds)])
+        arms, ys, per_round = [], [], []
+        for _ in range(rounds):
+            t1 = time.perf_counter()
+            arm, y = one()
+            per_round.append((time.perf_counter() - t1) * 1e3); arms.append(arm); ys.append(y)
         stream.synchronize()
         dt = time.perf_counter() - t0
-    return {"workload": "B=16, 4096 cached tokens, EXP3Spec over gamma in {2,3,4,5,6,8}, noise 0.2/1.5 every 64 tokens",
+    return {"ms_per_round_spread": spread(np, per_round), "workload": "B=16, 4096 cached tokens, EXP3Spec over gamma in {2,3,4,5,6,8}, noise 0.2/1.5 every 64 tokens",
             "rounds": rounds, "tokens_per_s": round(float(np.sum(ys)) * B / dt, 1), "ms_per_round": round(dt / rounds * 1e3, 3),
             "mean_accepted_tokens": round(float(np.mean(ys)), 3), "arm_pulls": [int(np.sum(np.asarray(arms) == a)) for a in range(len(gam))],
             "prompt_pass_s_both_models_65520_tokens": round(prefill_s, 3)}
@@ -245,14 +291,18 @@ def multi_draft_rounds_stage(bs, synth, torch, np, stream, rounds=12):
             _, n_emitted = rnd.spec_round(arm)
             host_y.copy_(n_emitted, non_blocking=True)
             stream.synchronize()
-            y = float(host_y.float().mean())
+            y = bs.batch_reward(host_y)[0]
             bandit.update(arm, y)
             return arm, y
         for _ in range(len(drafts)):              # UCBSpec pulls every arm once first: the graphs are captured here
             one()
         stream.synchronize()
         t0 = time.perf_counter()
-        arms, ys = zip(*[one() for _ in range(rounds)])
+        arms, ys, per_round = [], [], []
+        for _ in range(rounds):
+            t1 = time.perf_counter()
+            arm, y = one()
+            per_round.append((time.perf_counter() - t1) * 1e3); arms.append(arm); ys.append(y)
         stream.synchronize()
         dt = time.perf_counter() - t0
         # one verification pass of the same shape by itself (6 rows per sequence against the cache as it stands)
@@ -262,13 +312,14 @@ def multi_draft_rounds_stage(bs, synth, torch, np, stream, rounds=12):
         kvl = (total - 1 - q_len).clamp(min=0).to(torch.int32)
         qtok = tokens[:, ctx:ctx + q_len].contiguous()
         ts = []
-        for _ in range(4):
+        for _ in range(6):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             bs.verify_forward(target, tkv, qtok, kvl, workspace=ws, logits=lg)
             e1.record(stream); e1.synchronize()
             ts.append(e0.elapsed_time(e1))
         ms_v = float(np.median(ts[1:]))
+        verify_spread = spread(np, ts[1:])
     nq, nkv = tc["n_heads"] * tc["head_dim"], tc["n_kv_heads"] * tc["head_dim"]
     w_bytes = 2 * (tc["n_layers"] * (tc["d_model"] * (nq + 2 * nkv) + nq * tc["d_model"] + 3 * tc["d_model"] * tc["d_ff"]) + tc["vocab"] * tc["d_model"])
     kv_bytes = 2 * ctx * nkv * 2 * B * tc["n_layers"]
@@ -276,7 +327,7 @@ def multi_draft_rounds_stage(bs, synth, torch, np, stream, rounds=12):
                         "(1/2/4 layers, d=1024), gamma=5",
             "rounds": rounds, "tokens_per_s": round(float(np.sum(ys)) * B / dt, 1), "ms_per_round": round(dt / rounds * 1e3, 3),
             "mean_accepted_tokens": round(float(np.mean(ys)), 3), "arm_pulls": [int(np.sum(np.asarray(arms) == a)) for a in range(len(drafts))],
-            "verify_ms": round(ms_v, 3), "verify_rows": B * q_len,
+            "ms_per_round_spread": spread(np, per_round), "verify_ms": round(ms_v, 3), "verify_ms_spread": verify_spread, "verify_rows": B * q_len,
             "verify_weight_plus_kv_GBps": round((w_bytes + kv_bytes) / ms_v / 1e6, 1),
             "verify_frac_hbm": round((w_bytes + kv_bytes) / ms_v / 1e6 / HBM_PEAK_GBS, 4),
             "prompt_pass_s_target_%d_tokens" % (B * (ctx - 1)): round(prefill_target_s, 3)}
@@ -295,6 +346,9 @@ def main():
                          "{0,2,4,6,8} with the measured tokens/s of the round as the reward (bs_throughput_reward)")
     ap.add_argument("--canonical-rounds", type=int, default=32, help="rounds of gamma = 0 (canonical decoding) timed as the baseline")
     ap.add_argument("--no-multi-draft", action="store_true", help="skip the stage with the 8B-shaped target and three draft models")
+    ap.add_argument("--only-sampling", action="store_true",
+                    help="run only the stand-alone sampling call at B = 64, gamma = 8, V = 32000 (200 calls) and print its JSON "
+                         "(for profiling it by itself); not the benchmark line")
     ap.add_argument("--only-multi-draft", action="store_true",
                     help="run only that stage and print its JSON (for profiling it by itself); not the benchmark line")
     ap.add_argument("--pmc-mode", action="store_true",
@@ -313,6 +367,9 @@ def main():
     from paper_2505_15141_amd import binding as bs, synth
 
     torch.cuda.set_device(0)
+    if args.only_sampling:
+        print(json.dumps({"stage": "sampling", **sampling_stage(bs, torch, np, torch.cuda.Stream(), SAMPLING_CASES[:1], reps=200)}))
+        return
     if args.only_multi_draft:
         print(json.dumps({"stage": "rounds_b32_ctx8192_three_drafts",
                           **multi_draft_rounds_stage(bs, synth, torch, np, torch.cuda.Stream())}))
@@ -323,7 +380,8 @@ def main():
     round_gammas = gammas if by_throughput else gammas + [0]         # the device also knows the canonical step (gamma = 0)
     canon_arm = round_gammas.index(0)
     L, B, prefix = max(gammas), 1, 1024
-    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12 + 14 * 4
+    budget_tokens = 256                              # a request of the workload: 256 new tokens after the prompt
+    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12 + 14 * 4 + budget_tokens + 4
     max_len = prefix + (L + 1) * total_rounds + L + 2
     seed = 2025
 
@@ -355,7 +413,7 @@ def main():
             _, n_emitted = rnd.spec_round(arm)
             host_y.copy_(n_emitted, non_blocking=True)
             stream.synchronize()                      # the next arm choice depends on y (Alg. 3)
-            return float(host_y.float().mean()), time.perf_counter() - t_start
+            return bs.batch_reward(host_y)[0], time.perf_counter() - t_start
 
         canon_s = None
         if by_throughput and not args.pmc_mode:       # duration of one target pass: the reference of the throughput reward
@@ -422,6 +480,20 @@ def main():
                 ts.append(e0.elapsed_time(e1))
             verify_ms[str(g)] = round(float(np.median(ts[1:])), 4)
 
+        # ---- one request of the workload's size: rounds until 256 tokens are out (the bandit keeps what it has learnt) ----
+        budget = None
+        if not args.pmc_mode and args.steps:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n_tok, n_rounds = 0.0, 0
+            while n_tok < budget_tokens:
+                n_tok += one_round()[1] * B
+                n_rounds += 1
+            torch.cuda.synchronize()
+            dt_b = time.perf_counter() - t0
+            budget = {"tokens": budget_tokens, "rounds": n_rounds, "seconds": round(dt_b, 4),
+                      "tokens_per_s": round(n_tok / dt_b, 2), "emitted": int(n_tok)}
+
         # ---- roofline of the dominant kernel: eager rounds with HIP events around every GEMM launch ----
         eager_gammas = [2, 4, 6, 8]
         rnd_eager = bs.Round(target, tkv, [draft], [dkv], [0] * 4, eager_gammas, tokens, total, goal, 1.0, seed, use_graph=False)
@@ -454,7 +526,10 @@ def main():
             stages = {"target_gemm": {"GBps": round(by_t / (ms_t * 1e-3) / 1e9, 1), "frac_hbm": round(by_t / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                       "launches": int(n_t), "avg_us": round(ms_t * 1e3 / max(n_t, 1), 2)},
                       "attention_b1": {"keys": n_keys, "avg_us": round(ms_a * 1e3 / max(n_a, 1), 2),
-                                       "GBps": round(attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9, 1)}}
+                                       "GBps": round(attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9, 1),
+                                       "roofline": hbm_roofline("bs::attn_mfma_kernel<128> (one launch per layer of the B = 1 verification pass)",
+                                                                attn_bytes_b1 / (ms_a * 1e-3 / max(n_a, 1)) / 1e9,
+                                                                "keys and values of the sequence once per layer")}}
         del ws9, lg9
 
     if not args.pmc_mode:
@@ -470,7 +545,7 @@ def main():
             wsb = torch.empty(target.forward_workspace_bytes(Bb, q_len, ctx + 64), dtype=torch.uint8, device="cuda")
             lgb = torch.empty(Bb, q_len, tc["vocab"], dtype=torch.float32, device="cuda")
             ts = []
-            for _ in range(4):
+            for _ in range(6):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
                 bs.verify_forward(target, kvb, qtok, kvlb, workspace=wsb, logits=lgb)
@@ -480,7 +555,7 @@ def main():
             kv_bytes_b = 2 * (ctx + q_len) * tc["n_kv_heads"] * tc["head_dim"] * 2 * Bb * tc["n_layers"]
             nq_b = tc["n_heads"] * tc["head_dim"]
             wb_b = 2 * (tc["n_layers"] * (tc["d_model"] * 3 * nq_b + nq_b * tc["d_model"] + 3 * tc["d_model"] * tc["d_ff"]) + tc["vocab"] * tc["d_model"])
-            stages["verify_b16_ctx4096"] = {"ms": round(ms_b, 3), "rows": Bb * q_len, "weight_plus_kv_GBps": round((wb_b + kv_bytes_b) / ms_b / 1e6, 1),
+            stages["verify_b16_ctx4096"] = {"ms": round(ms_b, 3), "ms_spread": spread(np, ts[1:]), "rows": Bb * q_len, "weight_plus_kv_GBps": round((wb_b + kv_bytes_b) / ms_b / 1e6, 1),
                                             "frac_hbm": round((wb_b + kv_bytes_b) / ms_b / 1e6 / HBM_PEAK_GBS, 4),
                                             "mfma_issue_frac_of_peak": round(2 * wb_b * Bb * q_len / (ms_b * 1e-3) / 2.5e15, 4)}
             del kvb, wsb, lgb
@@ -503,6 +578,16 @@ def main():
                 "traffic": (round(by1 / max(n1, 1) * pmc_traffic_ratio(), 1) if pmc_traffic_ratio() else None), "launches": int(n1), "avg_us": round(ms1 * 1e3 / max(n1, 1), 3),
                 "avg_algorithmic_bytes": round(by1 / max(n1, 1), 1)}
     mean_y = float(np.mean(ys)) if ys else 0.0
+    draft_us = ((round_ms["8"] - round_ms["2"] - (verify_ms["8"] - verify_ms["2"])) / 6.0 * 1e3
+                if "8" in round_ms and "2" in round_ms and verify_ms else None)
+    nq_d, nkv_d = dc["n_heads"] * dc["head_dim"], dc["n_kv_heads"] * dc["head_dim"]
+    draft_bytes = 2 * (dc["n_layers"] * (dc["d_model"] * (nq_d + 2 * nkv_d) + nq_d * dc["d_model"] + 3 * dc["d_model"] * dc["d_ff"])
+                       + dc["vocab"] * dc["d_model"])
+    if draft_us and stages is not None:
+        # one draft step = prep + the resident forward kernel + the draw; latency-bound: 61 dependent phases of a few microseconds
+        stages["draft_step"] = {"us": round(draft_us, 1), "weight_bytes": int(draft_bytes),
+                                "roofline": hbm_roofline("bs::dec_step_kernel<64> (+ prep and draw) per draft step, from the slope of the round "
+                                                         "time over gamma", draft_bytes / draft_us / 1e3, "every draft weight once per step")}
     out = {"metric": "generated tokens/s at 1 GPU", "value": round(gen_tokens / elapsed, 2) if args.steps else 0.0, "unit": "tokens/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed / max(args.steps, 1) * 1e3, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -515,9 +600,8 @@ def main():
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
            "ms_per_step_spread": ({"median": round(float(np.median(step_ms)), 4), "p10": round(float(np.percentile(step_ms, 10)), 4),
                                    "p90": round(float(np.percentile(step_ms, 90)), 4)} if len(step_ms) else None),
-           "round_ms_by_gamma": round_ms,
-           "draft_step_us": (round((round_ms["8"] - round_ms["2"] - (verify_ms["8"] - verify_ms["2"])) / 6.0 * 1e3, 1)
-                             if "8" in round_ms and "2" in round_ms and verify_ms else None),
+           "request_of_256_tokens": budget, "round_ms_by_gamma": round_ms,
+           "draft_step_us": round(draft_us, 1) if draft_us else None,
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
            "canonical_decoding_tokens_per_s": round(canonical, 2) if canonical else None,

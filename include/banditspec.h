@@ -300,8 +300,11 @@ int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const flo
  * class, the summed kernel time in ms, the summed algorithmic bytes and the launch count.  Classes:
  * 1, 2, 4, 6, 8, 16 = GEMM launches with up to that many tiles of 16 activation rows (bytes: each weight element
  * once, N*K*2); 50 = the fused few-row projections of draft steps (same bytes); 100 = attention (bytes
- * reported as 0: the cache lengths live on the device, the caller knows them); 0 = everything.  Enabling clears earlier records.  Do not enable while a graph is being
- * captured.
+ * reported as 0: the cache lengths live on the device, the caller knows them); 0 = everything.
+ * bs_profile_enable(1) starts an empty record; bs_profile_enable(0) stops recording and drops the record with its
+ * events, so collect before switching off.  Events cannot be recorded into a stream capture: while the record is on, a
+ * timed launch on a stream that is being captured fails with BS_ESTATE (switch the record off before capturing).  The
+ * record is guarded by a mutex: launches, enable and collect may come from several host threads.
  * ---------------------------------------------------------------------------------------------- */
 int bs_profile_enable(int on);
 int bs_profile_collect(int row_tiles, double* host_total_ms, double* host_total_bytes, long long* host_launches);

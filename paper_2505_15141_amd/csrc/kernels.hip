@@ -18,6 +18,7 @@
 //   attention   q_len causal query rows per head against the contiguous KV cache, split along the
 //               keys with online softmax; merge kernel combines the splits
 #include <math.h>
+#include <mutex>
 #include <vector>
 #include <hip/hip_ext.h>
 #include "common.h"
@@ -1096,16 +1097,42 @@ struct GemmProfile {
     std::vector<int> mt;
 };
 static GemmProfile g_prof;
+static std::mutex g_prof_mutex;      // launches may come from several host threads
 
+// Switching on starts an empty record; switching off drops the record and its events (collect first).
 int profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     g_prof.on = on != 0;
-    if (!on) return BS_OK;
     for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
     g_prof.ev.clear(); g_prof.bytes.clear(); g_prof.mt.clear();
     return BS_OK;
 }
 
+// Events for one timed launch, or none when the record is off.  Events cannot be recorded into a stream capture: a
+// launch that is being captured while the record is on is refused.
+static int prof_events(hipStream_t s, hipEvent_t* e0, hipEvent_t* e1) {
+    *e0 = nullptr; *e1 = nullptr;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof.on) return BS_OK;
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    BS_HIP(hipStreamIsCapturing(s, &st));
+    BS_REQUIRE(st == hipStreamCaptureStatusNone, BS_ESTATE, "per-launch timing is switched on while the stream is being captured: "
+               "switch it off (bs_profile_enable(0)) before capturing");
+    BS_HIP(hipEventCreate(e0));
+    if (hipEventCreate(e1) != hipSuccess) { (void)hipEventDestroy(*e0); *e0 = nullptr; BS_FAIL(BS_EHIP, "hipEventCreate failed"); }
+    return BS_OK;
+}
+static void prof_record(hipEvent_t e0, hipEvent_t e1, double bytes, int cls) {
+    if (!e0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof.on) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return; }   // switched off in between
+    g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
+    g_prof.bytes.push_back(bytes);
+    g_prof.mt.push_back(cls);
+}
+
 int profile_collect(int mt_filter, double* total_ms, double* total_bytes, long long* launches) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
     double ms = 0.0, by = 0.0;
     long long n = 0;
     for (size_t i = 0; i < g_prof.bytes.size(); ++i) {
@@ -1143,17 +1170,9 @@ int launch_gemm(int dtype, GemmArgs a, hipStream_t s) {
     }
     const bool big_ok = a.K % 32 == 0;                              // the many-row kernel works in whole 32-column stages
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    auto prof_begin = [&]() -> int {
-        if (!g_prof.on) return BS_OK;
-        BS_HIP(hipEventCreate(&e0));
-        BS_HIP(hipEventCreate(&e1));
-        return BS_OK;
-    };
+    auto prof_begin = [&]() -> int { return prof_events(s, &e0, &e1); };
     auto prof_end = [&](int mt) -> int {                            // classes by 16-row tiles: 1, 2, 4, 6, 8, 16
-        if (!g_prof.on) return BS_OK;
-        g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
-        g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0);
-        g_prof.mt.push_back(mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
+        prof_record(e0, e1, (double)a.N * (double)a.K * 2.0, mt <= 1 ? 1 : mt <= 2 ? 2 : mt <= 4 ? 4 : mt <= 6 ? 6 : mt <= 8 ? 8 : 16);
         return BS_OK;
     };
     int rc;
@@ -1686,10 +1705,7 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
     const bool deep = steps / (epi == EPI_SWIGLU ? 4 : W) > 4;      // ring of 8 unless a wavefront has at most 4 steps
     const dim3 grid(a.N / 16), block(64 * W);
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (g_prof.on) {
-        BS_HIP(hipEventCreate(&e0));
-        BS_HIP(hipEventCreate(&e1));
-    }
+    { const int prc = prof_events(s, &e0, &e1); if (prc != BS_OK) return prc; }
     const size_t lds = dec_lds_bytes(a.M, a.K);
 #define BS_DEC(E, MG) do { if (deep) BS_LAUNCH_TIMED((gemm_dec_kernel<E, 8, MG>), grid, block, lds, s, e0, e1, a); \
                            else BS_LAUNCH_TIMED((gemm_dec_kernel<E, 4, MG>), grid, block, lds, s, e0, e1, a); } while (0)
@@ -1699,11 +1715,7 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
     else BS_DEC(EPI_SWIGLU, false);
 #undef BS_DEC
     BS_LAUNCH_CHECK();
-    if (g_prof.on) {                                       // class 50: fused few-row projections
-        g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
-        g_prof.bytes.push_back((double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0));
-        g_prof.mt.push_back(50);
-    }
+    prof_record(e0, e1, (double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0), 50);   // class 50: fused few-row projections
     return BS_OK;
 }
 
@@ -1787,10 +1799,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         const dim3 mgrid(n_splits * (out ? n_rt : 1), KVH, B);
         uint16_t* direct = (out && n_splits == 1) ? reinterpret_cast<uint16_t*>(out) : nullptr;     // no merge needed
         hipEvent_t e0 = nullptr, e1 = nullptr;
-        if (g_prof.on) {
-            BS_HIP(hipEventCreate(&e0));
-            BS_HIP(hipEventCreate(&e1));
-        }
+        { const int prc = prof_events(s, &e0, &e1); if (prc != BS_OK) return prc; }
 #define BS_ATTN(HD, NT) BS_LAUNCH_TIMED((attn_mfma_kernel<HD, NT>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache, \
                                         (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane)
         if (hd == 128) { if (nt == 2) BS_ATTN(128, 2); else BS_ATTN(128, 1); }
@@ -1799,11 +1808,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
             BS_FAIL(BS_ESHAPE, "attention: bf16 caches need head_dim 64 or 128, got %d", hd);
 #undef BS_ATTN
         BS_LAUNCH_CHECK();
-        if (g_prof.on) {                                   // class 100: the split attention kernel (bytes known to the caller)
-            g_prof.ev.push_back(e0); g_prof.ev.push_back(e1);
-            g_prof.bytes.push_back(0.0);
-            g_prof.mt.push_back(100);
-        }
+        prof_record(e0, e1, 0.0, 100);                     // class 100: the split attention kernel (bytes known to the caller)
         if (out && !direct) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,

@@ -204,3 +204,33 @@ def test_argument_errors():
     with pytest.raises(b.BanditSpecError) as e:
         b.verify_forward(m, kv, torch.zeros(1, 17, dtype=torch.int32, device="cuda"), kvl)
     assert e.value.code == -2
+
+
+def test_per_launch_timing_refuses_a_stream_capture_and_counts_eager_launches():
+    """The measurement hook: with the record on, eager launches of the bf16 GEMM are counted, a pass that is being
+    captured into a graph is refused (BS_ESTATE, nothing launched), and switching the record off drops it."""
+    b = bs()
+    W, m, kv = setup(MID, 1, 64, seed=5, packed=True)
+    toks = torch.zeros(1, 9, dtype=torch.int32, device="cuda"); kvl = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(m.forward_workspace_bytes(1, 9, 64), dtype=torch.uint8, device="cuda")
+    lg = torch.empty(1, 9, MID["vocab"], dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        b.verify_forward(m, kv, toks, kvl, workspace=ws, logits=lg)
+        side.synchronize()
+        b.profile_enable(True)
+        try:
+            b.verify_forward(m, kv, toks, kvl, workspace=ws, logits=lg)
+            side.synchronize()
+            ms, by, n = b.profile_collect(0)
+            assert n >= 4 * MID["n_layers"] and ms > 0 and by > 0
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                with pytest.raises(b.BanditSpecError) as e:
+                    b.verify_forward(m, kv, toks, kvl, workspace=ws, logits=lg)
+            assert e.value.code == -5
+        finally:
+            b.profile_enable(False)
+        assert b.profile_collect(0)[2] == 0
+        b.verify_forward(m, kv, toks, kvl, workspace=ws, logits=lg)          # and the library still works
+        side.synchronize()
