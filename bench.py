@@ -609,6 +609,8 @@ def main():
            "prefill": {"tokens": prefix - 1, "seconds": round(prefill_s, 4), "tokens_per_s": round((prefix - 1) / prefill_s, 1),
                        # projections only: 2 flops per weight and token; both activation planes go through the matrix cores
                        "useful_TFLOPs": round(weights_bytes * (prefix - 1) / prefill_s / 1e12, 1),
+                       "useful_frac_of_mfma_peak": round(weights_bytes * (prefix - 1) / prefill_s / 2.5e15, 4),
+                       # issued = useful x 2: every weight tile is multiplied with the hi and with the lo activation plane
                        "mfma_issue_frac_of_peak": round(2 * weights_bytes * (prefix - 1) / prefill_s / 2.5e15, 4)},
            "stages": stages, "roofline": roofline}
     if not args.no_cpu_baseline:
