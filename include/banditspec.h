@@ -197,12 +197,21 @@ size_t bs_forward_workspace_bytes(const bs_model_cfg* cfg, int B, int max_q_len,
  *               1 for a draft step, 0 for cache fill only)
  *  dev_logits   [B, logit_rows, vocab] float32 out (may be NULL if logit_rows == 0)
  * Sequences with kv_len[b] + q_len > max_len are skipped entirely and bit 0 of the device status
- * word (first int32 of the workspace) is set; other sequences are unaffected.
- * The same call serves the draft model's steps (q_len = 1 or 2, logit_rows = 1).
+ * word (first int32 of the workspace) is set; other sequences are unaffected.  The library only ever ORs bits into that
+ * word: zero it (the workspace once, say) before relying on it.
+ * The same call serves the draft model's steps (q_len = 1 or 2, logit_rows = 1).  One or two rows in all (B * q_len <= 2)
+ * of a small packed bf16 model with head_dim 64 run as ONE resident kernel of one workgroup per compute unit whose
+ * workgroups wait for each other's outputs; it needs the GPU's compute units to itself while it runs (work of the same
+ * stream or graph is ordered behind it anyway).  Every wait is bounded: see bs_step_poll_limit.
  * ---------------------------------------------------------------------------------------------- */
 int bs_verify_forward(const bs_model* m, const bs_kv* kv, const int32_t* dev_q_tokens,
                       const int32_t* dev_kv_len, int q_len, int logit_rows, float* dev_logits,
                       void* dev_workspace, size_t workspace_bytes, void* stream);
+/* The bound of the resident kernel's waits, in polls of one cell (default 2^18, about a quarter of a second; 0 restores
+ * the default).  A pass that runs out of polls ends without a result -- its logits and the cache rows it was to write are
+ * not valid -- and sets bit 16 of the device status word; no launch ever waits without end.  Applies to passes enqueued
+ * after the call.  Meant for tests of that path. */
+int bs_step_poll_limit(unsigned polls);
 
 /* Prompt processing: fills the cache for positions 0..n-1 of every sequence (same n for all), in
  * chunks through the same kernels.  dev_tokens [B, token_stride] int32, n <= token_stride.
@@ -283,6 +292,7 @@ int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emi
  *   2  a token id outside [0, vocab) was replaced by 0
  *   4  total_len < 2 or > max_len at the start of a round (sequence left out)
  *   8  a sequence still generating had total_len + gamma > max_len (left out, see dev_goal_len above)
+ *  16  a resident draft step ran out of polls (bs_step_poll_limit): that round's tokens are not valid
  * Copies the word to *host_out (HOST memory) and WAITS for `stream`: this call synchronises.  Not for use while the
  * stream is being captured. */
 int bs_round_status(bs_round* r, int32_t* host_out, void* stream);

@@ -88,6 +88,7 @@ _sig("bs_round_reset", C.c_int, vp, u32, vp)
 _sig("bs_spec_round", C.c_int, vp, C.c_int, vp, vp, vp)
 _sig("bs_round_status", C.c_int, vp, C.POINTER(i32), vp)
 _sig("bs_draft_propose", C.c_int, vp, C.c_int, vp, vp, vp)
+_sig("bs_step_poll_limit", C.c_int, C.c_uint)
 _sig("bs_profile_enable", C.c_int, C.c_int)
 _sig("bs_profile_collect", C.c_int, C.c_int, C.POINTER(f64), C.POINTER(f64), C.POINTER(C.c_longlong))
 _sig("bs_round_debug_views", C.c_int, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp))
@@ -382,6 +383,11 @@ class Round:
         if getattr(self, "h", None) and lib is not None:
             lib.bs_round_destroy(self.h)
             self.h = None
+
+
+def step_poll_limit(polls=0):
+    """Bound of the resident draft step's waits (0: the default)."""
+    check(lib.bs_step_poll_limit(int(polls)))
 
 
 def profile_enable(on=True):

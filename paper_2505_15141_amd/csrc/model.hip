@@ -1,6 +1,7 @@
 // Host side of the model path: handles, workspace carving, the forward pass schedule (verification
 // pass of App. A and the draft steps), prompt prefill, and the round driver (Alg. 2 with vanilla
 // speculative decoding; one iteration of the loop of Alg. 3 on the device).
+#include <atomic>
 #include <new>
 #include <vector>
 #include "common.h"
@@ -8,6 +9,10 @@
 #include "sample.h"
 
 using namespace bs;
+
+// polls of one exchange cell before a resident step gives up: about a quarter of a second at the default
+constexpr unsigned STEP_DEFAULT_POLLS = 1u << 18;
+static std::atomic<unsigned> g_step_polls{STEP_DEFAULT_POLLS};
 
 struct bs_model {
     bs_model_cfg cfg;
@@ -246,7 +251,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         a.X = w.xch + off[0]; a.Q = w.xch + off[1]; a.KVN = w.xch + off[2]; a.PA = w.xch + off[3]; a.ACT = w.xch + off[4];
         a.status = w.status; a.splits = st_splits;
         a.logits = logits; a.logits_bstride = logits_bstride;
-        a.spin_limit = 1u << 18;      // about a quarter of a second of polling: then the pass is given up (status bit 16)
+        a.spin_limit = g_step_polls.load();       // polls of a cell before the pass is given up (status bit 16)
         BS_TRY(launch_step(a, s));
         return BS_OK;
     }
@@ -804,6 +809,11 @@ extern "C" __attribute__((visibility("default"))) int bs_round_debug_views(bs_ro
     if (dl) *dl = r->ws.draft_logits;
     if (dt) *dt = r->ws.draft_tokens;
     if (mg) *mg = r->ws.margins;
+    return BS_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int bs_step_poll_limit(unsigned polls) {
+    g_step_polls.store(polls ? polls : STEP_DEFAULT_POLLS);
     return BS_OK;
 }
 

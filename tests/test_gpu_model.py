@@ -234,3 +234,33 @@ def test_per_launch_timing_refuses_a_stream_capture_and_counts_eager_launches():
         assert b.profile_collect(0)[2] == 0
         b.verify_forward(m, kv, toks, kvl, workspace=ws, logits=lg)          # and the library still works
         side.synchronize()
+
+
+def test_resident_step_gives_up_after_its_poll_limit_and_recovers():
+    """One row of a small packed bf16 model runs as one resident kernel whose workgroups poll for each other's outputs.
+    With the poll limit at 1 every wait runs out at once: the launch must still end (no workgroup waits for ever), report
+    it in bit 16 of the status word, and the next pass with the default limit must be right again."""
+    b = bs()
+    c = MID
+    W, m, kv = setup(c, 1, 96, seed=21, packed=True)
+    n_prefix = 40
+    toks = synth.make_prompts(1, n_prefix + 2, c["vocab"], 22)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    b.prefill(m, kv, dt, n_prefix)
+    kvl = torch.full((1,), n_prefix, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(m.forward_workspace_bytes(1, 2, 96), dtype=torch.uint8, device="cuda")     # the status word starts at 0
+    lg = torch.empty(1, 2, c["vocab"], dtype=torch.float32, device="cuda")
+    q = dt[:, n_prefix:n_prefix + 2].contiguous()
+    try:
+        b.step_poll_limit(1)
+        b.verify_forward(m, kv, q, kvl, workspace=ws, logits=lg)
+        torch.cuda.synchronize()                      # returns: the launch ended
+        assert int(ws[:4].view(torch.int32).cpu()[0]) & 16
+    finally:
+        b.step_poll_limit(0)
+    ws[:4].zero_()                                    # the word is only ever OR-ed into
+    b.verify_forward(m, kv, q, kvl, workspace=ws, logits=lg)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).cpu()[0]) & 16 == 0
+    ref = forward(c, W, toks[0], storage="bf16")
+    assert np.max(np.abs(lg[0].cpu().numpy() - ref[n_prefix:n_prefix + 2])) < TOL["bf16"]
