@@ -381,7 +381,8 @@ def main():
     canon_arm = round_gammas.index(0)
     L, B, prefix = max(gammas), 1, 1024
     budget_tokens = 256                              # a request of the workload: 256 new tokens after the prompt
-    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12 + 14 * 4 + budget_tokens + 4
+    thr_rounds = 0 if (by_throughput or args.pmc_mode) else 96    # a short run with throughput as the reward (Sec. 6, second experiment)
+    total_rounds = args.warmup + args.steps + args.profile_rounds + args.canonical_rounds + 12 + 14 * 4 + budget_tokens + 4 + thr_rounds + 8
     max_len = prefix + (L + 1) * total_rounds + L + 2
     seed = 2025
 
@@ -494,6 +495,28 @@ def main():
             budget = {"tokens": budget_tokens, "rounds": n_rounds, "seconds": round(dt_b, 4),
                       "tokens_per_s": round(n_tok / dt_b, 2), "emitted": int(n_tok)}
 
+        # ---- throughput as the reward (Sec. 6, the speculation-length experiment): arms gamma in {0,2,4,6,8}, gamma = 0 being
+        #      canonical decoding; every round's measured tokens/s, mapped by bs_throughput_reward, is the arm's reward ----
+        thr_stage = None
+        if thr_rounds:
+            thr_gammas = [0, 2, 4, 6, 8]
+            thr_arm_of = [round_gammas.index(g) for g in thr_gammas]
+            canon_ref = float(np.median([timed_round(canon_arm)[1] for _ in range(5)][1:]))
+            tb = bs.Bandit(bs.BS_UCBSPEC, len(thr_gammas), L, 0.5)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            toks_thr, pulls = 0.0, [0] * len(thr_gammas)
+            for _ in range(thr_rounds):
+                a_ = tb.select()
+                y_, sec_ = timed_round(thr_arm_of[a_])
+                tb.update(a_, bs.throughput_reward(y_ * B, sec_, canon_ref, L))
+                toks_thr += y_ * B; pulls[a_] += 1
+            torch.cuda.synchronize()
+            dt_thr = time.perf_counter() - t0
+            thr_stage = {"workload": "same models and prompt, UCBSpec over gamma in {0,2,4,6,8}, reward = bs_throughput_reward(tokens, seconds of the "
+                                     "round, seconds of a gamma = 0 round, L = 8)", "rounds": thr_rounds, "tokens_per_s": round(toks_thr / dt_thr, 2),
+                         "arm_pulls_gamma_0_2_4_6_8": pulls, "canonical_round_ms": round(canon_ref * 1e3, 4)}
+
         # ---- roofline of the dominant kernel: eager rounds with HIP events around every GEMM launch ----
         eager_gammas = [2, 4, 6, 8]
         rnd_eager = bs.Round(target, tkv, [draft], [dkv], [0] * 4, eager_gammas, tokens, total, goal, 1.0, seed, use_graph=False)
@@ -600,7 +623,7 @@ def main():
            "arm_pulls": [int(arms.count(a)) for a in range(len(gammas))],
            "ms_per_step_spread": ({"median": round(float(np.median(step_ms)), 4), "p10": round(float(np.percentile(step_ms, 10)), 4),
                                    "p90": round(float(np.percentile(step_ms, 90)), 4)} if len(step_ms) else None),
-           "request_of_256_tokens": budget, "round_ms_by_gamma": round_ms,
+           "request_of_256_tokens": budget, "throughput_as_reward": thr_stage, "round_ms_by_gamma": round_ms,
            "draft_step_us": round(draft_us, 1) if draft_us else None,
            "verify_step_ms": verify_ms, "verify_weight_bytes": int(weights_bytes),
            "verify_hbm_frac_at_gamma8": round(weights_bytes / (verify_ms["8"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if verify_ms else None,
