@@ -159,9 +159,11 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
             }
         }
     };
-    auto wmma = [&](int s0, int n) -> f32x4 {
+    // the lane's B operand of k step s0 (hi plane; the lo plane is M * Kp elements further), as an element offset into xs
+    auto plane_off = [&](int s0) -> int { return min(li, M - 1) * Kp + lq * 8 + s0 * 32; };
+    auto wmma = [&](int boff, int n) -> f32x4 {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};             // hi and lo plane: two independent chains
-        const uint16_t* bh = xs + (size_t)min(li, M - 1) * Kp + lq * 8 + s0 * 32;
+        const uint16_t* bh = xs + boff;
         const uint16_t* bl = bh + (size_t)M * Kp;
 #pragma unroll
         for (int g = 0; g < STEP_MAXS / 4; ++g) {
@@ -186,6 +188,14 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
         *reinterpret_cast<uint2*>(&xs[(size_t)m * Kp + c]) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
         *reinterpret_cast<uint2*>(&xs[(size_t)(M + m) * Kp + c]) =
             make_uint2(pack_bf16(v0 - to_f(h0), v1 - to_f(h1)), pack_bf16(v2 - to_f(h2), v3 - to_f(h3)));
+    };
+
+    // r of row m from the wavefronts' partial sums of squares (valid behind the staging barrier of a normed phase)
+    auto row_scale = [&](int m) -> float {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < STEP_WAVES; ++w) t += s_part[w][m];
+        return 1.0f / sqrtf(t / (float)d + a.eps);
     };
 
     // ---- per-row facts from the prep kernel (positions, tokens) ----------------------------------------------------------
@@ -481,23 +491,28 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                     for (int e = 0; e < 4; ++e) wo[((size_t)wave * R + li) * (HD + 1) + t * 16 + 4 * lq + e] = o[t][e];
             }
             if (!alive()) return;
-            // two dimensions per lane: one 16-byte store of two cells
-            for (int idx = tid; idx < R * (HD / 2); idx += STEP_THREADS) {
-                const int r = idx / (HD / 2), dd = (idx % (HD / 2)) * 2;
-                float mm = -INFINITY;
+            // eight consecutive lanes = the eight wavefronts' shares of two output dimensions of one row: each reads its
+            // wavefront's (max, sum, two outputs), three shuffles find the maximum, three add the rescaled shares, and the
+            // first of the eight stores two cells with one 16-byte store
+            for (int base = 0; base < R * (HD / 2); base += STEP_THREADS / STEP_WAVES) {
+                const int idx = base + (tid >> 3), w = tid & 7;
+                const bool on = idx < R * (HD / 2);
+                const int r = on ? idx / (HD / 2) : 0, dd = on ? (idx % (HD / 2)) * 2 : 0;
+                const float mw = wm[w * 16 + r];
+                float mm = mw;
+                mm = fmaxf(mm, __shfl_xor(mm, 1, 64)); mm = fmaxf(mm, __shfl_xor(mm, 2, 64)); mm = fmaxf(mm, __shfl_xor(mm, 4, 64));
+                const float f = (mw == -INFINITY) ? 0.f : __expf(mw - mm);
+                float ov0 = wo[((size_t)w * R + r) * (HD + 1) + dd] * f, ov1 = wo[((size_t)w * R + r) * (HD + 1) + dd + 1] * f;
+                float lv = wl[w * 16 + r] * f;
 #pragma unroll
-                for (int w = 0; w < STEP_WAVES; ++w) mm = fmaxf(mm, wm[w * 16 + r]);
-                float ov0 = 0.f, ov1 = 0.f, lv = 0.f;
-#pragma unroll
-                for (int w = 0; w < STEP_WAVES; ++w) {
-                    const float f = (wm[w * 16 + r] == -INFINITY) ? 0.f : __expf(wm[w * 16 + r] - mm);
-                    ov0 += wo[((size_t)w * R + r) * (HD + 1) + dd] * f;
-                    ov1 += wo[((size_t)w * R + r) * (HD + 1) + dd + 1] * f;
-                    lv += wl[w * 16 + r] * f;
+                for (int o_ = 1; o_ < 8; o_ <<= 1) {
+                    ov0 += __shfl_xor(ov0, o_, 64); ov1 += __shfl_xor(ov1, o_, 64); lv += __shfl_xor(lv, o_, 64);
                 }
-                const int c = (((m_first + (r & qs)) * H + at_kvh * Gq + (r >> qs)) * (S + 1) + at_s) * PCELLS;
-                st_cells2(bPA, c + dd, ov0, ov1, fout);
-                if (dd == 0) st_cells4(bPA, c + HD, mm, lv, 0.f, 0.f, fout);
+                if (on && w == 0) {
+                    const int c = (((m_first + (r & qs)) * H + at_kvh * Gq + (r >> qs)) * (S + 1) + at_s) * PCELLS;
+                    st_cells2(bPA, c + dd, ov0, ov1, fout);
+                    if (dd == 0) st_cells4(bPA, c + HD, mm, lv, 0.f, 0.f, fout);
+                }
             }
             __syncthreads();                                                    // the combine buffers are free again
             continue;
@@ -507,6 +522,16 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
         const int n_tiles = is_lm ? 1 : tiles_of(kind);
         const int u0 = is_lm ? 0 : first_tile(kind);
         if (u0 >= n_tiles) continue;
+        // What the tile loop needs is worked out here, ahead of the polls, and pinned there: left to itself the compiler
+        // puts these couple of hundred scalar instructions between the staging barrier and the first multiply, where they
+        // are on the critical path (a wavefront issues one of them every four to five cycles).
+        const int K = kind == PH_O ? nq : (kind == PH_DOWN ? ff : d), steps = K >> 5;
+        const int wsh = kind == PH_GU ? 2 : 3, WS = 1 << wsh;
+        const int wv = kind == PH_GU ? (wave & 3) : wave;
+        int s0 = (wv * steps) >> wsh, n = (((wv + 1) * steps) >> wsh) - s0;
+        unsigned fout = step_flag(l, kind);
+        int boff = plane_off(s0);
+        asm volatile("" : "+s"(s0), "+s"(n), "+s"(fout), "+v"(boff));
         // the residual columns of the first tile (O, down: written two phases ago) are asked for ahead of the staging
         auto residual = [&](int u) -> float4 {
             const int c = u * 16 + 4 * lq;
@@ -521,49 +546,35 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
         if (!is_lm && (kind == PH_O || kind == PH_DOWN) && wave == 0 && row_ok) x_first = residual(u0);
         // ---- stage the input rows as planes in LDS ----
         if (is_lm || kind == PH_QKV || kind == PH_GU) {
-            // normalised rows: x * rsqrt(mean(x^2) + eps) * gain, whole rows (first layer: the token embeddings, else the
-            // residual stream X as the phase before left it)
+            // RMSNorm by linearity: norm(x) W^T = r * ((gain . x) W^T) with r = rsqrt(mean(x^2) + eps) per row, so the planes
+            // of gain . x are staged as soon as x is there and the row-wide sum only has to be ready for the epilogue, which
+            // multiplies by r (first layer: x = the token embeddings, else the residual stream X as the phase before left it)
             const float* gain = is_lm ? a.final_norm : (kind == PH_QKV ? a.an[l] : a.fn[l]);
             const bool src_embed = (is_lm ? a.n_layers : ph) == 0;
             const unsigned fin = (is_lm || kind == PH_QKV) ? step_flag(l - 1, PH_DOWN) : step_flag(l, PH_O);
-            float4 xv[STEP_XR], gn[STEP_XR];
             const int n4 = M * d / 4;
             float ss0 = 0.f, ss1 = 0.f;
 #pragma unroll
             for (int i = 0; i < STEP_XR; ++i) {
                 const int g = tid + i * STEP_THREADS;
-                xv[i] = make_float4(0.f, 0.f, 0.f, 0.f); gn[i] = xv[i];
                 if (g < n4) {
                     const int m = g * 4 >= d ? 1 : 0, c = g * 4 - m * d;
-                    gn[i] = *reinterpret_cast<const float4*>(gain + c);
+                    const float4 gn = *reinterpret_cast<const float4*>(gain + c);
+                    float4 xv;
                     if (src_embed) {
                         const uint2 e = *reinterpret_cast<const uint2*>(a.embed + (size_t)a.tok[m] * d + c);
-                        xv[i] = make_float4(__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xFFFF0000u),
-                                            __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xFFFF0000u));
+                        xv = make_float4(__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xFFFF0000u),
+                                         __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xFFFF0000u));
                     } else {
-                        xv[i] = poll4(bX, g * 4, fin);
+                        xv = poll4(bX, g * 4, fin);
                     }
-                    const float s = xv[i].x * xv[i].x + xv[i].y * xv[i].y + xv[i].z * xv[i].z + xv[i].w * xv[i].w;
+                    put_planes(m, c, xv.x * gn.x, xv.y * gn.y, xv.z * gn.z, xv.w * gn.w);
+                    const float s = xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
                     if (m == 0) ss0 += s; else ss1 += s;
                 }
             }
             ss0 = wsum(ss0); ss1 = wsum(ss1);
-            if (lane == 0) { s_part[wave][0] = ss0; s_part[wave][1] = ss1; }
-            if (!alive()) return;
-            float rs0 = 0.f, rs1 = 0.f;                                         // every lane adds the wavefronts' sums itself
-#pragma unroll
-            for (int w = 0; w < STEP_WAVES; ++w) { rs0 += s_part[w][0]; rs1 += s_part[w][1]; }
-            rs0 = 1.0f / sqrtf(rs0 / (float)d + a.eps);
-            rs1 = 1.0f / sqrtf(rs1 / (float)d + a.eps);
-#pragma unroll
-            for (int i = 0; i < STEP_XR; ++i) {
-                const int g = tid + i * STEP_THREADS;
-                if (g < n4) {
-                    const int m = g * 4 >= d ? 1 : 0, c = g * 4 - m * d;
-                    const float r = m == 0 ? rs0 : rs1;
-                    put_planes(m, c, xv[i].x * r * gn[i].x, xv[i].y * r * gn[i].y, xv[i].z * r * gn[i].z, xv[i].w * r * gn[i].w);
-                }
-            }
+            if (lane == 0) { s_part[wave][0] = ss0; s_part[wave][1] = ss1; }      // read behind the staging barrier: row_scale()
         } else if (kind == PH_O) {
             // the attention output: every workgroup combines the key splits of the whole rows itself (a few KB).  Four
             // columns per item; the (max, sum) of up to four splits at a time, then their weighted partial outputs.
@@ -633,15 +644,17 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
             // ---- logits: a wavefront owns whole 16-row tiles of the vocabulary, no sharing of K ----
             const int steps_d = d >> 5;
             const int v_tiles = (a.V + 15) / 16;
+            const float rs_row = row_scale(min(li, M - 1));
             for (int tw = wg * STEP_WAVES + wave; tw < v_tiles; tw += G * STEP_WAVES) {
                 const uint32_t tile_off = step_tile_off(tw * 16 + li, d, lq);
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                 for (int sb = 0; sb < steps_d; sb += STEP_MAXS) {
                     const int nn = min(STEP_MAXS, steps_d - sb);
                     wfetch(a.lm_head, tile_off, sb, nn);
-                    const f32x4 part = wmma(sb, nn);
+                    const f32x4 part = wmma(plane_off(sb), nn);
                     acc[0] += part[0]; acc[1] += part[1]; acc[2] += part[2]; acc[3] += part[3];
                 }
+                acc[0] *= rs_row; acc[1] *= rs_row; acc[2] *= rs_row; acc[3] *= rs_row;
                 // lane holds D[column tw*16 + 4 lq + e][row li]; row m = b * q_len + j gets logits if j >= q_len - logit_rows
                 if (row_ok) {
                     const int bq = li >> qs, j = li & qs, r = j - (q_len - a.logit_rows);
@@ -662,31 +675,26 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
         }
 
         // ---- the workgroup's tiles ----
-        const int K = kind == PH_O ? nq : (kind == PH_DOWN ? ff : d), steps = K >> 5;
-        const int wsh = kind == PH_GU ? 2 : 3, WS = 1 << wsh;
-        const int wv = kind == PH_GU ? (wave & 3) : wave;
-        const int s0 = (wv * steps) >> wsh, n = (((wv + 1) * steps) >> wsh) - s0;
-        const unsigned fout = step_flag(l, kind);
-        for (int u = u0; u < n_tiles; u += G) {
-            if (have_ph != ph || have_u != u) {                                  // a further tile of this phase
-                fetch_tile(l, kind, u);
-                have_ph = ph; have_u = u;
-            }
+        // One tile per workgroup and phase (the host admits no model with more tiles than workgroups): its weights were
+        // asked for at the top of an earlier phase.  A loop over further tiles here made the compiler carry a second copy
+        // of the weight registers and the addresses of 16 more loads through every phase.
+        {
+            const int u = u0;
             const int c = u * 16 + 4 * lq;                                       // lane's four output columns (wavefront 0)
             // what the epilogue needs from memory is requested before the multiply
             float4 x_old = make_float4(0.f, 0.f, 0.f, 0.f);
             float2 rc0 = make_float2(1.f, 0.f), rc1 = make_float2(1.f, 0.f);
             if (wave == 0 && row_ok) {
                 if (kind == PH_O || kind == PH_DOWN) {
-                    x_old = u == u0 ? x_first : residual(u);
+                    x_old = x_first;
                 } else if (kind == PH_QKV && c < nq + nkv) {
                     const int hc = c & (HD - 1);
                     rc0 = a.rope[(size_t)m_row * (HD / 2) + hc / 2];
                     rc1 = a.rope[(size_t)m_row * (HD / 2) + hc / 2 + 1];
                 }
             }
-            const f32x4 acc = wmma(s0, n);
-            __syncthreads();                                                     // red[] is free (an earlier tile's epilogue has read it)
+            const f32x4 acc = wmma(boff, n);
+            // red[] is free: whoever read it last did so before the workgroup-wide check that ended its phase
             *reinterpret_cast<f32x4*>(&red[wave][lane * 4]) = acc;
             __syncthreads();
             if (wave == 0 && row_ok) {
@@ -695,14 +703,19 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                     const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
                     t[0] += p[0]; t[1] += p[1]; t[2] += p[2]; t[3] += p[3];
                 }
+                if (kind == PH_QKV || kind == PH_GU) {                           // the deferred RMS scale of the input row
+                    const float rs = row_scale(li);
+                    t[0] *= rs; t[1] *= rs; t[2] *= rs; t[3] *= rs;
+                }
                 if (kind == PH_GU) {
                     for (int v = WS; v < STEP_WAVES; ++v) {
                         const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
                         t2[0] += p[0]; t2[1] += p[1]; t2[2] += p[2]; t2[3] += p[3];
                     }
+                    const float rs = row_scale(li);
                     float h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = t[e] / (1.0f + __expf(-t[e])) * t2[e];
+                    for (int e = 0; e < 4; ++e) h[e] = t[e] / (1.0f + __expf(-t[e])) * (t2[e] * rs);
                     st_cells4(bACT, li * ff + c, h[0], h[1], h[2], h[3], fout);
                 } else if (kind == PH_O || kind == PH_DOWN) {
                     st_cells4(bX, li * d + c, x_old.x + t[0], x_old.y + t[1], x_old.z + t[2], x_old.w + t[3], fout);
@@ -761,6 +774,8 @@ bool step_fits(const bs_model_cfg& c, int B, int q_len, int n_layers) {
     // other (measured, 4 layers x 1024 wide, 128 heads, 128256 tokens: 340 us against 190 us of the kernel-per-phase path)
     if (c.head_dim != 64 || c.vocab > 3 * 16 * STEP_WAVES * step_grid() / 2) return false;
     if (c.d_model % 32 || nq % 32 || c.d_ff % 32 || nkv % 16) return false;
+    const int grid = step_grid();
+    if ((nq + 2 * nkv) / 16 > grid || c.d_ff / 16 > grid || c.d_model / 16 > grid) return false;   // one tile per workgroup and phase
     const int R = c.n_heads / c.n_kv_heads * q_len;
     if (R > 16) return false;
     auto share = [](int K, int waves) { return (K / 32 + waves - 1) / waves; };     // k steps per wavefront
