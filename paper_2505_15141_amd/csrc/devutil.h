@@ -13,11 +13,10 @@ __device__ __forceinline__ float to_f(float v) { return v; }
 __device__ __forceinline__ float to_f(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 template <typename T> __device__ __forceinline__ T from_f(float f);
 template <> __device__ __forceinline__ float from_f<float>(float f) { return f; }
-template <> __device__ __forceinline__ uint16_t from_f<uint16_t>(float f) {   // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+// float -> bf16, round to nearest even: gfx950 has the conversion in hardware (v_cvt_pk_bf16_f32, two values per
+// instruction), which the compiler emits for a cast to __bf16; four integer instructions per value otherwise
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+template <> __device__ __forceinline__ uint16_t from_f<uint16_t>(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
 __device__ __forceinline__ float wsum(float v) {
 #pragma unroll
@@ -47,7 +46,8 @@ template <> __device__ __forceinline__ size_t v_index<uint16_t>(int key, int d, 
 __device__ __forceinline__ uint4 ldg16(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-    return (uint32_t)from_f<uint16_t>(a) | ((uint32_t)from_f<uint16_t>(b) << 16);
+    const bf16x2_hw v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(uint32_t, v);
 }
 __device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
     float r[8];
