@@ -191,11 +191,12 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
     };
 
     // r of row m from the wavefronts' partial sums of squares (valid behind the staging barrier of a normed phase)
+    const float inv_d = 1.0f / (float)d;
     auto row_scale = [&](int m) -> float {
         float t = 0.f;
 #pragma unroll
         for (int w = 0; w < STEP_WAVES; ++w) t += s_part[w][m];
-        return 1.0f / sqrtf(t / (float)d + a.eps);
+        return __builtin_amdgcn_rsqf(t * inv_d + a.eps);     // one instruction, 1 ulp: this sits in the epilogue, on the critical path
     };
 
     // ---- per-row facts from the prep kernel (positions, tokens) ----------------------------------------------------------
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
         // puts these couple of hundred scalar instructions between the staging barrier and the first multiply, where they
         // are on the critical path (a wavefront issues one of them every four to five cycles).
         const int K = kind == PH_O ? nq : (kind == PH_DOWN ? ff : d), steps = K >> 5;
-        const int wsh = kind == PH_GU ? 2 : 3, WS = 1 << wsh;
+        const int wsh = kind == PH_GU ? 2 : 3;
         const int wv = kind == PH_GU ? (wave & 3) : wave;
         int s0 = (wv * steps) >> wsh, n = (((wv + 1) * steps) >> wsh) - s0;
         unsigned fout = step_flag(l, kind);
@@ -617,7 +618,7 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                     }
                     mm = gm;
                 }
-                const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+                const float inv = lsum > 0.f ? __builtin_amdgcn_rcpf(lsum) : 0.f;
                 put_planes(m, col, o4[0] * inv, o4[1] * inv, o4[2] * inv, o4[3] * inv);
             }
         } else {
@@ -698,24 +699,27 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
             *reinterpret_cast<f32x4*>(&red[wave][lane * 4]) = acc;
             __syncthreads();
             if (wave == 0 && row_ok) {
-                f32x4 t = {0.f, 0.f, 0.f, 0.f}, t2 = {0.f, 0.f, 0.f, 0.f};
-                for (int v = 0; v < WS; ++v) {
-                    const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
-                    t[0] += p[0]; t[1] += p[1]; t[2] += p[2]; t[3] += p[3];
+                // all eight shares are read at once (a loop up to a run-time count reads them one LDS round trip after the
+                // other); gate / up: the first four wavefronts hold the gate columns, the last four the up columns
+                f32x4 pw[STEP_WAVES];
+#pragma unroll
+                for (int v = 0; v < STEP_WAVES; ++v) pw[v] = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
+                f32x4 t, t2;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    t[e] = (pw[0][e] + pw[1][e]) + (pw[2][e] + pw[3][e]);
+                    t2[e] = (pw[4][e] + pw[5][e]) + (pw[6][e] + pw[7][e]);
                 }
+                if (kind != PH_GU) { t[0] += t2[0]; t[1] += t2[1]; t[2] += t2[2]; t[3] += t2[3]; }
                 if (kind == PH_QKV || kind == PH_GU) {                           // the deferred RMS scale of the input row
                     const float rs = row_scale(li);
                     t[0] *= rs; t[1] *= rs; t[2] *= rs; t[3] *= rs;
                 }
                 if (kind == PH_GU) {
-                    for (int v = WS; v < STEP_WAVES; ++v) {
-                        const f32x4 p = *reinterpret_cast<const f32x4*>(&red[v][lane * 4]);
-                        t2[0] += p[0]; t2[1] += p[1]; t2[2] += p[2]; t2[3] += p[3];
-                    }
                     const float rs = row_scale(li);
                     float h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = t[e] / (1.0f + __expf(-t[e])) * (t2[e] * rs);
+                    for (int e = 0; e < 4; ++e) h[e] = t[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-t[e])) * (t2[e] * rs);
                     st_cells4(bACT, li * ff + c, h[0], h[1], h[2], h[3], fout);
                 } else if (kind == PH_O || kind == PH_DOWN) {
                     st_cells4(bX, li * d + c, x_old.x + t[0], x_old.y + t[1], x_old.z + t[2], x_old.w + t[3], fout);
