@@ -53,7 +53,7 @@ __device__ __forceinline__ u32x4 ld_cells2(DevBuf b, int c) { return __builtin_a
 constexpr int STEP_WAVES = 8, STEP_THREADS = 64 * STEP_WAVES;
 constexpr int STEP_MAXS = 16;            // k steps of 32 columns one wavefront may own in a phase (K <= 4096)
 constexpr int STEP_XR = 4;               // groups of four staged input values per lane (2 rows x 4096 columns / 4 / 512 lanes)
-constexpr int STEP_MB = 8;               // attention partials the O projection's staging merges per round of polls
+constexpr int STEP_MB = 6;               // attention partials the O projection's staging merges per round of polls
 constexpr int STEP_BLK = 1;              // key blocks a wavefront of an attention unit takes before more splits are used
 
 // tiled weights: byte offset of lane (row local % 16, k-slot lq) in the 16-row tile that holds row `local`; a k step is
@@ -347,14 +347,34 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                         for (int t = 0; t < DT; ++t) vfa[j][t] = make_uint4(0u, 0u, 0u, 0u);
                     }
                 }
+                // The queries of this unit's rows and, for an own-key unit, the keys and values of this pass's rows (they arrive
+                // together, from the QKV phase): one round of loads, addressed relative to the query buffer.
+                // Key j = li of this pass (row m_first + j).  Values: lane (dimension 16t + li, k-slot lq) holds keys
+                // (e >> 2) * 16 + 4 lq + (e & 3), so only k-slot 0, e < q_len exist; lane (li, lq) polls for the tiles
+                // t = lq, lq + 4, .. (four cells of dimensions 4 * (li / 4) .., the lane keeps its own) and k-slot 0 collects them.
+                constexpr int NQ = 2 * DS, NK = 2 * DS, NV = DT / 2;
+                float4 kv_[NK + NV];
                 {
-                    // the queries of this unit's rows
                     const float scale = 1.0f / sqrtf((float)HD);
-                    int qc[2 * DS];
-                    float4 qv[2 * DS];
+                    const int kvn_rel = (int)((reinterpret_cast<const char*>(a.KVN) - reinterpret_cast<const char*>(a.Q)) >> 3);
+                    int qc[NQ + NK + NV];
+                    float4 qo[NQ + NK + NV];
 #pragma unroll
-                    for (int i = 0; i < 2 * DS; ++i) qc[i] = ((m_first + qi_r) * H + at_kvh * Gq + g_r) * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4;
-                    poll4n(bQ, qc, fin, qv);
+                    for (int i = 0; i < NQ; ++i) qc[i] = ((m_first + qi_r) * H + at_kvh * Gq + g_r) * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4;
+#pragma unroll
+                    for (int i = 0; i < NK; ++i)
+                        qc[NQ + i] = (att_own && wave == 0 && li < q_len)
+                                         ? kvn_rel + (m_first + li) * 2 * nkv + at_kvh * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4 : -1;
+#pragma unroll
+                    for (int i = 0; i < NV; ++i)
+                        qc[NQ + NK + i] = (att_own && wave == 0 && ((i & 1) == 0 || q_len > 1))
+                                              ? kvn_rel + (m_first + (i & 1)) * 2 * nkv + nkv + at_kvh * HD + (lq + 4 * (i >> 1)) * 16 + (li & ~3) : -1;
+                    poll4n(bQ, qc, fin, qo);
+                    float4 qv[NQ];
+#pragma unroll
+                    for (int i = 0; i < NQ; ++i) qv[i] = qo[i];
+#pragma unroll
+                    for (int i = 0; i < NK + NV; ++i) kv_[i] = qo[NQ + i];
 #pragma unroll
                     for (int ds = 0; ds < DS; ++ds) {
                         float v[8] = {qv[2 * ds].x, qv[2 * ds].y, qv[2 * ds].z, qv[2 * ds].w, qv[2 * ds + 1].x, qv[2 * ds + 1].y, qv[2 * ds + 1].z, qv[2 * ds + 1].w};
@@ -385,22 +405,7 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                             old_fetch(blk, kf, vf);                             // more blocks than were foreseen: one at a time
                         }
                     } else {
-                        n_vis = q_len;
-                        // key j = li of this pass (row m_first + j): already bf16, so the hi plane is exact.  Values: lane
-                        // (dimension 16t + li, k-slot lq) holds keys (e >> 2) * 16 + 4 lq + (e & 3), so only k-slot 0, e < q_len
-                        // exist.  Lane (li, lq) polls for the tiles t = lq, lq + 4, .. (four cells of dimensions 4 * (li / 4) ..,
-                        // the lane keeps its own) and k-slot 0 collects them: one round of loads for keys and values.
-                        constexpr int NK = 2 * DS, NV = DT / 2;
-                        int kc_[NK + NV];
-                        float4 kv_[NK + NV];
-#pragma unroll
-                        for (int i = 0; i < NK; ++i)
-                            kc_[i] = li < q_len ? (m_first + li) * 2 * nkv + at_kvh * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4 : -1;
-#pragma unroll
-                        for (int i = 0; i < NV; ++i)
-                            kc_[NK + i] = ((i & 1) == 0 || q_len > 1)
-                                              ? (m_first + (i & 1)) * 2 * nkv + nkv + at_kvh * HD + (lq + 4 * (i >> 1)) * 16 + (li & ~3) : -1;
-                        poll4n(bKVN, kc_, fin, kv_);
+                        n_vis = q_len;                                           // the keys are bf16 already: the hi plane is exact
 #pragma unroll
                         for (int ds = 0; ds < DS; ++ds) {
                             const float4 k0 = kv_[2 * ds], k1 = kv_[2 * ds + 1];
@@ -587,18 +592,20 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                 const int base = ((m * H + h) * (S + 1)) * PCELLS;
                 float mm = -INFINITY, lsum = 0.f, o4[4] = {0.f, 0.f, 0.f, 0.f};
                 for (int sx = 0; sx <= Se; sx += STEP_MB) {                            // the used splits, then the own keys' partial (slot S)
-                    // (max, sum, pad, pad) of up to STEP_MB partials in one round of loads, their four output cells in another
+                    // (max, sum, pad, pad) of and the four output cells of up to STEP_MB partials in one round of loads
                     // (every cell of a used partial is written, also by a unit that had nothing to attend to)
-                    int pc[STEP_MB], slot[STEP_MB];
-                    float4 ml[STEP_MB], ov[STEP_MB];
+                    int pc[2 * STEP_MB], slot[STEP_MB];
+                    float4 pv_[2 * STEP_MB], ml[STEP_MB], ov[STEP_MB];
 #pragma unroll
                     for (int q = 0; q < STEP_MB; ++q) slot[q] = sx + q < Se ? sx + q : (sx + q == Se ? S : -1);
 #pragma unroll
-                    for (int q = 0; q < STEP_MB; ++q) pc[q] = slot[q] >= 0 ? base + slot[q] * PCELLS + HD : -1;
-                    poll4n(bPA, pc, fin, ml);
+                    for (int q = 0; q < STEP_MB; ++q) {
+                        pc[2 * q] = slot[q] >= 0 ? base + slot[q] * PCELLS + HD : -1;
+                        pc[2 * q + 1] = slot[q] >= 0 ? base + slot[q] * PCELLS + d0 : -1;
+                    }
+                    poll4n(bPA, pc, fin, pv_);
 #pragma unroll
-                    for (int q = 0; q < STEP_MB; ++q) pc[q] = slot[q] >= 0 ? base + slot[q] * PCELLS + d0 : -1;
-                    poll4n(bPA, pc, fin, ov);
+                    for (int q = 0; q < STEP_MB; ++q) { ml[q] = pv_[2 * q]; ov[q] = pv_[2 * q + 1]; }
                     float gm = mm;
 #pragma unroll
                     for (int q = 0; q < STEP_MB; ++q)
