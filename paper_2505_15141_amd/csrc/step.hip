@@ -360,6 +360,9 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                     int qc[NQ + NK + NV];
                     float4 qo[NQ + NK + NV];
 #pragma unroll
+                    // Every wavefront polls for the queries, also one that has no block to multiply them with: a unit must not
+                    // write its partial before the QKV phase of this layer has run, or it would overwrite what the O projection
+                    // of the layer before is still reading (a unit without any cached key would run layers ahead).
                     for (int i = 0; i < NQ; ++i) qc[i] = ((m_first + qi_r) * H + at_kvh * Gq + g_r) * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4;
 #pragma unroll
                     for (int i = 0; i < NK; ++i)
