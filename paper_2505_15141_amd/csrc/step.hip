@@ -317,11 +317,12 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
             f32x4 o[DT];
 #pragma unroll
             for (int t = 0; t < DT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (at_pos0 >= 0) {
+            {
                 // this wavefront's blocks: its share of the split's cached keys (the first requested up front, before
-                // anything is polled for), or (own-key unit, wavefront 0) the keys of this pass's own rows as one block
+                // anything is polled for), or (own-key unit, wavefront 0) the keys of this pass's own rows as one block;
+                // none for a sequence that was left out (at_pos0 < 0: no cached blocks either), which still waits below
                 const int n_old = (!att_own && blk0 < blk_end) ? (blk_end - blk0 + STEP_WAVES - 1) / STEP_WAVES : 0;
-                const int n_it = att_own ? (wave == 0 ? 1 : 0) : n_old;
+                const int n_it = at_pos0 < 0 ? 0 : (att_own ? (wave == 0 ? 1 : 0) : n_old);
                 uint4 kfa[STEP_BLK][2][DS], vfa[STEP_BLK][DT], qh[DS], ql[DS];
                 auto old_fetch = [&](int blk, uint4 (&kf)[2][DS], uint4 (&vf)[DT]) {
 #pragma unroll
@@ -360,17 +361,18 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                     int qc[NQ + NK + NV];
                     float4 qo[NQ + NK + NV];
 #pragma unroll
-                    // Every wavefront polls for the queries, also one that has no block to multiply them with: a unit must not
-                    // write its partial before the QKV phase of this layer has run, or it would overwrite what the O projection
-                    // of the layer before is still reading (a unit without any cached key would run layers ahead).
+                    // Every wavefront polls for the queries, also one that has no block to multiply them with and one of a
+                    // sequence that was left out (the QKV phase writes query cells for every row): a unit must not write its
+                    // partial before the QKV phase of this layer has run, or it would overwrite what the O projection of the
+                    // layer before is still reading (a unit without any cached key would run layers ahead).
                     for (int i = 0; i < NQ; ++i) qc[i] = ((m_first + qi_r) * H + at_kvh * Gq + g_r) * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4;
 #pragma unroll
                     for (int i = 0; i < NK; ++i)
-                        qc[NQ + i] = (att_own && wave == 0 && li < q_len)
+                        qc[NQ + i] = (att_own && n_it > 0 && li < q_len)
                                          ? kvn_rel + (m_first + li) * 2 * nkv + at_kvh * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4 : -1;
 #pragma unroll
                     for (int i = 0; i < NV; ++i)
-                        qc[NQ + NK + i] = (att_own && wave == 0 && ((i & 1) == 0 || q_len > 1))
+                        qc[NQ + NK + i] = (att_own && n_it > 0 && ((i & 1) == 0 || q_len > 1))
                                               ? kvn_rel + (m_first + (i & 1)) * 2 * nkv + nkv + at_kvh * HD + (lq + 4 * (i >> 1)) * 16 + (li & ~3) : -1;
                     poll4n(bQ, qc, fin, qo);
                     float4 qv[NQ];

@@ -264,3 +264,26 @@ def test_resident_step_gives_up_after_its_poll_limit_and_recovers():
     assert int(ws[:4].view(torch.int32).cpu()[0]) & 16 == 0
     ref = forward(c, W, toks[0], storage="bf16")
     assert np.max(np.abs(lg[0].cpu().numpy() - ref[n_prefix:n_prefix + 2])) < TOL["bf16"]
+
+
+def test_resident_step_with_a_sequence_left_out():
+    """Two sequences, one row each, on a small packed bf16 model (the resident one-launch pass): sequence 1 has no room
+    in its cache and is left out.  Its attention units have nothing to do in any layer and must still keep in step with
+    the others; sequence 0's logits are right, bit 0 of the status word is set and bit 16 is not."""
+    b = bs()
+    c = MID
+    max_len = 48
+    W, m, kv = setup(c, 2, max_len, seed=23, packed=True)
+    toks = synth.make_prompts(2, 40, c["vocab"], 24)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    b.prefill(m, kv, dt, 30)
+    ws = torch.zeros(m.forward_workspace_bytes(2, 1, max_len), dtype=torch.uint8, device="cuda")
+    kvl = torch.tensor([30, max_len], dtype=torch.int32, device="cuda")       # sequence 1: position 48 of 48
+    for step in range(3):                             # several passes in a row: every layer of every pass hands over in step
+        lg = b.verify_forward(m, kv, dt[:, 30 + step:31 + step].contiguous(), kvl, workspace=ws)
+        torch.cuda.synchronize()
+        status = int(ws[:4].view(torch.int32).cpu()[0])
+        assert status & 1 and not status & 16, status
+        ref = forward(c, W, toks[0, :31 + step], storage="bf16")
+        assert np.max(np.abs(lg[0, 0].cpu().numpy() - ref[30 + step])) < TOL["bf16"], step
+        kvl[0] += 1
