@@ -53,7 +53,7 @@ __device__ __forceinline__ u32x4 ld_cells2(DevBuf b, int c) { return __builtin_a
 constexpr int STEP_WAVES = 8, STEP_THREADS = 64 * STEP_WAVES;
 constexpr int STEP_MAXS = 16;            // k steps of 32 columns one wavefront may own in a phase (K <= 4096)
 constexpr int STEP_XR = 4;               // groups of four staged input values per lane (2 rows x 4096 columns / 4 / 512 lanes)
-constexpr int STEP_MB = 6;               // attention partials the O projection's staging merges per round of polls
+constexpr int STEP_MB = 5;               // attention partials the O projection's staging merges per round of polls
 constexpr int STEP_XCOPIES = 2;          // copies of the residual stream's exchange cells: every workgroup of a phase polls all of them
 constexpr int STEP_BLK = 1;              // key blocks a wavefront of an attention unit takes before more splits are used
 
@@ -312,6 +312,7 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
             float* wm = reinterpret_cast<float*>(xs);                           // [waves][16]
             float* wl = wm + STEP_WAVES * 16;                                   // [waves][16]
             float* wo = wl + STEP_WAVES * 16;                                   // [waves][R][HD + 1]
+            uint4* sq = reinterpret_cast<uint4*>(wo + STEP_WAVES * R * (HD + 1));  // [2 planes][DS][64 lanes]: the queries as MFMA operands
             const int m_first = at_b * q_len;
             const unsigned fin = step_flag(l, PH_QKV), fout = step_flag(l, PH_ATT);
             const char* kbb = kc + (((size_t)at_b * KVH + at_kvh) * (size_t)a.cache_len * HD) * 2;
@@ -358,18 +359,20 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
                 // Key j = li of this pass (row m_first + j).  Values: lane (dimension 16t + li, k-slot lq) holds keys
                 // (e >> 2) * 16 + 4 lq + (e & 3), so only k-slot 0, e < q_len exist; lane (li, lq) polls for the tiles
                 // t = lq, lq + 4, .. (four cells of dimensions 4 * (li / 4) .., the lane keeps its own) and k-slot 0 collects them.
+                // Wavefront 0 polls for the whole unit and hands the queries on through LDS: eight wavefronts polling each for
+                // itself see the data up to a round trip apart, and the unit is as late as its last one.
                 constexpr int NQ = 2 * DS, NK = 2 * DS, NV = DT / 2;
                 float4 kv_[NK + NV];
-                {
+                if (wave == 0) {
                     const float scale = 1.0f / sqrtf((float)HD);
                     const int kvn_rel = (int)((reinterpret_cast<const char*>(a.KVN) - reinterpret_cast<const char*>(a.Q)) >> 3);
                     int qc[NQ + NK + NV];
                     float4 qo[NQ + NK + NV];
 #pragma unroll
-                    // Every wavefront polls for the queries, also one that has no block to multiply them with and one of a
-                    // sequence that was left out (the QKV phase writes query cells for every row): a unit must not write its
-                    // partial before the QKV phase of this layer has run, or it would overwrite what the O projection of the
-                    // layer before is still reading (a unit without any cached key would run layers ahead).
+                    // It polls whether or not anybody has a block to multiply the queries with, also for a sequence that was
+                    // left out (the QKV phase writes query cells for every row): a unit must not write its partial before the
+                    // QKV phase of this layer has run, or it would overwrite what the O projection of the layer before is still
+                    // reading (a unit without any cached key would run layers ahead).
                     for (int i = 0; i < NQ; ++i) qc[i] = ((m_first + qi_r) * H + at_kvh * Gq + g_r) * HD + (i >> 1) * 32 + lq * 8 + (i & 1) * 4;
 #pragma unroll
                     for (int i = 0; i < NK; ++i)
@@ -391,7 +394,14 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = rvalid ? v[e] * scale : 0.f;
                         split8(v, qh[ds], ql[ds]);
+                        sq[ds * 64 + lane] = qh[ds];
+                        sq[(DS + ds) * 64 + lane] = ql[ds];
                     }
+                }
+                if (!alive()) return;
+                if (wave != 0) {
+#pragma unroll
+                    for (int ds = 0; ds < DS; ++ds) { qh[ds] = sq[ds * 64 + lane]; ql[ds] = sq[(DS + ds) * 64 + lane]; }
                 }
                 for (int it = 0; it < n_it; ++it) {
                     const bool own = it >= n_old;
@@ -785,7 +795,7 @@ __global__ __launch_bounds__(STEP_THREADS) void dec_step_kernel(StepArgs a) {
 static size_t step_lds_bytes(int M, int d, int nq, int ff, int hd, int R) {
     const int kmax = d > nq ? (d > ff ? d : ff) : (nq > ff ? nq : ff);
     const size_t planes = (size_t)2 * M * (kmax + 8) * 2;
-    const size_t att = ((size_t)2 * STEP_WAVES * 16 + (size_t)STEP_WAVES * R * (hd + 1)) * 4;
+    const size_t att = ((size_t)2 * STEP_WAVES * 16 + (size_t)STEP_WAVES * R * (hd + 1)) * 4 + (size_t)2 * (hd / 32) * 64 * 16;
     return planes > att ? planes : att;
 }
 
