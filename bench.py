@@ -155,6 +155,44 @@ def sampling_stage(bs, torch, np, stream, cases=SAMPLING_CASES, reps=20):
     return out
 
 
+def draft_step_stage(bs, synth, torch, np, stream, prefix=1024, reps=20):
+    """The draft model's forward pass by itself (one launch of the resident step kernel per pass): one row and two rows
+    against 1024 cached tokens, ten passes captured in a graph and replayed, host clock around the replays."""
+    dc = synth.LLAMA7B_DRAFT
+    out = {}
+    with torch.cuda.stream(stream):
+        draft = bs.Model(dc, gpu_weights(dc, 2, torch)).pack(release_originals=True)
+        max_len = prefix + 3600
+        dkv = bs.KV(draft, 1, max_len)
+        tokens = torch.from_numpy(synth.make_prompts(1, max_len, dc["vocab"], 3).astype(np.int32)).cuda()
+        bs.prefill(draft, dkv, tokens, prefix)
+        kvl = torch.full((1,), prefix, dtype=torch.int32, device="cuda")
+        ws = torch.zeros(draft.forward_workspace_bytes(1, 2, max_len), dtype=torch.uint8, device="cuda")
+        lg = torch.empty(1, 1, dc["vocab"], dtype=torch.float32, device="cuda")
+        for q_len in (1, 2):
+            q = tokens[:, prefix:prefix + q_len].contiguous()
+            for _ in range(3):
+                bs.verify_forward(draft, dkv, q, kvl, logit_rows=1, workspace=ws, logits=lg)
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(10):
+                    bs.verify_forward(draft, dkv, q, kvl, logit_rows=1, workspace=ws, logits=lg)
+            g.replay(); stream.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                g.replay()
+            stream.synchronize()
+            out[f"rows_{q_len}"] = {"us_per_pass": round((time.perf_counter() - t0) / (10 * reps) * 1e6, 1)}
+        out["status_word"] = int(ws[:4].view(torch.int32).cpu()[0])
+    nq, nkv = dc["n_heads"] * dc["head_dim"], dc["n_kv_heads"] * dc["head_dim"]
+    wbytes = 2 * (dc["n_layers"] * (dc["d_model"] * (nq + 2 * nkv) + nq * dc["d_model"] + 3 * dc["d_model"] * dc["d_ff"]) + dc["vocab"] * dc["d_model"])
+    out["weight_bytes"] = int(wbytes)
+    out["roofline"] = hbm_roofline("bs::dec_step_kernel<64> (+ prep), one row", wbytes / out["rows_1"]["us_per_pass"] / 1e3,
+                                   "every draft weight once per pass")
+    return out
+
+
 def stage_probes(bs, synth, torch, np, stream):
     """HBM rates of the two other bandwidth-bound stages at the sizes where they matter (HIP-event timed):
     the stand-alone sampling workload (B=64, gamma=8, V=32000, bf16 logits) and the verification attention
@@ -349,6 +387,9 @@ def main():
     ap.add_argument("--only-sampling", action="store_true",
                     help="run only the stand-alone sampling call at B = 64, gamma = 8, V = 32000 (200 calls) and print its JSON "
                          "(for profiling it by itself); not the benchmark line")
+    ap.add_argument("--only-draft-step", action="store_true",
+                    help="run only the draft model's forward pass (one and two rows, 1024 cached tokens; graphs of ten passes) and "
+                         "print its JSON (for profiling it by itself); not the benchmark line")
     ap.add_argument("--only-multi-draft", action="store_true",
                     help="run only that stage and print its JSON (for profiling it by itself); not the benchmark line")
     ap.add_argument("--pmc-mode", action="store_true",
@@ -369,6 +410,9 @@ def main():
     torch.cuda.set_device(0)
     if args.only_sampling:
         print(json.dumps({"stage": "sampling", **sampling_stage(bs, torch, np, torch.cuda.Stream(), SAMPLING_CASES[:1], reps=200)}))
+        return
+    if args.only_draft_step:
+        print(json.dumps({"stage": "draft_forward_pass", **draft_step_stage(bs, synth, torch, np, torch.cuda.Stream())}))
         return
     if args.only_multi_draft:
         print(json.dumps({"stage": "rounds_b32_ctx8192_three_drafts",
