@@ -46,18 +46,19 @@ struct StepArgs {
     int B, q_len, M, logit_rows;
     const int32_t* pos; const int32_t* tok; const float2* rope;      // written by the prep kernel
     char* kv; size_t kv_layer; int cache_len;
-    void *X, *Q, *KVN, *PA, *ACT;        // exchange buffers of 8-byte cells {value, flag}: residual [M][d], queries [M][nq],
-                                         // new keys|values [M][2 nkv], attention partials [M][H][splits][hd + 4], SwiGLU output [M][ff];
-                                         // every flag is zero when the kernel starts (the prep kernel clears them)
+    void *X, *Q, *KVN, *PA, *ACT;        // exchange buffers of 8-byte cells {value, flag}: residual [copies][M][d], queries [M][nq],
+                                         // new keys|values [M][2 nkv], attention partials [M][H][splits + 1][hd + 4] (the last slot:
+                                         // the keys of the pass's own rows), SwiGLU output [M][ff]; every flag is zero when the
+                                         // kernel starts (the prep kernel clears them)
     int32_t* status; int splits;
     float* logits; size_t logits_bstride;
     unsigned spin_limit;                 // polls of a cell before a workgroup gives up (status bit 16)
     int kp;                              // set by the launcher: padded row of the staged planes
 };
 bool step_fits(const bs_model_cfg& c, int B, int q_len, int n_layers);
-// bytes of the exchange buffers X, Q, KVN, PA, ACT (each 256-byte aligned, in this order; off[i] = where buffer i starts)
 // splits of the cached keys the resident step uses for B sequences and this cache length; 0: no room for the units
 int step_splits(const bs_model_cfg& c, int B, int max_len);
+// bytes of the exchange buffers X, Q, KVN, PA, ACT (each 256-byte aligned, in this order; off[i] = where buffer i starts)
 size_t step_exchange_bytes(const bs_model_cfg& c, int M, int splits, size_t off[5]);
 int step_grid();                         // workgroups of the resident kernel = compute units of the device
 int launch_step(const StepArgs& a, hipStream_t s);

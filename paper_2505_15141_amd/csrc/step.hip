@@ -21,7 +21,12 @@
 // before it starts polling, so they travel while it waits.
 // Every projection phase is the few-row projection of gemm_dec_kernel: a workgroup owns 16 output columns over the
 // whole K, its 8 wavefronts split K and add through LDS, wavefront 0 finishes the columns.  RMSNorm needs no partial
-// sums here: every workgroup stages the whole input rows and reduces them itself.
+// sums here: every workgroup stages the whole input rows (gain . x, as soon as x is there) and adds up their squares
+// itself; the row's scale is applied in the epilogue.
+// At this size the instruction stream counts as much as the memory system: one wavefront retires a dependent
+// instruction every 4-8 cycles, so a few hundred instructions between "the input is there" and "the output is stored"
+// are a microsecond per phase.  What the phase loop needs is therefore worked out ahead of the polls, loops with
+// run-time bounds are kept off that path, and there is one tile per workgroup and phase.
 #include <math.h>
 #include "common.h"
 #include "kernels.h"
