@@ -32,6 +32,10 @@ struct DecArgs {
 };
 bool gemm_dec_fits(int M, int K);
 int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s);
+// The same epilogues (EPI_QKV, EPI_SWIGLU) for up to 16 rows of a wide model: one workgroup per compute unit owns several
+// 16-column units over the whole K.  gemm_rows_units: units per workgroup at most (0: the kernel does not apply), *grid: workgroups.
+int gemm_rows_units(int epi, int M, int N, int K, int* grid);
+int launch_gemm_rows(int epi, const DecArgs& a, hipStream_t s);
 int launch_embed_dec(const int32_t* tok, const void* embed, const float* gain, int M, int d, float* x, void* planes,
                      size_t plane, float* ssq, hipStream_t s);
 

@@ -1007,6 +1007,158 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
     }
 }
 
+// ---- fused projections for a few more rows of a wide model (verification of one sequence) -----------------
+// Between 3 and 16 rows the activations are too many to stage whole in every 16-column workgroup, and the 16-row
+// kernel above needs a consumer kernel per projection for its split-K partial sums.  Where a projection has
+// several 16-column units per compute unit (QKV and gate/up of the verification target) there is a third way:
+// one workgroup per compute unit owns up to ROWS_UMAX consecutive units over the WHOLE K range, its 8 wavefronts
+// split K, every wavefront streams its k steps of all the units and loads the matching activations straight
+// into the MFMA B operand (rows < M only; each k slice is read by one wavefront, so LDS would buy nothing and
+// the B registers are shared by the units), the accumulators meet in LDS and wavefront v finishes unit v with
+// the consumer's work: RMS scale + RoPE + q out + K/V cache write (EPI_QKV), silu(r g) * (r u) as planes
+// (EPI_SWIGLU, a unit being the gate and the up tile of the same 16 columns).  No partial sums, no consumer
+// kernel.  With ONE unit per workgroup (O, down) the activations are twice the weight bytes in L1 traffic and
+// the 16-row kernel + its consumer is faster, which is why EPI_RESID is not offered here.
+constexpr int ROWS_UMAX = 4;
+constexpr int rows_depth(int nt) { return nt <= 1 ? 8 : nt == 2 ? 6 : nt == 3 ? 4 : nt == 4 ? 3 : 2; }   // k steps in flight per wavefront
+
+template <int EPI, int NU>
+__device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float* __restrict__ red) {
+    constexpr int PER = EPI == EPI_SWIGLU ? 2 : 1, NT = NU * PER, DEPTH = rows_depth(NT);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lq = lane >> 4;
+    const bool row_ok = li < a.M;
+    const int m = min(li, a.M - 1);
+    // what the epilogue needs from memory is requested ahead of the operand streams (wavefront v finishes unit v)
+    const int c = (u0 + min(wave, NU - 1)) * 16 + 4 * lq;         // the lane's four output columns there
+    const int hd_mask = a.hd - 1;
+    float ssq = 0.f;
+    float2 rc0 = make_float2(1.f, 0.f), rc1 = make_float2(1.f, 0.f);
+    int p_row = -1;
+    if (wave < NU) {
+        for (int t = 0; t < a.ssq_tiles; ++t) ssq += a.ssq_in[(size_t)m * a.ssq_tiles + t];
+        if (EPI == EPI_QKV) {
+            p_row = a.pos[m];
+            const int hc = c & hd_mask;
+            rc0 = a.rope[(size_t)m * (a.hd / 2) + hc / 2];
+            rc1 = a.rope[(size_t)m * (a.hd / 2) + hc / 2 + 1];
+        }
+    }
+    const int steps = a.K / 32;
+    const int s_begin = (wave * steps) >> 3, s_end = ((wave + 1) * steps) >> 3;
+    const int n = s_end - s_begin, nn = max(n, 1) - 1;
+    const int sb = n > 0 ? s_begin : 0;                            // a wavefront without k steps re-reads step 0 and ignores it
+    const char* wp[NT];                                            // the wavefront's first k step of every tile (uniform)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int local = (u0 + t / PER) * 16;
+        const void* mat;
+        if (EPI == EPI_SWIGLU) mat = a.w[t % PER];
+        else {
+            int seg = 0;
+            if (a.w[1] && local >= a.seg_rows[0]) { local -= a.seg_rows[0]; seg = 1; if (a.w[2] && local >= a.seg_rows[1]) { local -= a.seg_rows[1]; seg = 2; } }
+            mat = a.w[seg];
+        }
+        wp[t] = reinterpret_cast<const char*>(mat) + ((size_t)(local >> 6) * 64 * a.K + ((local >> 4) & 3) * 512 + (size_t)sb * 2048) * 2;
+    }
+    const uint32_t loff = lane * 16;                               // a k step of a tile is one contiguous kilobyte, 16 bytes per lane
+    const uint16_t* bh = a.xh + (size_t)m * a.K + lq * 8 + sb * 32;
+    const uint16_t* bl = bh + a.x_plane;
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 rw[DEPTH][NT], Bh[DEPTH], Bl[DEPTH];
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+        const int sj = min(u, nn);
+        Bh[u] = make_uint4(0u, 0u, 0u, 0u); Bl[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (row_ok) { Bh[u] = ldg16(bh + sj * 32); Bl[u] = ldg16(bl + sj * 32); }      // rows >= M stay zero
+#pragma unroll
+        for (int t = 0; t < NT; ++t) rw[u][t] = ldg16(reinterpret_cast<const uint16_t*>(wp[t] + loff + sj * 4096));
+    }
+    for (int j = 0; j < n; j += DEPTH) {
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            const bool live = j + u < n;                           // steps past the end meet zero weights
+            const bf16x8 vh = __builtin_bit_cast(bf16x8, Bh[u]), vl = __builtin_bit_cast(bf16x8, Bl[u]);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                uint4 wv = rw[u][t];
+                if (!live) wv = make_uint4(0u, 0u, 0u, 0u);
+                const bf16x8 A = __builtin_bit_cast(bf16x8, wv);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, vh, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, vl, acc[t], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);                     // keep the refill behind its MFMAs: same registers, no copies
+            const int sj = min(j + DEPTH + u, nn);                 // prefetches clamped to the last step
+            if (row_ok) { Bh[u] = ldg16(bh + sj * 32); Bl[u] = ldg16(bl + sj * 32); }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) rw[u][t] = ldg16(reinterpret_cast<const uint16_t*>(wp[t] + loff + sj * 4096));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) *reinterpret_cast<f32x4*>(&red[(wave * NT + t) * 256 + lane * 4]) = acc[t];
+    __syncthreads();
+    if (wave >= NU) return;
+    // lane holds D[column c + e][row li] of unit `wave`
+    f32x4 t1 = {0.f, 0.f, 0.f, 0.f}, t2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        const f32x4 p = *reinterpret_cast<const f32x4*>(&red[(v * NT + wave * PER) * 256 + lane * 4]);
+        t1[0] += p[0]; t1[1] += p[1]; t1[2] += p[2]; t1[3] += p[3];
+        if (EPI == EPI_SWIGLU) {
+            const f32x4 q = *reinterpret_cast<const f32x4*>(&red[(v * NT + wave * PER + 1) * 256 + lane * 4]);
+            t2[0] += q[0]; t2[1] += q[1]; t2[2] += q[2]; t2[3] += q[3];
+        }
+    }
+    if (!row_ok) return;
+    const float rscale = 1.0f / sqrtf(ssq / (float)a.K + a.eps);  // r = rsqrt(mean square + eps) of the lane's input row
+    if (EPI == EPI_SWIGLU) {
+        float h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float g = t1[e] * rscale, u = t2[e] * rscale;
+            h[e] = g / (1.0f + __expf(-g)) * u;
+        }
+        store_planes4(a.out_planes, a.out_plane, (size_t)li * a.N + c, h[0], h[1], h[2], h[3]);
+    } else {
+        const int nq = a.H * a.hd, nkv = a.KVH * a.hd;
+        const int p = p_row, b = li / a.q_len;
+        const float v[4] = {t1[0] * rscale, t1[1] * rscale, t1[2] * rscale, t1[3] * rscale};
+        if (c < nq + nkv) {
+            const int hc = c & hd_mask;
+            const float r0 = v[0] * rc0.x - v[1] * rc0.y, r1 = v[0] * rc0.y + v[1] * rc0.x;
+            const float r2 = v[2] * rc1.x - v[3] * rc1.y, r3 = v[2] * rc1.y + v[3] * rc1.x;
+            if (c < nq) {
+                *reinterpret_cast<float4*>(a.q_out + (size_t)li * nq + c) = make_float4(r0, r1, r2, r3);
+            } else if (p >= 0) {
+                const int kh = (c - nq) >> (__ffs(a.hd) - 1);
+                uint16_t* dst = a.k_cache + (((size_t)b * a.KVH + kh) * a.cache_len + p) * a.hd + hc;
+                *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)from_f<uint16_t>(r0) | ((uint32_t)from_f<uint16_t>(r1) << 16),
+                                                            (uint32_t)from_f<uint16_t>(r2) | ((uint32_t)from_f<uint16_t>(r3) << 16));
+            }
+        } else if (p >= 0) {
+            const int cv = c - nq - nkv;
+            const int vh = cv >> (__ffs(a.hd) - 1), hc = cv & hd_mask;
+            uint16_t* base = a.v_cache + ((size_t)b * a.KVH + vh) * (size_t)a.cache_len * a.hd;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) base[v_index<uint16_t>(p, hc + e, a.hd)] = from_f<uint16_t>(v[e]);
+        }
+    }
+}
+
+// `units` units are dealt to the workgroups in consecutive runs of TU or TU - 1 (host: ceil(units / grid) == TU, grid <= units)
+template <int EPI, int TU>
+__global__ __launch_bounds__(512) void gemm_rows_kernel(DecArgs a, int units) {
+    extern __shared__ __attribute__((aligned(16))) float rows_red[];      // [8 wavefronts][tiles][256]
+    const int G = gridDim.x, b = blockIdx.x;
+    const int base = units / G, rem = units - base * G;
+    const int nu = base + (b < rem ? 1 : 0), u0 = b * base + min(b, rem);
+    if (nu == TU) rows_body<EPI, TU>(a, u0, rows_red);
+    else if (TU > 1 && nu == TU - 1) rows_body<EPI, (TU > 1 ? TU - 1 : 1)>(a, u0, rows_red);
+}
+
 // Split-K factor of the 16-row kernel: the smallest power of two that gives about 450 workgroups (two per
 // compute unit keep enough loads in flight; measured on the 7B shapes, more splits only add partial sums
 // for the consumer kernels to read), with at least 256 columns per split.
@@ -1716,6 +1868,45 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
 #undef BS_DEC
     BS_LAUNCH_CHECK();
     prof_record(e0, e1, (double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0), 50);   // class 50: fused few-row projections
+    return BS_OK;
+}
+
+// The fused projections for up to 16 rows: how many units (16-column tiles of the stacked QKV matrices; gate/up pairs)
+// a workgroup gets at most, 0 when the kernel does not apply.  *grid: workgroups (one per compute unit at most).
+int gemm_rows_units(int epi, int M, int N, int K, int* grid) {
+    if (epi != EPI_QKV && epi != EPI_SWIGLU) return 0;
+    if (M < 1 || M > 16 || K < 32 || K % 32 != 0 || N < 16 || N % 16 != 0) return 0;
+    if ((double)N * K * 2.0 >= 4294967296.0 || (double)M * K * 2.0 >= 4294967296.0) return 0;
+    const int cus = step_grid();
+    if (cus < 8) return 0;
+    const int units = N / 16, G = units < cus ? units : cus;
+    const int tu = (units + G - 1) / G;
+    if (tu > (epi == EPI_SWIGLU ? ROWS_UMAX - 1 : ROWS_UMAX)) return 0;       // 8 KB of LDS per tile and workgroup, 64 KB at most
+    if (grid) *grid = G;
+    return tu;
+}
+
+int launch_gemm_rows(int epi, const DecArgs& a, hipStream_t s) {
+    int G = 0;
+    const int tu = gemm_rows_units(epi, a.M, a.N, a.K, &G);
+    BS_REQUIRE(tu >= 1, BS_ESHAPE, "gemm_rows: M=%d N=%d K=%d", a.M, a.N, a.K);
+    BS_REQUIRE(epi != EPI_QKV || ((a.hd == 64 || a.hd == 128) && a.seg_rows[0] % 16 == 0 && a.seg_rows[1] % 16 == 0 && a.q_len >= 1), BS_ESHAPE,
+               "gemm_rows: head_dim %d", a.hd);
+    BS_REQUIRE(a.ssq_in && a.ssq_tiles >= 1, BS_EINVAL, "gemm_rows: the input rows' sums of squares are missing");
+    const int units = a.N / 16;
+    const dim3 grid(G), block(512);
+    const size_t lds = (size_t)8 * tu * (epi == EPI_SWIGLU ? 2 : 1) * 256 * sizeof(float);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    { const int prc = prof_events(s, &e0, &e1); if (prc != BS_OK) return prc; }
+#define BS_ROWS(E) do { switch (tu) { \
+        case 1: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 1>), grid, block, lds, s, e0, e1, a, units); break; \
+        case 2: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 2>), grid, block, lds, s, e0, e1, a, units); break; \
+        case 3: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 3>), grid, block, lds, s, e0, e1, a, units); break; \
+        default: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 4>), grid, block, lds, s, e0, e1, a, units); break; } } while (0)
+    if (epi == EPI_QKV) BS_ROWS(EPI_QKV); else BS_ROWS(EPI_SWIGLU);
+#undef BS_ROWS
+    BS_LAUNCH_CHECK();
+    prof_record(e0, e1, (double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0), 60);   // class 60: fused projections, up to 16 rows
     return BS_OK;
 }
 

@@ -291,6 +291,16 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
             BS_TRY(launch_gemm_dec(EPI_RESID, a, s));
         }
     } else {
+    // Up to 16 rows of a wide model (verification of one sequence): QKV and gate/up as whole-K projections with the
+    // consumer's work in the epilogue, where a compute unit gets at least two 16-column units and the deal is even enough.
+    bool fuse_qkv = false, fuse_gu = false;
+    if (dt == BS_BF16 && m->packed && M <= 16) {
+        int g = 0;
+        int tu = (hd == 64 || hd == 128) && nq % 16 == 0 && nkv % 16 == 0 ? gemm_rows_units(EPI_QKV, M, nqkv, d, &g) : 0;
+        fuse_qkv = tu >= 2 && (nqkv / 16) * 5 >= g * tu * 4;
+        tu = gemm_rows_units(EPI_SWIGLU, M, ff, d, &g);
+        fuse_gu = tu >= 2 && (ff / 16) * 5 >= g * tu * 4;
+    }
     BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
     for (int l = 0; l < c.n_layers; ++l) {
         const bs_layer_weights& L = m->layers[l];
@@ -307,9 +317,19 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         g.tiled = m->packed ? 1 : 0;
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.wq; g.w[1] = L.wk; g.w[2] = L.wv; g.seg_rows[0] = nq; g.seg_rows[1] = nkv;
         g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
+        if (fuse_qkv) {
+            DecArgs a = {};
+            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)M * d; a.w[0] = L.wq; a.w[1] = L.wk; a.w[2] = L.wv;
+            a.seg_rows[0] = nq; a.seg_rows[1] = nkv; a.M = M; a.N = nqkv; a.K = d;
+            a.ssq_in = w.ssq; a.ssq_tiles = norm_chunks(d); a.eps = c.norm_eps;
+            a.pos = w.pos; a.rope = w.rope; a.q_len = q_len; a.H = H; a.KVH = KVH; a.hd = hd; a.cache_len = crow;
+            a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
+            BS_TRY(launch_gemm_rows(EPI_QKV, a, s));
+        } else {
         BS_TRY(launch_gemm(dt, g, s));
         BS_TRY(launch_rope_kv(dt, w.part_qkv, w.ks_qkv, (size_t)M * nqkv, w.pos, w.rope, M, q_len, H, KVH, hd, crow,
                               w.q, kc, vc, ssq, d, c.norm_eps, s));
+        }
         BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
                                 (size_t)M * nq, w.att, s));
         g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
@@ -322,8 +342,16 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
                                   (size_t)M * d, w.h, s));
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = ff; g.seg_rows[1] = ff;
         g.out = w.part_gu; g.ks_stride = (size_t)M * 2 * ff; g.M = M; g.N = 2 * ff; g.K = d; g.ldo = 2 * ff; g.KS = w.ks_gu;
+        if (fuse_gu) {
+            DecArgs a = {};
+            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)M * d; a.w[0] = L.w_gate; a.w[1] = L.w_up;
+            a.M = M; a.N = ff; a.K = d; a.ssq_in = w.ssq; a.ssq_tiles = norm_chunks(d); a.eps = c.norm_eps;
+            a.out_planes = reinterpret_cast<uint16_t*>(w.act); a.out_plane = (size_t)M * ff;
+            BS_TRY(launch_gemm_rows(EPI_SWIGLU, a, s));
+        } else {
         BS_TRY(launch_gemm(dt, g, s));
         BS_TRY(launch_swiglu(dt, w.part_gu, w.ks_gu, (size_t)M * 2 * ff, M, ff, (size_t)M * ff, w.act, ssq, d, c.norm_eps, s));
+        }
         g.x = w.act; g.x_plane = (size_t)M * ff; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_d; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = ff; g.ldo = d; g.KS = w.ks_d;
         BS_TRY(launch_gemm(dt, g, s));

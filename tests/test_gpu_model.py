@@ -21,6 +21,11 @@ MID_GQA = synth.cfg(3, 512, 8, 64, 1024, 2048, n_kv_heads=2, dtype="bf16")
 WIDE = synth.cfg(2, 1024, 8, 128, 2816, 8192, n_kv_heads=2, dtype="bf16")
 ODD_F32 = synth.cfg(2, 72, 3, 24, 104, 130, dtype="f32")
 ODD_BF16 = synth.cfg(2, 96, 2, 64, 160, 1000, n_kv_heads=1, dtype="bf16")   # row counts that are not multiples of 64
+# narrow but with many projection columns: 432 units of 16 columns for QKV and for gate/up, i.e. two or one per compute
+# unit, which is where verification passes of up to 16 rows take the whole-K projections with fused epilogues
+ROWS = synth.cfg(2, 256, 36, 64, 6912, 512, dtype="bf16")
+ROWS_GQA = synth.cfg(1, 320, 36, 128, 6912, 512, n_kv_heads=9, dtype="bf16")
+ROWS_MANY = synth.cfg(1, 128, 72, 64, 10240, 512, dtype="bf16")             # 864 and 640 units: four / three per compute unit
 
 
 def setup(c, B, max_len, seed, std=None, packed=False):
@@ -56,7 +61,10 @@ def setup(c, B, max_len, seed, std=None, packed=False):
     # grouped queries with 17..32 rows per kv head: two row tiles share every K and V block (head_dim 128 and 64)
     (WIDE, 2, 200, 6, True), (WIDE, 1, 333, 8, False), (MID_GQA, 3, 77, 7, True),
     # the same against a cache long enough for several key splits (partials + merge)
-    (MID_GQA, 1, 1100, 6, True), (WIDE, 1, 1100, 5, True)])
+    (MID_GQA, 1, 1100, 6, True), (WIDE, 1, 1100, 5, True),
+    # 3..16 rows on models with several 16-column units per compute unit: whole-K QKV and gate/up with fused epilogues
+    (ROWS, 1, 70, 9, True), (ROWS, 1, 33, 3, True), (ROWS, 2, 40, 8, True), (ROWS, 1, 10, 16, True), (ROWS_GQA, 1, 70, 9, True),
+    (ROWS_GQA, 3, 20, 5, True), (ROWS_MANY, 1, 40, 7, True), (ROWS_MANY, 2, 300, 2, True)])
 def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packed):
     W, m, kv = setup(c, B, max(320, n_prefix + q_len + 8), seed=3, packed=packed)
     toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=4)
