@@ -21,11 +21,12 @@ struct GemmArgs {
 constexpr int DEC_MAX_ROWS = 2;
 enum { EPI_RESID = 0, EPI_QKV = 1, EPI_SWIGLU = 2 };
 struct DecArgs {
-    const uint16_t* xh; size_t x_plane;       // input planes [M][K] (hi; lo x_plane elements further)
+    const uint16_t* xh; size_t x_plane;       // input planes [M][K] (hi; lo x_plane elements further); gemm_rows: [K/32][16][32], x_plane = 16 K
     const void* w[3]; int seg_rows[2];        // tiled matrices stacked along N (QKV), or gate and up (SWIGLU)
     int M, N, K;                              // N: output columns (per matrix for SWIGLU)
     const float* ssq_in; int ssq_tiles; float eps;     // input rows' partial sums of squares [M][ssq_tiles] (QKV, SWIGLU)
     float* x; const float* gain_next; uint16_t* out_planes; size_t out_plane; float* ssq_out;   // RESID; out_planes also SWIGLU
+    int out_tiled;                            // gemm_rows: output planes in the tiled layout [N/32][16][32] (out_plane = 16 N)
     const int32_t* pos; const float2* rope; int q_len, H, KVH, hd, cache_len;                    // QKV
     float* q_out; uint16_t* k_cache; uint16_t* v_cache;
     const float* att_part; int att_splits;    // RESID with the attention's per-split partials as input instead of planes (uses H, hd)
@@ -85,8 +86,9 @@ int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t p
 // bf16 models: residual completion + planes of gain .* x + per-chunk sums of squares [rows][norm_chunks(d)]; the
 // consumers below apply the rows' RMS scale when given those sums (ssq != nullptr)
 int norm_chunks(int d);
+// tiled: planes in the layout of the whole-K projections for up to 16 rows, [d/32][16][32], plane = 16*d elements
 int launch_resid_sum(float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d, int rows,
-                     size_t plane, void* out, float* ssq, hipStream_t s);
+                     size_t plane, void* out, float* ssq, bool tiled, hipStream_t s);
 int launch_swiglu(int dtype, const float* part, int ks, size_t ks_stride, int M, int ff, size_t plane, void* out,
                   const float* ssq, int d, float eps, hipStream_t s);
 int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const int32_t* pos, const float2* rope, int M,
@@ -94,7 +96,7 @@ int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const
                    const float* ssq, int d, float eps, hipStream_t s);
 // out == nullptr: the splits are left un-merged in `part` (the consumer combines them)
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
-                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,
+                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out, bool out_tiled,
                      hipStream_t s);
 
 }  // namespace bs

@@ -119,6 +119,11 @@ __device__ __forceinline__ void store_planes4(uint16_t* base, size_t plane, size
     *reinterpret_cast<uint2*>(base + plane + idx) = make_uint2((uint32_t)l0 | ((uint32_t)l1 << 16), (uint32_t)l2 | ((uint32_t)l3 << 16));
 }
 
+// Activation planes for the whole-K projections of up to 16 rows (gemm_rows_kernel): [K/32][16 rows][32 columns], so that
+// the B operand of one k step (16 rows x 64 bytes) is one contiguous kilobyte like a weight tile, instead of 16 pieces
+// of 16 different cache lines.  A plane is 16*K elements whatever the row count; rows >= M are neither written nor read.
+__device__ __forceinline__ size_t xt_index(int m, int k) { return (size_t)(k >> 5) * 512 + m * 32 + (k & 31); }
+
 // ---- RMSNorm (+ pending split-K partials of the previous projection) -----------------------------
 // out row r takes input row src = (r / rows_out) * rows_in + (rows_in - rows_out) + r % rows_out
 // (rows_out = rows_in: identity; rows_out < rows_in: the trailing rows of every sequence).
@@ -176,7 +181,7 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(float* __restrict__ x, co
 // every row is spread over several compute units instead of one.
 __global__ __launch_bounds__(256) void resid_sum_kernel(float* __restrict__ x, const float* __restrict__ pend, int pend_ks,
                                                         size_t pend_stride, const float* __restrict__ gain, int d, size_t plane,
-                                                        uint16_t* __restrict__ out, float* __restrict__ ssq) {
+                                                        uint16_t* __restrict__ out, float* __restrict__ ssq, int tiled) {
     __shared__ float red[4];
     const int r = blockIdx.x, chunk = blockIdx.y, nchunks = gridDim.y;
     const int i = chunk * 1024 + threadIdx.x * 4;                 // d % 8 == 0 (host check): whole float4 granules
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(256) void resid_sum_kernel(float* __restrict__ x, c
         }
         ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         const float4 g = *reinterpret_cast<const float4*>(gain + i);
-        store_planes4(out, plane, (size_t)r * d + i, v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w);
+        store_planes4(out, plane, tiled ? xt_index(r, i) : (size_t)r * d + i, v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w);
     }
     ss = wsum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -1009,18 +1014,19 @@ __global__ __launch_bounds__(512) void gemm_dec_kernel(DecArgs a) {
 
 // ---- fused projections for a few more rows of a wide model (verification of one sequence) -----------------
 // Between 3 and 16 rows the activations are too many to stage whole in every 16-column workgroup, and the 16-row
-// kernel above needs a consumer kernel per projection for its split-K partial sums.  Where a projection has
-// several 16-column units per compute unit (QKV and gate/up of the verification target) there is a third way:
-// one workgroup per compute unit owns up to ROWS_UMAX consecutive units over the WHOLE K range, its 8 wavefronts
-// split K, every wavefront streams its k steps of all the units and loads the matching activations straight
-// into the MFMA B operand (rows < M only; each k slice is read by one wavefront, so LDS would buy nothing and
-// the B registers are shared by the units), the accumulators meet in LDS and wavefront v finishes unit v with
-// the consumer's work: RMS scale + RoPE + q out + K/V cache write (EPI_QKV), silu(r g) * (r u) as planes
-// (EPI_SWIGLU, a unit being the gate and the up tile of the same 16 columns).  No partial sums, no consumer
-// kernel.  With ONE unit per workgroup (O, down) the activations are twice the weight bytes in L1 traffic and
-// the 16-row kernel + its consumer is faster, which is why EPI_RESID is not offered here.
+// kernel above needs a consumer kernel per projection for its split-K partial sums.  On a wide model (about as many
+// 16-column units per projection as compute units, or more) there is a third way: one workgroup per compute unit
+// owns up to ROWS_UMAX consecutive units over the WHOLE K range, its 8 wavefronts split K, every wavefront streams
+// its k steps of all the units and loads the matching activations straight into the MFMA B operand (rows < M only;
+// each k slice is read by one wavefront, so LDS would buy nothing, and the B registers are shared by the units),
+// the accumulators meet in LDS and wavefront v finishes unit v with the consumer's work: RMS scale + RoPE + q out +
+// K/V cache write (EPI_QKV), silu(r g) * (r u) as planes (EPI_SWIGLU, a unit being the gate and the up tile of the
+// same 16 columns), residual add + planes of gain_next .* x + the unit's sums of squares (EPI_RESID).  No partial
+// sums, no consumer kernel.  The activation planes are tiled (xt_index): with the rows of a k step in 16 different
+// cache lines a projection with ONE unit per workgroup (O, down), whose activations are as many bytes as its
+// weights, ran a third slower (down projection, 9 rows: 27 against 21 us).
 constexpr int ROWS_UMAX = 4;
-constexpr int rows_depth(int nt) { return nt <= 1 ? 8 : nt == 2 ? 6 : nt == 3 ? 4 : nt == 4 ? 3 : 2; }   // k steps in flight per wavefront
+constexpr int rows_depth(int nt) { return nt <= 4 ? 4 : 2; }   // k steps in flight per wavefront (3 measured a third slower than 2 or 4)
 
 template <int EPI, int NU>
 __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float* __restrict__ red) {
@@ -1032,17 +1038,28 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
     // what the epilogue needs from memory is requested ahead of the operand streams (wavefront v finishes unit v)
     const int c = (u0 + min(wave, NU - 1)) * 16 + 4 * lq;         // the lane's four output columns there
     const int hd_mask = a.hd - 1;
-    float ssq = 0.f;
     float2 rc0 = make_float2(1.f, 0.f), rc1 = make_float2(1.f, 0.f);
+    float4 x_old = make_float4(0.f, 0.f, 0.f, 0.f), g_next = make_float4(0.f, 0.f, 0.f, 0.f);
     int p_row = -1;
     if (wave < NU) {
-        for (int t = 0; t < a.ssq_tiles; ++t) ssq += a.ssq_in[(size_t)m * a.ssq_tiles + t];
         if (EPI == EPI_QKV) {
             p_row = a.pos[m];
             const int hc = c & hd_mask;
             rc0 = a.rope[(size_t)m * (a.hd / 2) + hc / 2];
             rc1 = a.rope[(size_t)m * (a.hd / 2) + hc / 2 + 1];
         }
+        if (EPI == EPI_RESID) {
+            x_old = *reinterpret_cast<const float4*>(a.x + (size_t)m * a.N + c);
+            if (a.gain_next) g_next = *reinterpret_cast<const float4*>(a.gain_next + c);
+        }
+    }
+    // The input rows' sums of squares come in ssq_tiles pieces per row (4 from the residual kernel, K/16 from an
+    // EPI_RESID projection): the lanes (row li, lq) of all wavefronts share the pieces, 8 independent loads each
+    // (256 pieces), added up behind the operand streams and combined through LDS with the accumulators.
+    float sv[8];
+    if (EPI != EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sv[i] = a.ssq_in[(size_t)m * a.ssq_tiles + min(wave * 4 + lq + 32 * i, a.ssq_tiles - 1)];
     }
     const int steps = a.K / 32;
     const int s_begin = (wave * steps) >> 3, s_end = ((wave + 1) * steps) >> 3;
@@ -1062,7 +1079,7 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
         wp[t] = reinterpret_cast<const char*>(mat) + ((size_t)(local >> 6) * 64 * a.K + ((local >> 4) & 3) * 512 + (size_t)sb * 2048) * 2;
     }
     const uint32_t loff = lane * 16;                               // a k step of a tile is one contiguous kilobyte, 16 bytes per lane
-    const uint16_t* bh = a.xh + (size_t)m * a.K + lq * 8 + sb * 32;
+    const uint16_t* bh = a.xh + (size_t)sb * 512 + m * 32 + lq * 8;         // tiled planes (xt_index): a k step is 512 elements
     const uint16_t* bl = bh + a.x_plane;
     f32x4 acc[NT];
 #pragma unroll
@@ -1072,7 +1089,7 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
     for (int u = 0; u < DEPTH; ++u) {
         const int sj = min(u, nn);
         Bh[u] = make_uint4(0u, 0u, 0u, 0u); Bl[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (row_ok) { Bh[u] = ldg16(bh + sj * 32); Bl[u] = ldg16(bl + sj * 32); }      // rows >= M stay zero
+        if (row_ok) { Bh[u] = ldg16(bh + sj * 512); Bl[u] = ldg16(bl + sj * 512); }    // rows >= M stay zero
 #pragma unroll
         for (int t = 0; t < NT; ++t) rw[u][t] = ldg16(reinterpret_cast<const uint16_t*>(wp[t] + loff + sj * 4096));
     }
@@ -1091,7 +1108,7 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
             }
             __builtin_amdgcn_sched_barrier(0);                     // keep the refill behind its MFMAs: same registers, no copies
             const int sj = min(j + DEPTH + u, nn);                 // prefetches clamped to the last step
-            if (row_ok) { Bh[u] = ldg16(bh + sj * 32); Bl[u] = ldg16(bl + sj * 32); }
+            if (row_ok) { Bh[u] = ldg16(bh + sj * 512); Bl[u] = ldg16(bl + sj * 512); }
 #pragma unroll
             for (int t = 0; t < NT; ++t) rw[u][t] = ldg16(reinterpret_cast<const uint16_t*>(wp[t] + loff + sj * 4096));
             __builtin_amdgcn_sched_barrier(0);
@@ -1099,6 +1116,16 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
     }
 #pragma unroll
     for (int t = 0; t < NT; ++t) *reinterpret_cast<f32x4*>(&red[(wave * NT + t) * 256 + lane * 4]) = acc[t];
+    float* ssred = red + 8 * NT * 256;                             // [8 wavefronts][16 rows]
+    if (EPI != EPI_RESID) {
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part += wave * 4 + lq + 32 * i < a.ssq_tiles ? sv[i] : 0.f;
+        for (int t = wave * 4 + lq + 256; t < a.ssq_tiles; t += 32) part += a.ssq_in[(size_t)m * a.ssq_tiles + t];
+        part += __shfl_xor(part, 16, 64);
+        part += __shfl_xor(part, 32, 64);
+        if (lq == 0) ssred[wave * 16 + li] = part;
+    }
     __syncthreads();
     if (wave >= NU) return;
     // lane holds D[column c + e][row li] of unit `wave`
@@ -1112,7 +1139,26 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
             t2[0] += q[0]; t2[1] += q[1]; t2[2] += q[2]; t2[3] += q[3];
         }
     }
+    if (EPI == EPI_RESID) {
+        float ss = 0.f;
+        if (row_ok) {
+            float4 xv = x_old;
+            xv.x += t1[0]; xv.y += t1[1]; xv.z += t1[2]; xv.w += t1[3];
+            *reinterpret_cast<float4*>(a.x + (size_t)li * a.N + c) = xv;
+            ss = xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
+            if (a.gain_next)
+                store_planes4(a.out_planes, a.out_plane, a.out_tiled ? xt_index(li, c) : (size_t)li * a.N + c,
+                              xv.x * g_next.x, xv.y * g_next.y, xv.z * g_next.z, xv.w * g_next.w);
+        }
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (row_ok && lq == 0 && a.ssq_out) a.ssq_out[(size_t)li * (a.N / 16) + (c >> 4)] = ss;
+        return;
+    }
     if (!row_ok) return;
+    float ssq = 0.f;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) ssq += ssred[v * 16 + li];
     const float rscale = 1.0f / sqrtf(ssq / (float)a.K + a.eps);  // r = rsqrt(mean square + eps) of the lane's input row
     if (EPI == EPI_SWIGLU) {
         float h[4];
@@ -1121,7 +1167,7 @@ __device__ __forceinline__ void rows_body(const DecArgs& a, const int u0, float*
             const float g = t1[e] * rscale, u = t2[e] * rscale;
             h[e] = g / (1.0f + __expf(-g)) * u;
         }
-        store_planes4(a.out_planes, a.out_plane, (size_t)li * a.N + c, h[0], h[1], h[2], h[3]);
+        store_planes4(a.out_planes, a.out_plane, a.out_tiled ? xt_index(li, c) : (size_t)li * a.N + c, h[0], h[1], h[2], h[3]);
     } else {
         const int nq = a.H * a.hd, nkv = a.KVH * a.hd;
         const int p = p_row, b = li / a.q_len;
@@ -1784,7 +1830,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
 // 16 splits are requested together and folded into a running (max, sum, o) -- the partials were written by other dies
 // a moment ago, so every dependent round of loads is a trip to memory.
 template <typename T>
-__global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, size_t plane, void* __restrict__ out) {
+__global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, int hd, size_t plane, void* __restrict__ out, int tiled_H) {
     const size_t mh = blockIdx.x;
     const int d = threadIdx.x;
     const size_t pstride = (size_t)hd + 4;       // o[hd], max, sum, 2 pad: rows stay 16-byte aligned
@@ -1813,7 +1859,9 @@ __global__ void attn_merge_kernel(const float* __restrict__ part, int n_splits, 
         }
         mm = gm;
     }
-    Act<T>::store(out, plane, mh * hd + d, l > 0.f ? o / l : 0.f);
+    // tiled_H > 0: planes in the layout of the whole-K projections (xt_index), row = mh / H, column = (mh % H) * hd + d
+    const size_t idx = tiled_H > 0 ? xt_index((int)(mh / tiled_H), (int)(mh % tiled_H) * hd + d) : mh * hd + d;
+    Act<T>::store(out, plane, idx, l > 0.f ? o / l : 0.f);
 }
 
 // ---- launchers -----------------------------------------------------------------------------------
@@ -1874,7 +1922,7 @@ int launch_gemm_dec(int epi, const DecArgs& a, hipStream_t s) {
 // The fused projections for up to 16 rows: how many units (16-column tiles of the stacked QKV matrices; gate/up pairs)
 // a workgroup gets at most, 0 when the kernel does not apply.  *grid: workgroups (one per compute unit at most).
 int gemm_rows_units(int epi, int M, int N, int K, int* grid) {
-    if (epi != EPI_QKV && epi != EPI_SWIGLU) return 0;
+    if (epi != EPI_QKV && epi != EPI_SWIGLU && epi != EPI_RESID) return 0;
     if (M < 1 || M > 16 || K < 32 || K % 32 != 0 || N < 16 || N % 16 != 0) return 0;
     if ((double)N * K * 2.0 >= 4294967296.0 || (double)M * K * 2.0 >= 4294967296.0) return 0;
     const int cus = step_grid();
@@ -1892,10 +1940,11 @@ int launch_gemm_rows(int epi, const DecArgs& a, hipStream_t s) {
     BS_REQUIRE(tu >= 1, BS_ESHAPE, "gemm_rows: M=%d N=%d K=%d", a.M, a.N, a.K);
     BS_REQUIRE(epi != EPI_QKV || ((a.hd == 64 || a.hd == 128) && a.seg_rows[0] % 16 == 0 && a.seg_rows[1] % 16 == 0 && a.q_len >= 1), BS_ESHAPE,
                "gemm_rows: head_dim %d", a.hd);
-    BS_REQUIRE(a.ssq_in && a.ssq_tiles >= 1, BS_EINVAL, "gemm_rows: the input rows' sums of squares are missing");
+    BS_REQUIRE(epi == EPI_RESID || (a.ssq_in && a.ssq_tiles >= 1), BS_EINVAL, "gemm_rows: the input rows' sums of squares are missing");
+    BS_REQUIRE(epi != EPI_RESID || (a.x && (!a.gain_next || a.out_planes)), BS_EINVAL, "gemm_rows: residual or output planes missing");
     const int units = a.N / 16;
     const dim3 grid(G), block(512);
-    const size_t lds = (size_t)8 * tu * (epi == EPI_SWIGLU ? 2 : 1) * 256 * sizeof(float);
+    const size_t lds = ((size_t)8 * tu * (epi == EPI_SWIGLU ? 2 : 1) * 256 + 8 * 16) * sizeof(float);
     hipEvent_t e0 = nullptr, e1 = nullptr;
     { const int prc = prof_events(s, &e0, &e1); if (prc != BS_OK) return prc; }
 #define BS_ROWS(E) do { switch (tu) { \
@@ -1903,7 +1952,7 @@ int launch_gemm_rows(int epi, const DecArgs& a, hipStream_t s) {
         case 2: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 2>), grid, block, lds, s, e0, e1, a, units); break; \
         case 3: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 3>), grid, block, lds, s, e0, e1, a, units); break; \
         default: BS_LAUNCH_TIMED((gemm_rows_kernel<E, 4>), grid, block, lds, s, e0, e1, a, units); break; } } while (0)
-    if (epi == EPI_QKV) BS_ROWS(EPI_QKV); else BS_ROWS(EPI_SWIGLU);
+    if (epi == EPI_QKV) BS_ROWS(EPI_QKV); else if (epi == EPI_SWIGLU) BS_ROWS(EPI_SWIGLU); else BS_ROWS(EPI_RESID);
 #undef BS_ROWS
     BS_LAUNCH_CHECK();
     prof_record(e0, e1, (double)a.N * (double)a.K * 2.0 * (epi == EPI_SWIGLU ? 2.0 : 1.0), 60);   // class 60: fused projections, up to 16 rows
@@ -1934,10 +1983,11 @@ int launch_rmsnorm(int dtype, float* x, const float* pend, int pend_ks, size_t p
 }
 
 int launch_resid_sum(float* x, const float* pend, int pend_ks, size_t pend_stride, const float* gain, int d, int rows,
-                     size_t plane, void* out, float* ssq, hipStream_t s) {
+                     size_t plane, void* out, float* ssq, bool tiled, hipStream_t s) {
     if (rows <= 0) return BS_OK;
+    BS_REQUIRE(!tiled || (rows <= 16 && d % 32 == 0), BS_ESHAPE, "resid_sum: tiled planes hold at most 16 rows (%d) of a multiple of 32 columns (%d)", rows, d);
     hipLaunchKernelGGL(resid_sum_kernel, dim3(rows, norm_chunks(d)), dim3(256), 0, s, x, pend, pend_ks, pend_stride, gain, d, plane,
-                       (uint16_t*)out, ssq);
+                       (uint16_t*)out, ssq, tiled ? 1 : 0);
     BS_LAUNCH_CHECK();
     return BS_OK;
 }
@@ -1972,7 +2022,9 @@ int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const
 
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
                      int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,
-                     hipStream_t s) {
+                     bool out_tiled, hipStream_t s) {
+    BS_REQUIRE(!out_tiled || (dtype == BS_BF16 && out && n_splits > 1 && B * q_len <= 16), BS_ESHAPE,
+               "attention: tiled output planes are written by the merge of several key splits of at most 16 rows");
     const float scale = 1.0f / sqrtf((float)hd);
     const dim3 grid(n_splits, H, B), block(256);
     if (dtype == BS_BF16) {
@@ -2000,12 +2052,12 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
 #undef BS_ATTN
         BS_LAUNCH_CHECK();
         prof_record(e0, e1, 0.0, 100);                     // class 100: the split attention kernel (bytes known to the caller)
-        if (out && !direct) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
+        if (out && !direct) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out, out_tiled ? H : 0);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
                            (const float*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);
         BS_LAUNCH_CHECK();
-        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out);
+        hipLaunchKernelGGL((attn_merge_kernel<float>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out, out_tiled ? H : 0);
     }
     BS_LAUNCH_CHECK();
     return BS_OK;

@@ -162,6 +162,7 @@ struct FwdWs {
 static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* base) {
     FwdWs w;
     const size_t M = (size_t)B * q_len;
+    const size_t Mp = M < 16 ? 16 : M;           // planes in the 16-row tiled layout of the whole-K projections
     const size_t nq = (size_t)c.n_heads * c.head_dim, nkv = (size_t)c.n_kv_heads * c.head_dim;
     w.ks_qkv = gemm_splits(c.dtype, (int)(nq + 2 * nkv), c.d_model, (int)M);
     w.ks_o = gemm_splits(c.dtype, c.d_model, (int)nq, (int)M);
@@ -174,10 +175,10 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.tok = (int32_t*)take(M * 4);
     w.rope = (float2*)take(M * (c.head_dim / 2) * 8);
     w.x = (float*)take(M * c.d_model * 4);
-    w.h = take(M * c.d_model * 4);
+    w.h = take(Mp * c.d_model * 4);
     w.q = (float*)take(M * nq * 4);
-    w.att = take(M * nq * 4);
-    w.act = take(M * c.d_ff * 4);
+    w.att = take(Mp * nq * 4);
+    w.act = take(Mp * c.d_ff * 4);
     w.ssq = (float*)take(M * (c.d_model / 16 + 1) * 4);
     w.xch_bytes = (M <= 2 && step_splits(c, B, max_len) > 0) ? step_exchange_bytes(c, (int)M, step_splits(c, B, max_len), nullptr) : 0;
     w.xch = take(w.xch_bytes);
@@ -271,7 +272,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
             a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
             BS_TRY(launch_gemm_dec(EPI_QKV, a, s));
             BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
-                                    (size_t)M * nq, nullptr, s));          // splits are merged by the O projection
+                                    (size_t)M * nq, nullptr, false, s));   // splits are merged by the O projection
             a = DecArgs{};
             a.att_part = w.part_attn; a.att_splits = splits; a.H = H; a.hd = hd;
             a.xh = reinterpret_cast<const uint16_t*>(w.att); a.x_plane = (size_t)M * nq; a.w[0] = L.wo; a.M = M; a.N = d; a.K = nq;
@@ -291,16 +292,23 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
             BS_TRY(launch_gemm_dec(EPI_RESID, a, s));
         }
     } else {
-    // Up to 16 rows of a wide model (verification of one sequence): QKV and gate/up as whole-K projections with the
-    // consumer's work in the epilogue, where a compute unit gets at least two 16-column units and the deal is even enough.
-    bool fuse_qkv = false, fuse_gu = false;
+    // Up to 16 rows of a wide model (verification of one sequence): whole-K projections with the consumer's work in the
+    // epilogue (gemm_rows_kernel), where the 16-column units of a projection fill at least four fifths of the compute units'
+    // turns: QKV and gate/up from two units per compute unit on; O and down (one unit each on the 7B shape) only between
+    // those two, which produce and consume the layouts they use.  A layer is then 6 kernels instead of 10.
+    bool fuse_qkv = false, fuse_gu = false, fuse_o = false, fuse_d = false;
     if (dt == BS_BF16 && m->packed && M <= 16) {
         int g = 0;
         int tu = (hd == 64 || hd == 128) && nq % 16 == 0 && nkv % 16 == 0 ? gemm_rows_units(EPI_QKV, M, nqkv, d, &g) : 0;
         fuse_qkv = tu >= 2 && (nqkv / 16) * 5 >= g * tu * 4;
         tu = gemm_rows_units(EPI_SWIGLU, M, ff, d, &g);
         fuse_gu = tu >= 2 && (ff / 16) * 5 >= g * tu * 4;
+        tu = gemm_rows_units(EPI_RESID, M, d, nq, &g);
+        const bool wide = tu >= 1 && (d / 16) * 5 >= step_grid() * tu * 4;
+        fuse_o = wide && fuse_gu && splits > 1 && nq % 32 == 0;
+        fuse_d = wide && fuse_gu && fuse_qkv && gemm_rows_units(EPI_RESID, M, d, ff, &g) >= 1;
     }
+    const int ssq_chunks = norm_chunks(d);
     BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
     for (int l = 0; l < c.n_layers; ++l) {
         const bs_layer_weights& L = m->layers[l];
@@ -308,8 +316,10 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         char* vc = kc + kv_layer / 2;
         const bool defer = dt == BS_BF16;        // bf16: RMS scale applied behind the projection (see resid_sum_kernel)
         const float* ssq = defer ? w.ssq : nullptr;
-        if (defer)
-            BS_TRY(launch_resid_sum(w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, M, (size_t)M * d, w.h, w.ssq, s));
+        if (defer && fuse_d && l > 0) {}         // the down projection of the layer before left x, the planes and the sums of squares
+        else if (defer)
+            BS_TRY(launch_resid_sum(w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, M, fuse_qkv ? (size_t)16 * d : (size_t)M * d, w.h, w.ssq,
+                                    fuse_qkv, s));
         else
             BS_TRY(launch_rmsnorm(dt, w.x, pend, w.ks_d, (size_t)M * d, L.attn_norm, d, c.norm_eps, B, q_len, q_len,
                                   (size_t)M * d, w.h, s));
@@ -319,9 +329,9 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         g.out = w.part_qkv; g.ks_stride = (size_t)M * nqkv; g.M = M; g.N = nqkv; g.K = d; g.ldo = nqkv; g.KS = w.ks_qkv;
         if (fuse_qkv) {
             DecArgs a = {};
-            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)M * d; a.w[0] = L.wq; a.w[1] = L.wk; a.w[2] = L.wv;
+            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)16 * d; a.w[0] = L.wq; a.w[1] = L.wk; a.w[2] = L.wv;
             a.seg_rows[0] = nq; a.seg_rows[1] = nkv; a.M = M; a.N = nqkv; a.K = d;
-            a.ssq_in = w.ssq; a.ssq_tiles = norm_chunks(d); a.eps = c.norm_eps;
+            a.ssq_in = w.ssq; a.ssq_tiles = fuse_d && l > 0 ? d / 16 : ssq_chunks; a.eps = c.norm_eps;
             a.pos = w.pos; a.rope = w.rope; a.q_len = q_len; a.H = H; a.KVH = KVH; a.hd = hd; a.cache_len = crow;
             a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
             BS_TRY(launch_gemm_rows(EPI_QKV, a, s));
@@ -331,22 +341,31 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
                               w.q, kc, vc, ssq, d, c.norm_eps, s));
         }
         BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
-                                (size_t)M * nq, w.att, s));
+                                fuse_o ? (size_t)16 * nq : (size_t)M * nq, w.att, fuse_o, s));
         g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_o; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = nq; g.ldo = d; g.KS = w.ks_o;
+        if (fuse_o) {
+            DecArgs a = {};
+            a.xh = reinterpret_cast<const uint16_t*>(w.att); a.x_plane = (size_t)16 * nq; a.w[0] = L.wo; a.M = M; a.N = d; a.K = nq;
+            a.x = w.x; a.gain_next = L.ffn_norm; a.out_planes = reinterpret_cast<uint16_t*>(w.h); a.out_plane = (size_t)16 * d; a.out_tiled = 1;
+            a.ssq_out = w.ssq;
+            BS_TRY(launch_gemm_rows(EPI_RESID, a, s));
+        } else {
         BS_TRY(launch_gemm(dt, g, s));
         if (defer)
-            BS_TRY(launch_resid_sum(w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, M, (size_t)M * d, w.h, w.ssq, s));
+            BS_TRY(launch_resid_sum(w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, M, fuse_gu ? (size_t)16 * d : (size_t)M * d, w.h, w.ssq,
+                                    fuse_gu, s));
         else
             BS_TRY(launch_rmsnorm(dt, w.x, w.part_o, w.ks_o, (size_t)M * d, L.ffn_norm, d, c.norm_eps, B, q_len, q_len,
                                   (size_t)M * d, w.h, s));
+        }
         g.x = w.h; g.x_plane = (size_t)M * d; g.w[0] = L.w_gate; g.w[1] = L.w_up; g.w[2] = nullptr; g.seg_rows[0] = ff; g.seg_rows[1] = ff;
         g.out = w.part_gu; g.ks_stride = (size_t)M * 2 * ff; g.M = M; g.N = 2 * ff; g.K = d; g.ldo = 2 * ff; g.KS = w.ks_gu;
         if (fuse_gu) {
             DecArgs a = {};
-            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)M * d; a.w[0] = L.w_gate; a.w[1] = L.w_up;
-            a.M = M; a.N = ff; a.K = d; a.ssq_in = w.ssq; a.ssq_tiles = norm_chunks(d); a.eps = c.norm_eps;
-            a.out_planes = reinterpret_cast<uint16_t*>(w.act); a.out_plane = (size_t)M * ff;
+            a.xh = reinterpret_cast<const uint16_t*>(w.h); a.x_plane = (size_t)16 * d; a.w[0] = L.w_gate; a.w[1] = L.w_up;
+            a.M = M; a.N = ff; a.K = d; a.ssq_in = w.ssq; a.ssq_tiles = fuse_o ? d / 16 : ssq_chunks; a.eps = c.norm_eps;
+            a.out_planes = reinterpret_cast<uint16_t*>(w.act); a.out_plane = fuse_d ? (size_t)16 * ff : (size_t)M * ff; a.out_tiled = fuse_d ? 1 : 0;
             BS_TRY(launch_gemm_rows(EPI_SWIGLU, a, s));
         } else {
         BS_TRY(launch_gemm(dt, g, s));
@@ -354,8 +373,18 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         }
         g.x = w.act; g.x_plane = (size_t)M * ff; g.w[0] = L.w_down; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_d; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = ff; g.ldo = d; g.KS = w.ks_d;
+        if (fuse_d) {
+            const bool more = l + 1 < c.n_layers;
+            DecArgs a = {};
+            a.xh = reinterpret_cast<const uint16_t*>(w.act); a.x_plane = (size_t)16 * ff; a.w[0] = L.w_down; a.M = M; a.N = d; a.K = ff;
+            a.x = w.x; a.gain_next = more ? m->layers[l + 1].attn_norm : nullptr;
+            a.out_planes = reinterpret_cast<uint16_t*>(w.h); a.out_plane = (size_t)16 * d; a.out_tiled = 1;
+            a.ssq_out = more ? w.ssq : nullptr;
+            BS_TRY(launch_gemm_rows(EPI_RESID, a, s));
+        } else {
         BS_TRY(launch_gemm(dt, g, s));
         pend = w.part_d;
+        }
     }
     }
     if (logit_rows > 0) {

@@ -83,6 +83,35 @@ def test_prefill_then_verify_matches_full_recompute(c, B, n_prefix, q_len, packe
         assert np.max(np.abs(got - ref[n_prefix:n_prefix + q_len])) < tol, np.max(np.abs(got - ref[n_prefix:n_prefix + q_len]))
 
 
+# d_model / 16 units for O and down at least four fifths of the compute units: all four projections of a layer with fused
+# epilogues and tiled activation planes between them (6 kernels per layer); two layers so that the down projection's planes and
+# sums of squares feed a QKV projection.  The second shape has two units per compute unit for O and down, dealt unevenly.
+WIDE_ROWS = synth.cfg(2, 3328, 26, 128, 6912, 512, dtype="bf16")
+WIDE_ROWS2 = synth.cfg(1, 6656, 52, 128, 6912, 512, n_kv_heads=4, dtype="bf16")
+
+
+@pytest.mark.parametrize("c,B,n_prefix,q_len,max_len", [
+    (WIDE_ROWS, 1, 40, 9, 2100), (WIDE_ROWS, 1, 33, 3, 2100), (WIDE_ROWS, 2, 20, 8, 2100), (WIDE_ROWS, 1, 40, 9, 320),
+    (WIDE_ROWS2, 1, 24, 7, 2100)])
+def test_up_to_16_rows_on_a_wide_model(c, B, n_prefix, q_len, max_len):
+    """Verification passes of 3..16 rows where every projection takes the whole-K kernel with its consumer's work in the
+    epilogue; with the short cache the attention has one key split and the O projection keeps the 16-row kernel."""
+    Wd = synth.make_weights_device(c, 41, "cuda", std=0.02 * (4096 / c["d_model"]) ** 0.5)     # a hundred million weights: drawn on the GPU
+    W = {k: v.float().cpu().numpy() for k, v in Wd.items()}
+    m = bs().Model(c, Wd).pack(release_originals=True)
+    kv = bs().KV(m, B, max_len)
+    toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=42)
+    dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
+    bs().prefill(m, kv, dtoks, n_prefix, want_logits=False)
+    kvl = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
+    logits = bs().verify_forward(m, kv, dtoks[:, n_prefix:n_prefix + q_len].contiguous(), kvl)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = forward(c, W, toks[b], storage="bf16")
+        err = np.max(np.abs(logits[b].cpu().numpy() - ref[n_prefix:n_prefix + q_len]))
+        assert err < TOL["bf16"], (b, err)
+
+
 @pytest.mark.parametrize("B,n_prefix,q_len,max_len", [
     (1, 63, 2, 1100),      # three key splits of one 32-key block each: the two new keys fall into different splits
     (1, 64, 2, 1100), (2, 95, 1, 1100), (1, 1000, 2, 1100), (1, 31, 1, 2100), (1, 1, 1, 600), (2, 300, 1, 4200)])
