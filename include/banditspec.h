@@ -309,7 +309,8 @@ int bs_round_debug_views(bs_round* r, const float** dev_target_logits, const flo
  * alone).  bs_profile_collect synchronises on those events and returns, for launches of the asked
  * class, the summed kernel time in ms, the summed algorithmic bytes and the launch count.  Classes:
  * 1, 2, 4, 6, 8, 16 = GEMM launches with up to that many tiles of 16 activation rows (bytes: each weight element
- * once, N*K*2); 50 = the fused few-row projections of draft steps (same bytes); 100 = attention (bytes
+ * once, N*K*2); 50 = the fused few-row projections of draft steps (same bytes); 60 = the whole-K projections with
+ * fused epilogues that verification passes of up to 16 rows take on wide models (same bytes); 100 = attention (bytes
  * reported as 0: the cache lengths live on the device, the caller knows them); 0 = everything.
  * bs_profile_enable(1) starts an empty record; bs_profile_enable(0) stops recording and drops the record with its
  * events, so collect before switching off.  Events cannot be recorded into a stream capture: while the record is on, a
