@@ -57,4 +57,33 @@ __device__ __forceinline__ void split8(const float v[8], uint4& hi, uint4& lo) {
     lo = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
 }
 
+// ---- exchange cells {float value, uint32 flag}: device-scope accesses ------------------------------------------------
+// Data handed from one workgroup to another INSIDE a kernel travels in 8-byte cells that carry their own flag: one
+// store, one load, no fence, and a cell is valid when its flag is the one the reader expects.  The accesses bypass the
+// per-die caches (sc1), an 8-byte cell becomes visible as a whole.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+struct DevBuf { __amdgpu_buffer_rsrc_t r; };
+__device__ __forceinline__ DevBuf dev_buf(const void* base) {
+    DevBuf b;
+    b.r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
+    return b;
+}
+constexpr int AUX_SC1 = 16;
+// two cells at cell index c (even): one 16-byte store; each 8-byte cell becomes visible as a whole
+__device__ __forceinline__ void st_cells2(DevBuf b, int c, float v0, float v1, unsigned flag) {
+    const u32x4 u = {__float_as_uint(v0), flag, __float_as_uint(v1), flag};
+    __builtin_amdgcn_raw_buffer_store_b128(u, b.r, c * 8, 0, AUX_SC1);
+}
+__device__ __forceinline__ void st_cells4(DevBuf b, int c, float v0, float v1, float v2, float v3, unsigned flag) {
+    st_cells2(b, c, v0, v1, flag);
+    st_cells2(b, c + 2, v2, v3, flag);
+}
+__device__ __forceinline__ void st_cell1(DevBuf b, int c, float v, unsigned flag) {
+    const u32x2 u = {__float_as_uint(v), flag};
+    __builtin_amdgcn_raw_buffer_store_b64(u, b.r, c * 8, 0, AUX_SC1);
+}
+__device__ __forceinline__ u32x4 ld_cells2(DevBuf b, int c) { return __builtin_amdgcn_raw_buffer_load_b128(b.r, c * 8, 0, AUX_SC1); }
+__device__ __forceinline__ u32x2 ld_cell1(DevBuf b, int c) { return __builtin_amdgcn_raw_buffer_load_b64(b.r, c * 8, 0, AUX_SC1); }
+
 }  // namespace bs

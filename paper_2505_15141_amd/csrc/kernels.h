@@ -95,8 +95,12 @@ int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const
                    int q_len, int H, int KVH, int hd, int max_len, float* q_out, void* k_cache, void* v_cache,
                    const float* ssq, int d, float eps, hipStream_t s);
 // out == nullptr: the splits are left un-merged in `part` (the consumer combines them)
+// Exchange cells for combining the key splits inside the attention kernel (at most 16 query rows per head group, all
+// workgroups resident together; otherwise a merge kernel runs): zero when the pass starts, one flag per layer.
+struct AttnCells { void* buf; size_t bytes; unsigned flag, spin_limit; int32_t* status; };
+size_t attn_cells_bytes(int rows, int H, int hd, int n_splits);
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
-                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out, bool out_tiled,
+                     int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out, bool out_tiled, const AttnCells* cells,
                      hipStream_t s);
 
 }  // namespace bs

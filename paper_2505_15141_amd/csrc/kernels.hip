@@ -1619,13 +1619,28 @@ __global__ __launch_bounds__(256) void attn_kernel(const float* __restrict__ q, 
 // TB/s of distinct K/V bytes against 5.3 with one tile).  Two tiles take about 320 registers, one wavefront per SIMD;
 // its next block is therefore requested before the current one is multiplied (two register sets, loop unrolled by two;
 // two blocks ahead measured the same).
+// Combining the key splits inside this kernel (mg.cells != null; one row tile, all workgroups resident together: host
+// check): a workgroup hands its partial over in exchange cells instead of `part`, then the workgroup of split s combines,
+// for the rows r = S-1-s, 2S-1-s, ... of its head group (S splits; the last splits hold the fewest keys, often none), the
+// partials of all splits as they arrive (bounded polls) and writes the attention output planes -- the hand-over costs
+// about two microseconds where a merge kernel costs five.
+// The cells are all zero when the pass starts (prep kernel) and every layer hands over under its own flag.
+struct AttnMerge {
+    void* cells;                 // [M][H][n_splits][HD + 4] cells: o[HD], max, sum, 2 pad
+    uint16_t* out; size_t plane; // attention output planes; tiled: in the layout of the whole-K projections (xt_index)
+    int tiled;
+    unsigned flag, spin_limit;
+    int32_t* status;             // bit 16: a poll ran out of patience
+};
+
 template <int HD, int NT>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict__ q, const uint16_t* __restrict__ k_cache,
                                                         const uint16_t* __restrict__ v_cache,
                                                         const int32_t* __restrict__ pos, int q_len, int H, int KVH,
                                                         int cache_len, float scale, float* __restrict__ part, int n_splits,
-                                                        uint16_t* __restrict__ direct_out, size_t plane) {
+                                                        uint16_t* __restrict__ direct_out, size_t plane, AttnMerge mg) {
     constexpr int DS = HD / 32, DT = HD / 16;
+    constexpr int PC = HD + 4;                   // cells of one partial
     __shared__ float wm[4][16], wl[4][16];
     __shared__ float wo[4][16][HD + 1];
     // blockIdx.x = (group of NT row tiles, split of the keys): with many query rows (a prompt chunk) the groups are
@@ -1643,6 +1658,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
             for (int idx = threadIdx.x + rt * 256; idx < R * HD; idx += 256 * n_rt) {
                 const int r = idx / HD, d = idx % HD;
                 Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + r % q_len) * H + kvh * G + r / q_len) * HD + d, 0.f);
+            }
+            return;
+        }
+        if (NT == 1 && mg.cells) {                   // no workgroup of this sequence polls: the rows' owners write zeros
+            for (int rr = n_splits - 1 - split; rr < R; rr += n_splits) {
+                const int m = m_first + rr % q_len, head = kvh * G + rr / q_len;
+                for (int d = threadIdx.x; d < HD; d += 256)
+                    Act<uint16_t>::store(mg.out, mg.plane, mg.tiled ? xt_index(m, head * HD + d) : ((size_t)m * H + head) * HD + d, 0.f);
             }
             return;
         }
@@ -1818,9 +1841,81 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
                     Act<uint16_t>::store(direct_out, plane, ((size_t)(m_first + qq) * H + kvh * G + gg) * HD + d, lv > 0.f ? ov / lv : 0.f);
                     continue;
                 }
+                if (NT == 1 && mg.cells) {           // hand the partial over in cells
+                    const DevBuf bc = dev_buf(mg.cells);
+                    const int c0 = (((m_first + qq) * H + kvh * G + gg) * n_splits + split) * PC;
+                    st_cell1(bc, c0 + d, ov, mg.flag);
+                    if (d == 0) st_cells2(bc, c0 + HD, mm, lv, mg.flag);
+                    continue;
+                }
                 float* dst = part + ((((size_t)(m_first + qq)) * H + kvh * G + gg) * n_splits + split) * pstride;
                 dst[d] = ov;
                 if (d == 0) { dst[HD] = mm; dst[HD + 1] = lv; }
+            }
+        }
+    }
+    if constexpr (NT == 1) {
+        if (!mg.cells) return;
+        // ---- combine the splits of this workgroup's rows: lane = (head-dim element d, share sp0 of the splits) ----
+        constexpr int P = 256 / HD;                  // HD threads per share; sp0 is uniform in a wavefront
+        const DevBuf bc = dev_buf(mg.cells);
+        const int d = threadIdx.x % HD, sp0 = threadIdx.x / HD;
+        for (int rr = n_splits - 1 - split; rr < R; rr += n_splits) {
+            const int m = m_first + rr % q_len, head = kvh * G + rr / q_len;
+            const int base = ((m * H + head) * n_splits) * PC;
+            float mm = -INFINITY, o = 0.f, l = 0.f;
+            for (int s0 = sp0; s0 < n_splits; s0 += 4 * P) {
+                u32x2 co[4];
+                u32x4 cml[4];
+                unsigned spins = 0;
+                while (true) {
+                    asm volatile("" ::: "memory");      // the cells change under our feet: every round reads memory again
+                    bool ok = true;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int sp = min(s0 + u * P, n_splits - 1);       // past the end: the last split again, ignored below
+                        co[u] = ld_cell1(bc, base + sp * PC + d);
+                        cml[u] = ld_cells2(bc, base + sp * PC + HD);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) ok = ok && co[u].y == mg.flag && cml[u].y == mg.flag && cml[u].w == mg.flag;
+                    if (ok) break;
+                    if (++spins > mg.spin_limit) { atomicOr(mg.status, 16); break; }
+                }
+                float gm = mm;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (s0 + u * P < n_splits) gm = fmaxf(gm, __uint_as_float(cml[u].x));
+                if (gm == -INFINITY) continue;
+                const float keep = __expf(mm - gm);     // 0 when nothing was accumulated yet
+                o *= keep; l *= keep;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float mv = __uint_as_float(cml[u].x);
+                    if (s0 + u * P >= n_splits || mv == -INFINITY) continue;
+                    const float f = __expf(mv - gm);
+                    l += __uint_as_float(cml[u].z) * f;
+                    o += __uint_as_float(co[u].x) * f;
+                }
+                mm = gm;
+            }
+            __syncthreads();                         // wo / wm / wl are free again
+            wo[sp0][0][d] = o;
+            if (d == 0) { wm[sp0][0] = mm; wl[sp0][0] = l; }
+            __syncthreads();
+            if (sp0 == 0) {
+                float gm = wm[0][0];
+#pragma unroll
+                for (int p = 1; p < P; ++p) gm = fmaxf(gm, wm[p][0]);
+                float ov = 0.f, lv = 0.f;
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const float f = (wm[p][0] == -INFINITY) ? 0.f : __expf(wm[p][0] - gm);
+                    ov += wo[p][0][d] * f;
+                    lv += wl[p][0] * f;
+                }
+                Act<uint16_t>::store(mg.out, mg.plane, mg.tiled ? xt_index(m, head * HD + d) : ((size_t)m * H + head) * HD + d,
+                                     lv > 0.f ? ov / lv : 0.f);
             }
         }
     }
@@ -1870,9 +1965,9 @@ int launch_prep(const int32_t* q_tokens, int q_stride, const int32_t* kv_len, in
                 int32_t* status, void* clear, size_t clear_bytes, hipStream_t s) {
     const int threads = q_len > 16 ? 1024 : 128;
     const size_t clear16 = clear_bytes / 16;
-    // one clearing block per 32 KiB, at most 64
+    // one clearing block per 32 KiB, at most 512 (a few MB of attention cells: two or three sweeps per lane)
     int extra = (int)((clear_bytes + 32767) / 32768);
-    if (extra > 64) extra = 64;
+    if (extra > 512) extra = 512;
     hipLaunchKernelGGL(prep_kernel, dim3(B + extra), dim3(threads), 0, s, q_tokens, q_stride, kv_len, kv_base, q_len, max_len, V,
                        hd / 2, rope_base, pos, tok, rope, status, B, reinterpret_cast<uint4*>(clear), clear16);
     BS_LAUNCH_CHECK();
@@ -2020,9 +2115,29 @@ int launch_rope_kv(int dtype, const float* part, int ks, size_t ks_stride, const
     return BS_OK;
 }
 
+// bytes of the exchange cells through which the key splits of `rows` query rows are combined inside the attention kernel
+size_t attn_cells_bytes(int rows, int H, int hd, int n_splits) {
+    const double b = (double)rows * H * n_splits * (hd + 4) * 8.0;
+    return b < 2147483648.0 ? (size_t)b : 0;           // 32-bit cell offsets
+}
+
+// workgroups of the one-tile attention kernel that the device holds at the same time
+static size_t attn_resident_workgroups(int hd) {
+    static size_t cached[2] = {0, 0};
+    size_t& c = cached[hd == 128 ? 1 : 0];
+    if (c == 0) {
+        int per_cu = 0;
+        const hipError_t e = hd == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<128, 1>, 256, 0)
+                                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<64, 1>, 256, 0);
+        const int cus = step_grid();
+        c = (e == hipSuccess && per_cu > 0 && cus > 0) ? (size_t)per_cu * cus : 1;      // 1: never enough, the merge kernel runs
+    }
+    return c;
+}
+
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
                      int q_len, int H, int KVH, int hd, int max_len, int n_splits, float* part, size_t plane, void* out,
-                     bool out_tiled, hipStream_t s) {
+                     bool out_tiled, const AttnCells* cells, hipStream_t s) {
     BS_REQUIRE(!out_tiled || (dtype == BS_BF16 && out && n_splits > 1 && B * q_len <= 16), BS_ESHAPE,
                "attention: tiled output planes are written by the merge of several key splits of at most 16 rows");
     const float scale = 1.0f / sqrtf((float)hd);
@@ -2041,10 +2156,17 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         }
         const dim3 mgrid(n_splits * (out ? n_rt : 1), KVH, B);
         uint16_t* direct = (out && n_splits == 1) ? reinterpret_cast<uint16_t*>(out) : nullptr;     // no merge needed
+        // the splits combined inside the kernel: one row tile, exchange cells at hand, every workgroup resident at once
+        AttnMerge mg = {};
+        if (cells && cells->buf && out && !direct && nt == 1 && n_rt == 1 && attn_cells_bytes(B * q_len, H, hd, n_splits) <= cells->bytes &&
+            (size_t)n_splits * KVH * B <= attn_resident_workgroups(hd)) {
+            mg.cells = cells->buf; mg.out = reinterpret_cast<uint16_t*>(out); mg.plane = plane; mg.tiled = out_tiled ? 1 : 0;
+            mg.flag = cells->flag; mg.spin_limit = cells->spin_limit; mg.status = cells->status;
+        }
         hipEvent_t e0 = nullptr, e1 = nullptr;
         { const int prc = prof_events(s, &e0, &e1); if (prc != BS_OK) return prc; }
 #define BS_ATTN(HD, NT) BS_LAUNCH_TIMED((attn_mfma_kernel<HD, NT>), mgrid, block, 0, s, e0, e1, q, (const uint16_t*)k_cache, \
-                                        (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane)
+                                        (const uint16_t*)v_cache, pos, q_len, H, KVH, max_len, scale, part, n_splits, direct, plane, mg)
         if (hd == 128) { if (nt == 2) BS_ATTN(128, 2); else BS_ATTN(128, 1); }
         else if (hd == 64) { if (nt == 2) BS_ATTN(64, 2); else BS_ATTN(64, 1); }
         else
@@ -2052,7 +2174,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
 #undef BS_ATTN
         BS_LAUNCH_CHECK();
         prof_record(e0, e1, 0.0, 100);                     // class 100: the split attention kernel (bytes known to the caller)
-        if (out && !direct) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out, out_tiled ? H : 0);
+        if (out && !direct && !mg.cells) hipLaunchKernelGGL((attn_merge_kernel<uint16_t>), dim3(B * q_len * H), dim3(hd), 0, s, part, n_splits, hd, plane, out, out_tiled ? H : 0);
     } else {
         hipLaunchKernelGGL((attn_kernel<float>), grid, block, 0, s, q, (const float*)k_cache,
                            (const float*)v_cache, pos, q_len, H, KVH, hd, max_len, scale, part);

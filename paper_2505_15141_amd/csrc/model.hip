@@ -153,6 +153,7 @@ static int attn_splits(int B, int H, int max_len) {
 struct FwdWs {
     int32_t* status; int32_t* pos; int32_t* tok; float2* rope; float* x; void* h; float* q; void* att; void* act; float* ssq;
     char* xch; size_t xch_bytes;    // resident step kernel: exchange cells (one or two rows only)
+    char* acells; size_t acells_bytes;   // attention: exchange cells of the key splits (up to 16 rows of a bf16 model)
     float *part_qkv, *part_o, *part_gu, *part_d, *part_attn;
     int ks_qkv, ks_o, ks_gu, ks_d;
     size_t total;
@@ -182,6 +183,8 @@ static FwdWs carve(const bs_model_cfg& c, int B, int q_len, int max_len, char* b
     w.ssq = (float*)take(M * (c.d_model / 16 + 1) * 4);
     w.xch_bytes = (M <= 2 && step_splits(c, B, max_len) > 0) ? step_exchange_bytes(c, (int)M, step_splits(c, B, max_len), nullptr) : 0;
     w.xch = take(w.xch_bytes);
+    w.acells_bytes = (c.dtype == BS_BF16 && M <= 16 && M > 2) ? attn_cells_bytes((int)M, c.n_heads, c.head_dim, attn_splits(B, c.n_heads, max_len)) : 0;
+    w.acells = take(w.acells_bytes);
     w.part_qkv = (float*)take(M * (nq + 2 * nkv) * 4 * w.ks_qkv);
     w.part_o = (float*)take(M * c.d_model * 4 * w.ks_o);
     w.part_gu = (float*)take(M * 2 * c.d_ff * 4 * w.ks_gu);
@@ -232,7 +235,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
     const int st_splits = M <= 2 ? step_splits(c, B, kv->max_len) : 0;
     const bool resident = few_rows && st_splits > 0 && step_fits(c, B, q_len, c.n_layers);
     BS_TRY(launch_prep(q_tokens, q_stride, kv_len, kv_base, B, q_len, kv->max_len, c.vocab, hd, c.rope_base, w.pos, w.tok,
-                       w.rope, w.status, resident ? w.xch : nullptr, resident ? w.xch_bytes : 0, s));
+                       w.rope, w.status, resident ? w.xch : w.acells_bytes ? w.acells : nullptr, resident ? w.xch_bytes : w.acells_bytes, s));
     if (resident) {
         StepArgs a = {};
         for (int l = 0; l < c.n_layers; ++l) {
@@ -272,7 +275,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
             a.q_out = w.q; a.k_cache = reinterpret_cast<uint16_t*>(kc); a.v_cache = reinterpret_cast<uint16_t*>(vc);
             BS_TRY(launch_gemm_dec(EPI_QKV, a, s));
             BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
-                                    (size_t)M * nq, nullptr, false, s));   // splits are merged by the O projection
+                                    (size_t)M * nq, nullptr, false, nullptr, s));   // splits are merged by the O projection
             a = DecArgs{};
             a.att_part = w.part_attn; a.att_splits = splits; a.H = H; a.hd = hd;
             a.xh = reinterpret_cast<const uint16_t*>(w.att); a.x_plane = (size_t)M * nq; a.w[0] = L.wo; a.M = M; a.N = d; a.K = nq;
@@ -309,11 +312,15 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
         fuse_d = wide && fuse_gu && fuse_qkv && gemm_rows_units(EPI_RESID, M, d, ff, &g) >= 1;
     }
     const int ssq_chunks = norm_chunks(d);
+    // the attention's key splits combined inside its kernel (exchange cells, cleared by the prep kernel above)
+    const bool in_kernel_merge = w.acells_bytes > 0 && splits > 1 && c.n_layers < 65536;
+    AttnCells ac = {w.acells, w.acells_bytes, 0u, g_step_polls.load(), w.status};
     BS_TRY(launch_embed(dt, w.tok, m->embed, M, d, w.x, s));
     for (int l = 0; l < c.n_layers; ++l) {
         const bs_layer_weights& L = m->layers[l];
         char* kc = kv->buf + (size_t)l * kv_layer;
         char* vc = kc + kv_layer / 2;
+        ac.flag = (unsigned)l + 1u;
         const bool defer = dt == BS_BF16;        // bf16: RMS scale applied behind the projection (see resid_sum_kernel)
         const float* ssq = defer ? w.ssq : nullptr;
         if (defer && fuse_d && l > 0) {}         // the down projection of the layer before left x, the planes and the sums of squares
@@ -341,7 +348,7 @@ static int forward(const bs_model* m, const bs_kv* kv, const int32_t* q_tokens, 
                               w.q, kc, vc, ssq, d, c.norm_eps, s));
         }
         BS_TRY(launch_attention(dt, w.q, kc, vc, w.pos, B, q_len, H, KVH, hd, crow, splits, w.part_attn,
-                                fuse_o ? (size_t)16 * nq : (size_t)M * nq, w.att, fuse_o, s));
+                                fuse_o ? (size_t)16 * nq : (size_t)M * nq, w.att, fuse_o, in_kernel_merge ? &ac : nullptr, s));
         g.x = w.att; g.x_plane = (size_t)M * nq; g.w[0] = L.wo; g.w[1] = g.w[2] = nullptr; g.seg_rows[0] = d; g.seg_rows[1] = 0;
         g.out = w.part_o; g.ks_stride = (size_t)M * d; g.M = M; g.N = d; g.K = nq; g.ldo = d; g.KS = w.ks_o;
         if (fuse_o) {

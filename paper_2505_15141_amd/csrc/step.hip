@@ -34,27 +34,6 @@
 
 namespace bs {
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-// ---- exchange buffers: cells {float value, uint32 flag}, device-scope accesses ------------------------------------
-struct DevBuf { __amdgpu_buffer_rsrc_t r; };
-__device__ __forceinline__ DevBuf dev_buf(const void* base) {
-    DevBuf b;
-    b.r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7FFFFFFF, 0x00020000);
-    return b;
-}
-constexpr int AUX_SC1 = 16;
-// two cells at cell index c (even): one 16-byte store; each 8-byte cell becomes visible as a whole
-__device__ __forceinline__ void st_cells2(DevBuf b, int c, float v0, float v1, unsigned flag) {
-    const u32x4 u = {__float_as_uint(v0), flag, __float_as_uint(v1), flag};
-    __builtin_amdgcn_raw_buffer_store_b128(u, b.r, c * 8, 0, AUX_SC1);
-}
-__device__ __forceinline__ void st_cells4(DevBuf b, int c, float v0, float v1, float v2, float v3, unsigned flag) {
-    st_cells2(b, c, v0, v1, flag);
-    st_cells2(b, c + 2, v2, v3, flag);
-}
-__device__ __forceinline__ u32x4 ld_cells2(DevBuf b, int c) { return __builtin_amdgcn_raw_buffer_load_b128(b.r, c * 8, 0, AUX_SC1); }
-
 constexpr int STEP_WAVES = 8, STEP_THREADS = 64 * STEP_WAVES;
 constexpr int STEP_MAXS = 16;            // k steps of 32 columns one wavefront may own in a phase (K <= 4096)
 constexpr int STEP_XR = 4;               // groups of four staged input values per lane (2 rows x 4096 columns / 4 / 512 lanes)

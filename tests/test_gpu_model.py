@@ -92,7 +92,11 @@ WIDE_ROWS2 = synth.cfg(1, 6656, 52, 128, 6912, 512, n_kv_heads=4, dtype="bf16")
 
 @pytest.mark.parametrize("c,B,n_prefix,q_len,max_len", [
     (WIDE_ROWS, 1, 40, 9, 2100), (WIDE_ROWS, 1, 33, 3, 2100), (WIDE_ROWS, 2, 20, 8, 2100), (WIDE_ROWS, 1, 40, 9, 320),
-    (WIDE_ROWS2, 1, 24, 7, 2100)])
+    (WIDE_ROWS2, 1, 24, 7, 2100),
+    # up to 16 rows per head group against a cache long enough for several key splits: the splits are combined inside the
+    # attention kernel (head_dim 64 and 128, one and several query heads per kv head, more splits than rows and fewer)
+    (MID, 1, 200, 9, 2100), (MID, 2, 150, 5, 2100), (MID_GQA, 2, 130, 3, 4200), (WIDE, 1, 100, 4, 1100), (MID, 1, 900, 16, 1100),
+    (MID, 3, 40, 4, 8300)])
 def test_up_to_16_rows_on_a_wide_model(c, B, n_prefix, q_len, max_len):
     """Verification passes of 3..16 rows where every projection takes the whole-K kernel with its consumer's work in the
     epilogue; with the short cache the attention has one key split and the O projection keeps the 16-row kernel."""
@@ -301,6 +305,43 @@ def test_resident_step_gives_up_after_its_poll_limit_and_recovers():
     assert int(ws[:4].view(torch.int32).cpu()[0]) & 16 == 0
     ref = forward(c, W, toks[0], storage="bf16")
     assert np.max(np.abs(lg[0].cpu().numpy() - ref[n_prefix:n_prefix + 2])) < TOL["bf16"]
+
+
+def test_key_splits_combined_in_the_attention_kernel_with_a_sequence_left_out_and_with_no_patience():
+    """Three sequences of five rows against a long cache (several key splits, combined inside the attention kernel through
+    exchange cells): sequence 1 has no room and is left out, its workgroups hand nothing over and nobody waits for them;
+    the others' logits are right, bit 0 of the status word is set, bit 16 is not.  With a poll limit of one a pass gives up
+    (the workgroups of the last splits hold no keys and poll while the others still walk theirs: bit 16, no hang), and the next pass
+    with the default limit is right again."""
+    b = bs()
+    c = MID
+    max_len, n_prefix, q_len = 8300, 600, 5
+    W, m, kv = setup(c, 3, max_len, seed=27, packed=True)
+    toks = synth.make_prompts(3, n_prefix + q_len, c["vocab"], 28)
+    dt = torch.from_numpy(toks.astype(np.int32)).cuda()
+    b.prefill(m, kv, dt, n_prefix)
+    ws = torch.zeros(m.forward_workspace_bytes(3, q_len, max_len), dtype=torch.uint8, device="cuda")
+    kvl = torch.tensor([n_prefix, max_len - 2, n_prefix], dtype=torch.int32, device="cuda")
+    q = dt[:, n_prefix:n_prefix + q_len].contiguous()
+
+    def check(expect_bit16):
+        lg = b.verify_forward(m, kv, q, kvl, workspace=ws)
+        torch.cuda.synchronize()
+        status = int(ws[:4].view(torch.int32).cpu()[0])
+        assert status & 1 and bool(status & 16) == expect_bit16, status
+        if not expect_bit16:
+            for i in (0, 2):
+                ref = forward(c, W, toks[i], storage="bf16")
+                assert np.max(np.abs(lg[i].cpu().numpy() - ref[n_prefix:n_prefix + q_len])) < TOL["bf16"], i
+
+    check(False)
+    b.step_poll_limit(1)
+    try:
+        check(True)
+    finally:
+        b.step_poll_limit(0)
+    ws.zero_()
+    check(False)
 
 
 def test_resident_step_with_a_sequence_left_out():
