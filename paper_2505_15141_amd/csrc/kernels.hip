@@ -1858,39 +1858,40 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float* __restrict_
         if (!mg.cells) return;
         // ---- combine the splits of this workgroup's rows: lane = (head-dim element d, share sp0 of the splits) ----
         constexpr int P = 256 / HD;                  // HD threads per share; sp0 is uniform in a wavefront
+        constexpr int MU = 8;                        // splits a lane polls in one round (all loads in flight together)
         const DevBuf bc = dev_buf(mg.cells);
         const int d = threadIdx.x % HD, sp0 = threadIdx.x / HD;
         for (int rr = n_splits - 1 - split; rr < R; rr += n_splits) {
             const int m = m_first + rr % q_len, head = kvh * G + rr / q_len;
             const int base = ((m * H + head) * n_splits) * PC;
             float mm = -INFINITY, o = 0.f, l = 0.f;
-            for (int s0 = sp0; s0 < n_splits; s0 += 4 * P) {
-                u32x2 co[4];
-                u32x4 cml[4];
+            for (int s0 = sp0; s0 < n_splits; s0 += MU * P) {
+                u32x2 co[MU];
+                u32x4 cml[MU];
                 unsigned spins = 0;
                 while (true) {
                     asm volatile("" ::: "memory");      // the cells change under our feet: every round reads memory again
                     bool ok = true;
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
+                    for (int u = 0; u < MU; ++u) {
                         const int sp = min(s0 + u * P, n_splits - 1);       // past the end: the last split again, ignored below
                         co[u] = ld_cell1(bc, base + sp * PC + d);
                         cml[u] = ld_cells2(bc, base + sp * PC + HD);
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) ok = ok && co[u].y == mg.flag && cml[u].y == mg.flag && cml[u].w == mg.flag;
+                    for (int u = 0; u < MU; ++u) ok = ok && co[u].y == mg.flag && cml[u].y == mg.flag && cml[u].w == mg.flag;
                     if (ok) break;
                     if (++spins > mg.spin_limit) { atomicOr(mg.status, 16); break; }
                 }
                 float gm = mm;
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < MU; ++u)
                     if (s0 + u * P < n_splits) gm = fmaxf(gm, __uint_as_float(cml[u].x));
                 if (gm == -INFINITY) continue;
                 const float keep = __expf(mm - gm);     // 0 when nothing was accumulated yet
                 o *= keep; l *= keep;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < MU; ++u) {
                     const float mv = __uint_as_float(cml[u].x);
                     if (s0 + u * P >= n_splits || mv == -INFINITY) continue;
                     const float f = __expf(mv - gm);
