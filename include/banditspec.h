@@ -202,12 +202,15 @@ size_t bs_forward_workspace_bytes(const bs_model_cfg* cfg, int B, int max_q_len,
  * The same call serves the draft model's steps (q_len = 1 or 2, logit_rows = 1).  One or two rows in all (B * q_len <= 2)
  * of a small packed bf16 model with head_dim 64 run as ONE resident kernel of one workgroup per compute unit whose
  * workgroups wait for each other's outputs; it needs the GPU's compute units to itself while it runs (work of the same
- * stream or graph is ordered behind it anyway).  Every wait is bounded: see bs_step_poll_limit.
+ * stream or graph is ordered behind it anyway).  Passes of up to 16 rows per head group against a cache long enough for
+ * several key splits combine the splits inside the attention kernel the same way (exchange cells in the workspace; all its
+ * workgroups resident together, or a merge kernel runs instead).  Every wait is bounded: see bs_step_poll_limit.
  * ---------------------------------------------------------------------------------------------- */
 int bs_verify_forward(const bs_model* m, const bs_kv* kv, const int32_t* dev_q_tokens,
                       const int32_t* dev_kv_len, int q_len, int logit_rows, float* dev_logits,
                       void* dev_workspace, size_t workspace_bytes, void* stream);
-/* The bound of the resident kernel's waits, in polls of one cell (default 2^18, about a quarter of a second; 0 restores
+/* The bound of the waits inside kernels (the resident kernel's; the attention kernel's when it combines its key splits),
+ * in polls of one cell (default 2^18, about a quarter of a second; 0 restores
  * the default).  A pass that runs out of polls ends without a result -- its logits and the cache rows it was to write are
  * not valid -- and sets bit 16 of the device status word; no launch ever waits without end.  Applies to passes enqueued
  * after the call.  Meant for tests of that path. */
@@ -292,7 +295,7 @@ int bs_spec_round(bs_round* r, int arm, int32_t* dev_emitted, int32_t* dev_n_emi
  *   2  a token id outside [0, vocab) was replaced by 0
  *   4  total_len < 2 or > max_len at the start of a round (sequence left out)
  *   8  a sequence still generating had total_len + gamma > max_len (left out, see dev_goal_len above)
- *  16  a resident draft step ran out of polls (bs_step_poll_limit): that round's tokens are not valid
+ *  16  a wait inside a kernel ran out of polls (bs_step_poll_limit): that round's tokens are not valid
  * Copies the word to *host_out (HOST memory) and WAITS for `stream`: this call synchronises.  Not for use while the
  * stream is being captured. */
 int bs_round_status(bs_round* r, int32_t* host_out, void* stream);
