@@ -307,6 +307,35 @@ def test_resident_step_gives_up_after_its_poll_limit_and_recovers():
     assert np.max(np.abs(lg[0].cpu().numpy() - ref[n_prefix:n_prefix + 2])) < TOL["bf16"]
 
 
+def test_fused_and_unfused_schedules_agree_closely():
+    """The same wide model packed (five kernels per layer: whole-K projections with fused epilogues, key splits combined in the
+    attention kernel) and unpacked (16-row GEMM with split-K, consumer kernels, merge kernel): the two schedules share no
+    projection kernel and differ only in the order of fp32 additions, so their logits agree far more closely than either has to
+    agree with the fp64 oracle -- a wrong rotation angle, sum-of-squares piece or residual column in one of them shows here."""
+    c, B, n_prefix, q_len, max_len = WIDE_ROWS, 2, 30, 7, 2100
+    Wd = synth.make_weights_device(c, 51, "cuda", std=0.02 * (4096 / c["d_model"]) ** 0.5)
+    toks = synth.make_prompts(B, n_prefix + q_len, c["vocab"], seed=52)
+    dtoks = torch.from_numpy(toks.astype(np.int32)).cuda()
+    outs = []
+    for packed in (False, True):
+        m = bs().Model(c, dict(Wd))
+        if packed:
+            m.pack(release_originals=False)
+        kv = bs().KV(m, B, max_len)
+        bs().prefill(m, kv, dtoks, n_prefix, want_logits=False)
+        kvl = torch.full((B,), n_prefix, dtype=torch.int32, device="cuda")
+        first = bs().verify_forward(m, kv, dtoks[:, n_prefix:n_prefix + 3].contiguous(), kvl).cpu().numpy()
+        kvl += 3                                       # the second pass reads the cache rows the first one's epilogue wrote
+        second = bs().verify_forward(m, kv, dtoks[:, n_prefix + 3:n_prefix + q_len].contiguous(), kvl).cpu().numpy()
+        torch.cuda.synchronize()
+        outs.append((first, second))
+    for a, b_ in zip(outs[0], outs[1]):
+        scale = float(np.max(np.abs(a)))
+        assert scale > 0.1
+        # measured: 1.6e-4 .. 2.8e-4 on logits of magnitude 5..6 (a k or v that rounds to the neighbouring bf16 value in the cache)
+        assert np.max(np.abs(a - b_)) < 5e-4 * max(scale, 1.0), (np.max(np.abs(a - b_)), scale)
+
+
 def test_key_splits_combined_in_the_attention_kernel_with_a_sequence_left_out_and_with_no_patience():
     """Three sequences of five rows against a long cache (several key splits, combined inside the attention kernel through
     exchange cells): sequence 1 has no room and is left out, its workgroups hand nothing over and nobody waits for them;
