@@ -246,8 +246,8 @@ __global__ void swiglu_kernel(const float* __restrict__ part, int ks, size_t ks_
 // slice [M, KC] of both planes is staged once per workgroup in LDS (rows padded by 16 bytes so that the
 // 16 rows read by one ds_read_b128 phase fall into distinct banks) and shared by the four wavefronts.
 // Each wavefront owns its output rows, so no cross-wavefront reduction is needed; split-K partials are
-// summed by the consumer kernel.  Three kernels by row count: gemm_bf16_m16_kernel (up to 16 rows, the
-// verification pass of one sequence: pure weight streaming), this one with two row tiles (17..32 rows, and the
+// summed by the consumer kernel.  Three kernels by row count: gemm_bf16_m16_kernel (up to 16 rows: pure weight
+// streaming; the layers of a wide model take gemm_rows_kernel instead), this one with two row tiles (17..32 rows, and the
 // fallback when K is not a multiple of 32), gemm_bf16_big_kernel from 33 rows on (measured faster from there).
 
 // Weight layouts.  Row-major [N][K], or TILED: the matrix is cut into 64-row x 32-column blocks stored
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(64 * BIG_WAVES) void gemm_bf16_big_kernel(GemmArgs 
     }
 }
 
-// ---- GEMM for at most 16 activation rows (verification of one sequence, draft steps) -----------------
+// ---- GEMM for at most 16 activation rows (LM heads; the layers of models too narrow for gemm_rows_kernel) ----
 // Same operand mapping as above, but the whole K range of the workgroup (at most M16_KMAX columns) is
 // staged in LDS once, behind the first weight loads, and the loop over 32-wide k slices then runs without
 // barriers: each wavefront keeps a ring of M16_DEPTH weight loads (16 rows x 64 bytes each) in flight and
