@@ -204,8 +204,9 @@ size_t bs_forward_workspace_bytes(const bs_model_cfg* cfg, int B, int max_q_len,
  * workgroups wait for each other's outputs; it needs the GPU's compute units to itself while it runs (work of the same
  * stream or graph is ordered behind it anyway).  Passes of up to 16 rows per head group against a cache long enough for
  * several key splits combine the splits inside the attention kernel the same way (exchange cells in the workspace; only
- * when two such launches fit on the device side by side, else a merge kernel runs instead; more passes than that running
- * concurrently on other streams can make a wait run into its bound).  Every wait is bounded: see bs_step_poll_limit.
+ * when all workgroups of the launch fit on the device together, else a merge kernel runs instead; like the resident kernel
+ * it counts on having the compute units to itself: other work running concurrently on other streams can make a wait run
+ * into its bound).  Every wait is bounded: see bs_step_poll_limit.
  * ---------------------------------------------------------------------------------------------- */
 int bs_verify_forward(const bs_model* m, const bs_kv* kv, const int32_t* dev_q_tokens,
                       const int32_t* dev_kv_len, int q_len, int logit_rows, float* dev_logits,

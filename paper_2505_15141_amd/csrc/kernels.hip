@@ -2160,7 +2160,7 @@ int launch_attention(int dtype, const float* q, const void* k_cache, const void*
         // the splits combined inside the kernel: one row tile, exchange cells at hand, every workgroup resident at once
         AttnMerge mg = {};
         if (cells && cells->buf && out && !direct && nt == 1 && n_rt == 1 && attn_cells_bytes(B * q_len, H, hd, n_splits) <= cells->bytes &&
-            (size_t)2 * n_splits * KVH * B <= attn_resident_workgroups(hd)) {    // room for two such launches side by side
+            (size_t)n_splits * KVH * B <= attn_resident_workgroups(hd)) {
             mg.cells = cells->buf; mg.out = reinterpret_cast<uint16_t*>(out); mg.plane = plane; mg.tiled = out_tiled ? 1 : 0;
             mg.flag = cells->flag; mg.spin_limit = cells->spin_limit; mg.status = cells->status;
         }
