@@ -2038,6 +2038,9 @@ int launch_gemm_rows(int epi, const DecArgs& a, hipStream_t s) {
                "gemm_rows: head_dim %d", a.hd);
     BS_REQUIRE(epi == EPI_RESID || (a.ssq_in && a.ssq_tiles >= 1), BS_EINVAL, "gemm_rows: the input rows' sums of squares are missing");
     BS_REQUIRE(epi != EPI_RESID || (a.x && (!a.gain_next || a.out_planes)), BS_EINVAL, "gemm_rows: residual or output planes missing");
+    BS_REQUIRE(epi != EPI_SWIGLU || (a.out_planes && a.w[0] && a.w[1]), BS_EINVAL, "gemm_rows: gate/up matrices or output planes missing");
+    BS_REQUIRE(epi != EPI_QKV || (a.q_out && a.k_cache && a.v_cache && a.pos && a.rope), BS_EINVAL, "gemm_rows: QKV outputs or positions missing");
+    BS_REQUIRE(a.xh && a.w[0], BS_EINVAL, "gemm_rows: input planes or weights missing");
     const int units = a.N / 16;
     const dim3 grid(G), block(512);
     const size_t lds = ((size_t)8 * tu * (epi == EPI_SWIGLU ? 2 : 1) * 256 + 8 * 16) * sizeof(float);
@@ -2124,16 +2127,15 @@ size_t attn_cells_bytes(int rows, int H, int hd, int n_splits) {
 
 // workgroups of the one-tile attention kernel that the device holds at the same time
 static size_t attn_resident_workgroups(int hd) {
-    static size_t cached[2] = {0, 0};
-    size_t& c = cached[hd == 128 ? 1 : 0];
-    if (c == 0) {
+    auto ask = [](bool wide) -> size_t {
         int per_cu = 0;
-        const hipError_t e = hd == 128 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<128, 1>, 256, 0)
-                                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<64, 1>, 256, 0);
+        const hipError_t e = wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<128, 1>, 256, 0)
+                                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<64, 1>, 256, 0);
         const int cus = step_grid();
-        c = (e == hipSuccess && per_cu > 0 && cus > 0) ? (size_t)per_cu * cus : 1;      // 1: never enough, the merge kernel runs
-    }
-    return c;
+        return (e == hipSuccess && per_cu > 0 && cus > 0) ? (size_t)per_cu * cus : 1;   // 1: never enough, the merge kernel runs
+    };
+    static const size_t c128 = ask(true), c64 = ask(false);      // asked once (initialisation of a local static is thread-safe)
+    return hd == 128 ? c128 : c64;
 }
 
 int launch_attention(int dtype, const float* q, const void* k_cache, const void* v_cache, const int32_t* pos, int B,
